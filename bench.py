@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the A3GNN mini-batch hot path on one MI355X.
+
+A step is one pass of the whole path over one mini-batch of synthetic input that is already
+resident in HBM: a3_sample_blocks (frontier degrees, keyed selection, dedup/relabel into block
+CSRs, every hop) followed by a3_gather_features for the input nodes.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload social|copurchase|citation|tiny]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=40)
+    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--workload", default="social")
+    p.add_argument("--bias-rate", type=float, default=None, help="gamma (default: the workload's first)")
+    p.add_argument("--cache-frac", type=float, default=None)
+    p.add_argument("--batch", type=int, default=None)
+    p.add_argument("--cpu-seconds", type=float, default=20.0,
+                   help="budget of the oracle (CPU baseline) leg; 0 disables it")
+    p.add_argument("--traffic-bytes", type=float, default=None,
+                   help="measured HBM bytes per gather launch (from rocprofv3 --pmc), if known")
+    return p.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2511_07421_amd as a3
+    from workloads import get_config, make_graph, make_features, degree_ranked_cache, seed_batch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    if not os.path.exists(a3.library_path()):
+        print("bench.py: HIP library not built (run __graft_entry__.build())", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda", 0)
+    w = get_config(args.workload)
+    gamma = args.bias_rate if args.bias_rate is not None else w.bias_rates[-1]
+    cache_frac = args.cache_frac if args.cache_frac is not None else w.cache_frac
+    batch = args.batch or w.batch
+    K, W = args.steps, args.warmup
+
+    t_gen = time.time()
+    g = make_graph(w.num_nodes, w.mean_degree, w.d_min, w.d_max, w.a, w.symmetric, w.graph_seed,
+                   w.idx_dtype, device=dev)
+    full = make_features(w.num_nodes, w.feat_dim, w.feat_dtype, device=dev)
+    split = degree_ranked_cache(g, full, cache_frac, pin_host=True)
+    del full
+    d_cm = split.cache_map
+    idx_np = np.int32 if w.idx_dtype == torch.int32 else np.int64
+    seeds = [torch.from_numpy(seed_batch(w.num_nodes, batch, 0, b, dtype=idx_np)).to(dev)
+             for b in range(K + W)]
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+    stats = g.stats()
+    ib = stats["idx_bytes"]
+    row_bytes = w.row_bytes
+
+    ctx = a3.Context(batch, w.fanouts)
+    bias_q16 = int(round(gamma * 65536))
+    # output rows: at most every node, at most seeds x prod(1 + fanout)
+    cap_rows = batch
+    for f in w.fanouts:
+        cap_rows = cap_rows * (1 + f)
+    cap_rows = min(cap_rows, w.num_nodes)
+    out = torch.empty((cap_rows, w.feat_dim), dtype=w.feat_dtype, device=dev)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    n_edges = n_in = n_cached_in = 0
+    marks = []
+
+    def step(b, timed):
+        nonlocal n_edges, n_in, n_cached_in
+        e0, e1, e2 = (ev(), ev(), ev()) if timed else (None, None, None)
+        if timed:
+            e0.record()
+        blocks = ctx.sample_blocks(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b)
+        if timed:
+            e1.record()
+        rows = blocks.n_src[-1]
+        ctx.gather_features(split.feat_dev, split.feat_host, d_cm, blocks.input_nodes, out=out[:rows])
+        if timed:
+            e2.record()
+            marks.append((e0, e1, e2, rows, sum(blocks.n_edges), blocks.input_nodes))
+            n_edges += sum(blocks.n_edges)
+            n_in += rows
+        return blocks
+
+    for b in range(W):
+        step(b, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for b in range(W, W + K):
+        step(b, True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    total_s = t1 - t0
+    ms_sample = sum(m[0].elapsed_time(m[1]) for m in marks)
+    ms_gather = sum(m[1].elapsed_time(m[2]) for m in marks)
+    # hit rate of the last timed batch (outside the timed region)
+    last_ids = marks[-1][5].long()
+    hit_rate = float((d_cm[last_ids] >= 0).float().mean().item()) if last_ids.numel() else 1.0
+    cached_rows = n_in * hit_rate  # rows served from HBM (exact when the cache holds everything)
+
+    gather_payload_gbps = n_in * row_bytes / (ms_gather * 1e-3) / 1e9
+    algo_bytes_per_launch = (n_in / K) * (2 * row_bytes + ib + 4)
+    gather_avg_s = ms_gather * 1e-3 / K
+    achieved = algo_bytes_per_launch / gather_avg_s / 1e9
+    result = {
+        "metric": "sampled edges/s + feature-gather GB/s (% of HBM peak) per mini-batch, 1 GPU",
+        "value": n_edges / total_s,
+        "unit": "sampled edges/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": total_s * 1e3 / K,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32/int64 indices + byte copies of %s rows" % str(w.feat_dtype).replace("torch.", ""),
+        "data": "synthetic",
+        "config": {"workload": w.name, "num_nodes": stats["num_nodes"], "nnz": stats["nnz"],
+                   "mean_degree": round(stats["mean_degree"], 2), "max_degree": stats["max_degree"],
+                   "idx_bytes": ib, "row_bytes": row_bytes, "batch": batch, "fanouts": w.fanouts,
+                   "bias_rate": gamma, "cache_frac": cache_frac,
+                   "generate_seconds": round(t_gen, 2)},
+        "gather_GBps": gather_payload_gbps,
+        "gather_frac_of_hbm_peak": achieved / HBM_PEAK_GBPS,
+        "sample_edges_per_s": n_edges / (ms_sample * 1e-3),
+        "ms_sample": ms_sample / K,
+        "ms_gather": ms_gather / K,
+        "edges_per_step": n_edges / K,
+        "input_rows_per_step": n_in / K,
+        "cache_hit_rate": hit_rate,
+        "roofline": {"kernel": "k_gather", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": args.traffic_bytes,
+                     "algorithmic_bytes_per_launch": algo_bytes_per_launch,
+                     "avg_launch_seconds": gather_avg_s},
+    }
+
+    if args.cpu_seconds > 0:
+        import oracle
+        ip_h, ix_h = g.indptr.cpu().numpy(), g.indices.cpu().numpy()
+        cm_h = d_cm.cpu().numpy()
+        fd_h = None if split.feat_dev is None else split.feat_dev.cpu().numpy()
+        fh_h = None if split.feat_host is None else split.feat_host.numpy()
+        spent, done, o_edges, o_rows, o_sample, o_gather = 0.0, 0, 0, 0, 0.0, 0.0
+        while spent < args.cpu_seconds and done < K:
+            s_h = seeds[W + done].cpu().numpy()
+            c0 = time.perf_counter()
+            ob = oracle.sample_blocks(ip_h, ix_h, s_h, w.fanouts, cm_h, bias_q16, W + done)
+            c1 = time.perf_counter()
+            oracle.gather_features(fd_h, fh_h, cm_h, ob.input_nodes.astype(idx_np))
+            c2 = time.perf_counter()
+            o_edges += sum(ob.n_edges)
+            o_rows += ob.n_src[-1]
+            o_sample += c1 - c0
+            o_gather += c2 - c1
+            spent += c2 - c0
+            done += 1
+        result["cpu_baseline"] = {
+            "value": o_edges / spent, "unit": "sampled edges/s", "cores": 1, "kind": "oracle",
+            "sample": "%d of the timed mini-batches of workload %s (same seeds, same rng_seed), "
+                      "%.1f s of CPU work" % (done, w.name, spent),
+            "gather_GBps": o_rows * row_bytes / max(o_gather, 1e-9) / 1e9,
+            "ms_sample": o_sample * 1e3 / done, "ms_gather": o_gather * 1e3 / done,
+        }
+    ctx.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

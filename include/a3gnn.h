@@ -1,0 +1,131 @@
+/*
+ * a3gnn: the mini-batch hot path of A3GNN ("Towards Affordable, Adaptive and
+ * Automatic GNN Training on CPU-GPU Heterogeneous Platforms") on one AMD
+ * MI355X (gfx950).  C ABI; every pointer is marked host or device.
+ *
+ * The path (paper Alg. 0, "Sampling" and "Batch Generating" stages):
+ *   1. multi-hop fanout neighbour sampling from a seed set (Sec. III-A), each
+ *      neighbourhood sampled by weighted reservoir sampling (Alg. 1) with a
+ *      larger weight, the bias rate gamma, on neighbours whose feature row is
+ *      already in the device cache (locality-aware sampling);
+ *   2. reindex (Alg. 0 line 7): global ids -> local ids with duplicates
+ *      eliminated, one bipartite block in CSR form per hop;
+ *   3. feature_retrieve (Alg. 0 line 10): the input nodes' feature rows are
+ *      copied from the device cache or from the host store, as the device map
+ *      (Sec. III, feature cache module) says.
+ *
+ * Determinism.  rand(0,1) of Alg. 1 line 2 is a Philox4x32-10 draw x keyed on
+ * (rng_seed, hop, node id, neighbour slot); u = (x+1)/2^32.  The key
+ * k = u^(1/w) is compared in the log domain with integers only:
+ * K = floor((-log2(u) in Q32) * 65536 / w_q16), smaller is better, ties go to
+ * the larger x and then to the smaller slot.  A node with degree <= fanout
+ * keeps all its neighbours.  Exactly one output is correct for given inputs.
+ *
+ * Errors.  Every call returns A3_OK (0) or a negative code, never throws,
+ * aborts or prints.  Text for the last failure: a3_last_error().
+ */
+#ifndef A3GNN_H
+#define A3GNN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define A3_MAX_HOPS 8
+#define A3_MAX_FANOUT 1024
+
+#define A3_OK 0
+#define A3_ERR_INVALID_ARG (-1) /* null required pointer, bad width, fanout < 1, gamma < 1, ... */
+#define A3_ERR_CAPACITY (-2)    /* request exceeds what the context was created for */
+#define A3_ERR_HIP (-3)         /* HIP runtime failure, or no usable device */
+#define A3_ERR_INPUT (-4)       /* A3_VALIDATE found seeds out of range or repeated */
+
+/* a3_create flags */
+#define A3_VALIDATE 1u       /* check seeds (range, uniqueness) on the device before sampling */
+#define A3_NO_EIDS 2u        /* do not produce blk_eids */
+#define A3_HOST_ONLY 4u      /* no device: calls validate their arguments, then fail with A3_ERR_HIP */
+#define A3_FORCE_RADIX 8u    /* testing: always use the exhaustive selection path */
+
+typedef struct a3_ctx a3_ctx;
+
+/* Opaque context: owns the output arena, the relabel map and scratch memory.
+ *   out          host, receives the context.
+ *   hip_device   device ordinal.
+ *   hip_stream   hipStream_t (as void*) on which all work of this context is
+ *                queued; NULL = the default stream.
+ *   max_seeds, max_hops, max_fanouts[max_hops] (host)
+ *                upper limits of later a3_sample_blocks calls; the arena is
+ *                sized for them (per hop h: dst <= dst_{h-1} * (1 + f_{h-1})).
+ * Not thread-safe: one caller at a time per context. */
+int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t max_seeds, int32_t max_hops,
+              const int32_t* max_fanouts, uint32_t flags);
+int a3_destroy(a3_ctx* ctx);
+/* hipStream_t for subsequent calls; pending work on the old stream is waited for. */
+int a3_set_stream(a3_ctx* ctx, void* hip_stream);
+/* Text of the last error on ctx (ctx == NULL: of the last failed a3_create in
+ * this thread).  Owned by the library; valid until the next call. */
+const char* a3_last_error(const a3_ctx* ctx);
+
+/* Result of a3_sample_blocks.  Counts are host values; arrays are device
+ * memory owned by the context, valid until the next a3_sample_blocks on the
+ * same context or a3_destroy.  Hop h (0 = next to the seeds) is a bipartite
+ * block: n_dst[h] destination nodes, n_src[h] source nodes, n_edges[h] edges.
+ * Destinations are the first n_dst[h] sources, and the sources of hop h are
+ * the destinations of hop h+1, so ONE array maps local to global ids for all
+ * hops: input_nodes[0 : n_src[h]]. */
+typedef struct {
+  int32_t num_hops;
+  int64_t n_dst[A3_MAX_HOPS];
+  int64_t n_src[A3_MAX_HOPS];
+  int64_t n_edges[A3_MAX_HOPS];
+  int32_t* blk_indptr[A3_MAX_HOPS];  /* device [n_dst[h] + 1] */
+  int32_t* blk_indices[A3_MAX_HOPS]; /* device [n_edges[h]]: local source id of each edge */
+  int64_t* blk_eids[A3_MAX_HOPS];    /* device [n_edges[h]]: position of the edge in `indices`; NULL with A3_NO_EIDS */
+  void* input_nodes;                 /* device [n_src[num_hops-1]], idx_bytes wide: global id of local id */
+} a3_blocks;
+
+/* Sampling + reindex (Sec. III-A, Alg. 1, Alg. 0 line 7).
+ *   indptr      device int64 [num_nodes + 1], CSR row starts.
+ *   indices     device int32 (idx_bytes = 4) or int64 (idx_bytes = 8) [indptr[num_nodes]];
+ *               rows sorted, no repeated neighbour (not checked).
+ *   seeds       device, idx_bytes wide, [num_seeds]; distinct ids in [0, num_nodes).
+ *   fanouts     host int32 [num_hops]; fanouts[h] applies to hop h from the seeds.
+ *   cache_map   device int32 [num_nodes], the device map: c >= 0 means the
+ *               node's feature row is in the device cache; NULL = nothing is.
+ *   bias_q16    the bias rate gamma in Q16.16 (>= 65536; 65536 = uniform sampling).
+ *   rng_seed    any value; same inputs + same seed give the same bytes.
+ *   out         host, filled on success.
+ * Per destination i (in order) the min(fanout, degree) chosen neighbours are
+ * emitted in ascending slot order; new source nodes are numbered in order of
+ * first appearance after the destinations.
+ * Synchronisation: returns after the counts are on the host (one stream
+ * synchronisation); the arrays are then complete.
+ * Errors: A3_ERR_INVALID_ARG, A3_ERR_CAPACITY (outputs invalid), A3_ERR_HIP,
+ * A3_ERR_INPUT (only with A3_VALIDATE).  num_seeds == 0 succeeds with empty blocks. */
+int a3_sample_blocks(a3_ctx* ctx, const int64_t* indptr, const void* indices, int32_t idx_bytes,
+                     int64_t num_nodes, const void* seeds, int64_t num_seeds,
+                     const int32_t* fanouts, int32_t num_hops, const int32_t* cache_map,
+                     uint32_t bias_q16, uint64_t rng_seed, a3_blocks* out);
+
+/* Feature retrieve (Alg. 0 line 10): out[i,:] = feat_dev[c,:] if
+ * c = cache_map[ids[i]] >= 0, else feat_host[-c-1,:].
+ *   feat_dev    device [n_cached, row_bytes]; may be NULL if no id maps to it.
+ *   feat_host   host memory that the device can read (pinned, mapped)
+ *               [n_uncached, row_bytes]; may be NULL if no id maps to it.
+ *   cache_map   device int32 [num_nodes]; NULL = every row is in feat_dev at row = id.
+ *   ids         device, idx_bytes wide, [n_ids] (typically a3_blocks.input_nodes).
+ *   row_bytes   > 0, multiple of 2.
+ *   out         device [n_ids, row_bytes], caller-allocated.
+ * Rows are copied byte for byte.  Asynchronous on the context's stream.
+ * A needed store that is NULL is reported as A3_ERR_INVALID_ARG only when it
+ * can be known on the host (both NULL); otherwise behaviour is undefined. */
+int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
+                       const int32_t* cache_map, const void* ids, int32_t idx_bytes, int64_t n_ids,
+                       int64_t row_bytes, void* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,11 @@
+"""MI355X-native mini-batch path of A3GNN: locality-aware neighbour sampling, reindex into
+per-hop block CSRs, and feature gather from an HBM cache plus a pinned-host remainder.
+
+All computation happens in the HIP library behind the C ABI of include/a3gnn.h; this package
+only marshals torch tensors (device memory, streams) into that ABI.
+"""
+from .binding import (  # noqa: F401
+    A3Error, Context, Blocks, lib, library_path,
+    A3_OK, A3_ERR_INVALID_ARG, A3_ERR_CAPACITY, A3_ERR_HIP, A3_ERR_INPUT,
+    A3_VALIDATE, A3_NO_EIDS, A3_HOST_ONLY, A3_FORCE_RADIX, A3_MAX_HOPS, A3_MAX_FANOUT,
+)

@@ -1,0 +1,191 @@
+"""ctypes binding of include/a3gnn.h: argument marshalling only.
+
+The entry points keep their C names (lib().a3_create, ...); Context wraps them for torch
+tensors.  There is no fallback: if the HIP library is missing, loading raises.
+"""
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+import torch
+
+A3_MAX_HOPS = 8
+A3_MAX_FANOUT = 1024
+A3_OK, A3_ERR_INVALID_ARG, A3_ERR_CAPACITY, A3_ERR_HIP, A3_ERR_INPUT = 0, -1, -2, -3, -4
+A3_VALIDATE, A3_NO_EIDS, A3_HOST_ONLY, A3_FORCE_RADIX = 1, 2, 4, 8
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_lib = None
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "liba3gnn.so")
+
+
+class _CBlocks(C.Structure):
+    _fields_ = [
+        ("num_hops", C.c_int32),
+        ("n_dst", C.c_int64 * A3_MAX_HOPS),
+        ("n_src", C.c_int64 * A3_MAX_HOPS),
+        ("n_edges", C.c_int64 * A3_MAX_HOPS),
+        ("blk_indptr", C.c_void_p * A3_MAX_HOPS),
+        ("blk_indices", C.c_void_p * A3_MAX_HOPS),
+        ("blk_eids", C.c_void_p * A3_MAX_HOPS),
+        ("input_nodes", C.c_void_p),
+    ]
+
+
+def lib():
+    """The loaded C-ABI library.  Built by `python -m paper_2511_07421_amd.build` (hipcc)."""
+    global _lib
+    if _lib is None:
+        path = library_path()
+        if not os.path.exists(path):
+            from . import build as _build
+            _build.build()
+        L = C.CDLL(path)
+        L.a3_create.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_void_p, C.c_int64, C.c_int32,
+                                C.POINTER(C.c_int32), C.c_uint32]
+        L.a3_create.restype = C.c_int
+        L.a3_destroy.argtypes = [C.c_void_p]
+        L.a3_destroy.restype = C.c_int
+        L.a3_set_stream.argtypes = [C.c_void_p, C.c_void_p]
+        L.a3_set_stream.restype = C.c_int
+        L.a3_last_error.argtypes = [C.c_void_p]
+        L.a3_last_error.restype = C.c_char_p
+        L.a3_sample_blocks.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,
+                                       C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_int32,
+                                       C.c_void_p, C.c_uint32, C.c_uint64, C.POINTER(_CBlocks)]
+        L.a3_sample_blocks.restype = C.c_int
+        L.a3_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_int32, C.c_int64, C.c_int64, C.c_void_p]
+        L.a3_gather_features.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+class A3Error(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"a3gnn error {code}: {message}")
+        self.code = code
+
+
+class _DevView:
+    """Exposes ctx-owned device memory to torch without a copy."""
+
+    def __init__(self, ptr: int, n: int, typestr: str):
+        self.__cuda_array_interface__ = {"shape": (n,), "typestr": typestr, "data": (ptr, False),
+                                         "version": 2, "strides": None}
+
+
+def _view(ptr, n: int, dtype: torch.dtype, device) -> torch.Tensor:
+    if n == 0 or not ptr:
+        return torch.empty(0, dtype=dtype, device=device)
+    typestr = {torch.int32: "<i4", torch.int64: "<i8"}[dtype]
+    return torch.as_tensor(_DevView(int(ptr), int(n), typestr), device=device)
+
+
+@dataclass
+class Blocks:
+    """Views into context-owned device memory: valid until the next sample_blocks on the context."""
+    num_hops: int
+    n_dst: List[int]
+    n_src: List[int]
+    n_edges: List[int]
+    blk_indptr: List[torch.Tensor] = field(default_factory=list)
+    blk_indices: List[torch.Tensor] = field(default_factory=list)
+    blk_eids: List[Optional[torch.Tensor]] = field(default_factory=list)
+    input_nodes: torch.Tensor = None
+
+    def to_host(self) -> "Blocks":
+        """Independent host copies (numpy arrays), for comparisons."""
+        b = Blocks(self.num_hops, list(self.n_dst), list(self.n_src), list(self.n_edges))
+        b.blk_indptr = [t.cpu().numpy() for t in self.blk_indptr]
+        b.blk_indices = [t.cpu().numpy() for t in self.blk_indices]
+        b.blk_eids = [None if t is None else t.cpu().numpy() for t in self.blk_eids]
+        b.input_nodes = self.input_nodes.cpu().numpy()
+        return b
+
+
+def _dptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+class Context:
+    """An a3_ctx bound to a device and to torch's current stream on it."""
+
+    def __init__(self, max_seeds: int, max_fanouts: Sequence[int], device: int = 0, flags: int = 0,
+                 stream: Optional[int] = None):
+        self._h = C.c_void_p()
+        self.flags = flags
+        self.device = torch.device("cuda", device) if not (flags & A3_HOST_ONLY) else torch.device("cpu")
+        if stream is None and not (flags & A3_HOST_ONLY):
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+        fan = (C.c_int32 * len(max_fanouts))(*max_fanouts)
+        rc = lib().a3_create(C.byref(self._h), device, C.c_void_p(stream or 0), max_seeds,
+                             len(max_fanouts), fan, flags)
+        if rc != A3_OK:
+            raise A3Error(rc, (lib().a3_last_error(None) or b"").decode())
+
+    def close(self):
+        if self._h:
+            lib().a3_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != A3_OK:
+            raise A3Error(rc, (lib().a3_last_error(self._h) or b"").decode())
+
+    def set_stream(self, stream: int):
+        self._check(lib().a3_set_stream(self._h, C.c_void_p(stream)))
+
+    def sample_blocks(self, indptr: torch.Tensor, indices: torch.Tensor, seeds: torch.Tensor,
+                      fanouts: Sequence[int], cache_map: Optional[torch.Tensor] = None,
+                      bias_q16: int = 65536, rng_seed: int = 0) -> Blocks:
+        assert indptr.dtype == torch.int64 and indptr.is_contiguous()
+        assert indices.dtype in (torch.int32, torch.int64) and indices.is_contiguous()
+        assert seeds.dtype == indices.dtype and seeds.is_contiguous()
+        assert cache_map is None or (cache_map.dtype == torch.int32 and cache_map.is_contiguous())
+        num_nodes = indptr.shape[0] - 1
+        fan = (C.c_int32 * len(fanouts))(*fanouts)
+        cb = _CBlocks()
+        rc = lib().a3_sample_blocks(self._h, _dptr(indptr), _dptr(indices), indices.element_size(),
+                                    num_nodes, _dptr(seeds), seeds.shape[0], fan, len(fanouts),
+                                    _dptr(cache_map), bias_q16, rng_seed, C.byref(cb))
+        self._check(rc)
+        H = cb.num_hops
+        b = Blocks(H, list(cb.n_dst[:H]), list(cb.n_src[:H]), list(cb.n_edges[:H]))
+        dev = indices.device
+        for h in range(H):
+            b.blk_indptr.append(_view(cb.blk_indptr[h], b.n_dst[h] + 1, torch.int32, dev))
+            b.blk_indices.append(_view(cb.blk_indices[h], b.n_edges[h], torch.int32, dev))
+            b.blk_eids.append(None if not cb.blk_eids[h] else
+                              _view(cb.blk_eids[h], b.n_edges[h], torch.int64, dev))
+        b.input_nodes = _view(cb.input_nodes, b.n_src[H - 1], indices.dtype, dev)
+        return b
+
+    def gather_features(self, feat_dev: Optional[torch.Tensor], feat_host: Optional[torch.Tensor],
+                        cache_map: Optional[torch.Tensor], ids: torch.Tensor,
+                        out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        ref = feat_dev if feat_dev is not None else feat_host
+        assert ref is not None and ref.dim() == 2
+        for t in (feat_dev, feat_host):
+            assert t is None or (t.is_contiguous() and t.dtype == ref.dtype and t.shape[1] == ref.shape[1])
+        assert feat_host is None or feat_host.is_pinned(), "feat_host must be pinned host memory"
+        assert ids.dtype in (torch.int32, torch.int64) and ids.is_contiguous()
+        row_bytes = ref.shape[1] * ref.element_size()
+        if out is None:
+            out = torch.empty((ids.shape[0], ref.shape[1]), dtype=ref.dtype, device=ids.device)
+        assert out.is_contiguous() and out.shape == (ids.shape[0], ref.shape[1]) and out.dtype == ref.dtype
+        rc = lib().a3_gather_features(self._h, _dptr(feat_dev), _dptr(feat_host), _dptr(cache_map),
+                                      _dptr(ids), ids.element_size(), ids.shape[0], row_bytes,
+                                      _dptr(out))
+        self._check(rc)
+        return out

@@ -1,0 +1,448 @@
+// C ABI of the A3GNN mini-batch path on MI355X: context, launch sequencing, error handling.
+// The kernels are in a3_kernels.hpp; the interface contract is in include/a3gnn.h.
+#include "a3gnn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "a3_kernels.hpp"
+
+using a3::DevState;
+
+struct a3_ctx {
+  int device = 0;
+  hipStream_t stream = nullptr;
+  uint32_t flags = 0;
+  int64_t max_seeds = 0;
+  int32_t max_hops = 0;
+  int32_t max_fanouts[A3_MAX_HOPS] = {0};
+  int64_t cap_dst[A3_MAX_HOPS + 1] = {0};  // arena capacity per hop
+  int64_t cap_edges[A3_MAX_HOPS] = {0};
+  int64_t cap_tiles = 0;
+
+  // arena (device)
+  void* S = nullptr;  // local -> global, 8 bytes per entry reserved
+  int32_t* blk_indptr[A3_MAX_HOPS] = {nullptr};
+  int32_t* blk_indices[A3_MAX_HOPS] = {nullptr};
+  int64_t* blk_eids[A3_MAX_HOPS] = {nullptr};
+  void* gid = nullptr;           // sampled global ids of the running hop, 8 bytes per entry
+  int32_t* vals = nullptr;       // scan input
+  int32_t* first_pos = nullptr;  // per edge: relabel-map value
+  int32_t* new_rank = nullptr;   // per edge: exclusive count of first occurrences
+  int32_t* tile_sums = nullptr;
+  int32_t* tile_offs = nullptr;
+  int32_t* node_map = nullptr;  // global id -> position, grown on demand
+  int64_t node_map_cap = 0;
+  bool node_map_dirty = false;
+  DevState* d_state = nullptr;
+  DevState* h_state = nullptr;  // pinned
+  std::vector<void*> allocs;
+  std::string err;
+};
+
+namespace {
+
+thread_local std::string g_create_err;
+
+int fail(a3_ctx* ctx, int code, const std::string& msg) {
+  if (ctx)
+    ctx->err = msg;
+  else
+    g_create_err = msg;
+  return code;
+}
+
+int hip_fail(a3_ctx* ctx, hipError_t e, const char* what) {
+  return fail(ctx, A3_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define A3_HIP(ctx, call)                               \
+  do {                                                  \
+    hipError_t e_ = (call);                             \
+    if (e_ != hipSuccess) return hip_fail(ctx, e_, #call); \
+  } while (0)
+
+template <typename T>
+int dev_alloc(a3_ctx* ctx, T** p, int64_t count) {
+  void* q = nullptr;
+  const size_t bytes = (size_t)std::max<int64_t>(count, 1) * sizeof(T);
+  hipError_t e = hipMalloc(&q, bytes);
+  if (e != hipSuccess) return hip_fail(ctx, e, "hipMalloc");
+  ctx->allocs.push_back(q);
+  *p = (T*)q;
+  return A3_OK;
+}
+
+inline unsigned blocks_for(int64_t n, int per_block) {
+  return (unsigned)std::max<int64_t>(1, (n + per_block - 1) / per_block);
+}
+
+// candidates kept by the draw threshold: enough above m that fewer than m survive only with
+// negligible probability (then the exhaustive path takes over)
+uint32_t lambda_for(int32_t m) { return (uint32_t)(m + 4.0 * std::sqrt((double)m) + 8.0); }
+uint32_t cap_for(uint32_t lambda) { return ((2 * lambda + 63) / 64) * 64; }
+constexpr uint32_t kChallengerCap = 192;
+
+size_t sample_lds_bytes(int32_t fanout, bool weighted) {
+  const uint32_t cap = cap_for(lambda_for(fanout));
+  size_t entries = (size_t)cap + (size_t)fanout;
+  if (weighted) entries += 3 * (size_t)fanout + 2 * (size_t)kChallengerCap;
+  return entries * sizeof(uint64_t);
+}
+
+void free_all(a3_ctx* ctx) {
+  for (void* p : ctx->allocs) (void)hipFree(p);
+  ctx->allocs.clear();
+  if (ctx->node_map) (void)hipFree(ctx->node_map);
+  ctx->node_map = nullptr;
+  if (ctx->h_state) (void)hipHostFree(ctx->h_state);
+  ctx->h_state = nullptr;
+}
+
+int ensure_node_map(a3_ctx* ctx, int64_t num_nodes) {
+  if (num_nodes > ctx->node_map_cap) {
+    if (ctx->node_map) {
+      A3_HIP(ctx, hipStreamSynchronize(ctx->stream));
+      A3_HIP(ctx, hipFree(ctx->node_map));
+      ctx->node_map = nullptr;
+      ctx->node_map_cap = 0;
+    }
+    void* q = nullptr;
+    A3_HIP(ctx, hipMalloc(&q, (size_t)std::max<int64_t>(num_nodes, 1) * sizeof(int32_t)));
+    ctx->node_map = (int32_t*)q;
+    ctx->node_map_cap = num_nodes;
+    ctx->node_map_dirty = true;
+  }
+  if (ctx->node_map_dirty) {
+    hipLaunchKernelGGL(a3::k_fill_i32, dim3(blocks_for(ctx->node_map_cap, 256)), dim3(256), 0,
+                       ctx->stream, ctx->node_map, ctx->node_map_cap, a3::kMapEmpty);
+    A3_HIP(ctx, hipGetLastError());
+    ctx->node_map_dirty = false;
+  }
+  return A3_OK;
+}
+
+template <typename IdxT>
+int sample_impl(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int64_t num_nodes,
+                const IdxT* seeds, int64_t num_seeds, const int32_t* fanouts, int32_t num_hops,
+                const int32_t* cache_map, uint32_t bias_q16, uint64_t rng_seed, a3_blocks* out) {
+  hipStream_t st = ctx->stream;
+  IdxT* S = (IdxT*)ctx->S;
+  IdxT* gid = (IdxT*)ctx->gid;
+  DevState* ds = ctx->d_state;
+  const bool weighted = cache_map != nullptr && bias_q16 > 65536u;
+  const int validate = (ctx->flags & A3_VALIDATE) ? 1 : 0;
+
+  // launch bounds per hop for this call: never more than the arena holds, never more than the
+  // graph has nodes
+  int64_t bound_dst[A3_MAX_HOPS + 1], bound_edges[A3_MAX_HOPS];
+  bound_dst[0] = num_seeds;
+  for (int h = 0; h < num_hops; ++h) {
+    bound_edges[h] = bound_dst[h] * (int64_t)fanouts[h];
+    bound_dst[h + 1] = std::min<int64_t>(bound_dst[h] + bound_edges[h],
+                                         std::max<int64_t>(num_nodes, bound_dst[h]));
+  }
+
+  int rc = ensure_node_map(ctx, num_nodes);
+  if (rc != A3_OK) return rc;
+  ctx->node_map_dirty = true;  // until the call has cleaned up after itself
+
+  hipLaunchKernelGGL(a3::k_init_seeds<IdxT>, dim3(blocks_for(num_seeds, 256)), dim3(256), 0, st,
+                     seeds, num_seeds, num_nodes, S, ctx->node_map, ds, validate);
+  if (validate) {
+    hipLaunchKernelGGL(a3::k_check_seeds<IdxT>, dim3(blocks_for(num_seeds, 256)), dim3(256), 0, st,
+                       seeds, num_seeds, num_nodes, ctx->node_map, ds);
+    hipLaunchKernelGGL(a3::k_gate_on_error, dim3(1), dim3(64), 0, st, ds);
+  }
+
+  for (int h = 0; h < num_hops; ++h) {
+    const int32_t f = fanouts[h];
+    const unsigned dst_tiles = blocks_for(bound_dst[h], a3::kScanTile);
+    const unsigned edge_tiles = blocks_for(bound_edges[h], a3::kScanTile);
+    // a1: degrees -> edge offsets of the block
+    hipLaunchKernelGGL(a3::k_count_degrees<IdxT>, dim3(dst_tiles), dim3(a3::kScanThreads), 0, st, S,
+                       indptr, ds, h, f, ctx->vals, ctx->tile_sums);
+    hipLaunchKernelGGL(a3::k_scan_tile_sums, dim3(1), dim3(a3::kScanThreads), 0, st,
+                       ctx->tile_sums, ctx->tile_offs, ds, h, 0, ctx->blk_indptr[h]);
+    hipLaunchKernelGGL(a3::k_scan_apply, dim3(dst_tiles), dim3(a3::kScanThreads), 0, st, ctx->vals,
+                       ctx->tile_offs, ds, h, 0, ctx->blk_indptr[h]);
+    // a2-a4: selection, one wave per frontier node
+    if (bound_dst[h] > 0) {
+      a3::SampleArgs<IdxT> sa;
+      sa.indptr = indptr;
+      sa.indices = indices;
+      sa.cache_map = cache_map;
+      sa.S = S;
+      sa.blk_indptr = ctx->blk_indptr[h];
+      sa.gid = gid;
+      sa.eids = ctx->blk_eids[h];
+      sa.node_map = ctx->node_map;
+      sa.st = ds;
+      sa.hop = h;
+      sa.fanout = f;
+      sa.lambda = lambda_for(f);
+      sa.cap = cap_for(sa.lambda);
+      sa.xcap = kChallengerCap;
+      sa.bias_q16 = bias_q16;
+      sa.seed_lo = (uint32_t)rng_seed;
+      sa.seed_hi = (uint32_t)(rng_seed >> 32);
+      sa.weighted = weighted ? 1u : 0u;
+      sa.force_radix = (ctx->flags & A3_FORCE_RADIX) ? 1u : 0u;
+      hipLaunchKernelGGL(a3::k_sample<IdxT>, dim3((unsigned)bound_dst[h]), dim3(a3::kWave),
+                         sample_lds_bytes(f, weighted), st, sa);
+    }
+    // a5: first occurrences -> numbering of new nodes -> local ids
+    hipLaunchKernelGGL(a3::k_flag_first<IdxT>, dim3(edge_tiles), dim3(a3::kScanThreads), 0, st, gid,
+                       ctx->node_map, ds, h, ctx->first_pos, ctx->vals, ctx->tile_sums);
+    hipLaunchKernelGGL(a3::k_scan_tile_sums, dim3(1), dim3(a3::kScanThreads), 0, st,
+                       ctx->tile_sums, ctx->tile_offs, ds, h, 1, (int32_t*)nullptr);
+    hipLaunchKernelGGL(a3::k_scan_apply, dim3(edge_tiles), dim3(a3::kScanThreads), 0, st, ctx->vals,
+                       ctx->tile_offs, ds, h, 1, ctx->new_rank);
+    hipLaunchKernelGGL(a3::k_relabel<IdxT>, dim3(blocks_for(bound_edges[h], 256)), dim3(256), 0, st,
+                       gid, ctx->first_pos, ctx->new_rank, ds, h, S, ctx->node_map,
+                       ctx->blk_indices[h]);
+  }
+  // leave the relabel map empty for the next call
+  hipLaunchKernelGGL(a3::k_reset_map<IdxT>, dim3(blocks_for(bound_dst[num_hops], 256)), dim3(256),
+                     0, st, S, ds, num_hops - 1, num_nodes, ctx->node_map);
+  A3_HIP(ctx, hipGetLastError());
+  A3_HIP(ctx, hipMemcpyAsync(ctx->h_state, ds, sizeof(DevState), hipMemcpyDeviceToHost, st));
+  A3_HIP(ctx, hipStreamSynchronize(st));
+  const DevState& hs = *ctx->h_state;
+  if (hs.error & (a3::kErrBadSeed | a3::kErrDupSeed)) {
+    return fail(ctx, A3_ERR_INPUT,
+                (hs.error & a3::kErrBadSeed) ? "a3_sample_blocks: a seed is outside [0, num_nodes)"
+                                             : "a3_sample_blocks: a seed appears twice");
+  }
+  if (hs.error & a3::kErrHugeRow)
+    return fail(ctx, A3_ERR_CAPACITY, "a3_sample_blocks: a CSR row has more than 2^31-1 entries");
+  ctx->node_map_dirty = false;
+
+  std::memset(out, 0, sizeof(*out));
+  out->num_hops = num_hops;
+  for (int h = 0; h < num_hops; ++h) {
+    out->n_dst[h] = hs.n_dst[h];
+    out->n_src[h] = hs.n_src[h];
+    out->n_edges[h] = hs.n_edges[h];
+    out->blk_indptr[h] = ctx->blk_indptr[h];
+    out->blk_indices[h] = ctx->blk_indices[h];
+    out->blk_eids[h] = ctx->blk_eids[h];
+  }
+  out->input_nodes = ctx->S;
+  return A3_OK;
+}
+
+template <typename VecT, typename IdxT>
+void launch_gather(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
+                   const int32_t* cache_map, const void* ids, int64_t n_ids, int64_t row_bytes,
+                   void* out) {
+  const uint32_t vpr = (uint32_t)(row_bytes / (int64_t)sizeof(VecT));
+  const int64_t total = n_ids * (int64_t)vpr;
+  const unsigned grid = blocks_for(total, a3::kGatherThreads * a3::kGatherUnroll);
+  hipLaunchKernelGGL((a3::k_gather<VecT, IdxT>), dim3(grid), dim3(a3::kGatherThreads), 0,
+                     ctx->stream, (const char*)feat_dev, (const char*)feat_host, cache_map,
+                     (const IdxT*)ids, n_ids, vpr, row_bytes, (VecT*)out);
+}
+
+template <typename IdxT>
+void gather_by_width(a3_ctx* ctx, int width, const void* feat_dev, const void* feat_host,
+                     const int32_t* cache_map, const void* ids, int64_t n_ids, int64_t row_bytes,
+                     void* out) {
+  switch (width) {
+    case 16: launch_gather<uint4, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
+    case 8: launch_gather<uint2, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
+    case 4: launch_gather<uint32_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
+    default: launch_gather<uint16_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
+  }
+}
+
+}  // namespace
+
+extern "C" const char* a3_last_error(const a3_ctx* ctx) {
+  return ctx ? ctx->err.c_str() : g_create_err.c_str();
+}
+
+extern "C" int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t max_seeds,
+                         int32_t max_hops, const int32_t* max_fanouts, uint32_t flags) {
+  if (!out) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_create: out is null");
+  *out = nullptr;
+  if (!max_fanouts) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_create: max_fanouts is null");
+  if (max_seeds < 0) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_create: max_seeds < 0");
+  if (max_hops < 1 || max_hops > A3_MAX_HOPS)
+    return fail(nullptr, A3_ERR_INVALID_ARG, "a3_create: max_hops must be in [1, A3_MAX_HOPS]");
+  for (int h = 0; h < max_hops; ++h)
+    if (max_fanouts[h] < 1 || max_fanouts[h] > A3_MAX_FANOUT)
+      return fail(nullptr, A3_ERR_INVALID_ARG, "a3_create: fanout must be in [1, A3_MAX_FANOUT]");
+
+  a3_ctx* ctx = new (std::nothrow) a3_ctx();
+  if (!ctx) return fail(nullptr, A3_ERR_HIP, "a3_create: out of host memory");
+  ctx->device = hip_device;
+  ctx->stream = (hipStream_t)hip_stream;
+  ctx->flags = flags;
+  ctx->max_seeds = max_seeds;
+  ctx->max_hops = max_hops;
+  ctx->cap_dst[0] = max_seeds;
+  int64_t max_edges = 0;
+  for (int h = 0; h < max_hops; ++h) {
+    ctx->max_fanouts[h] = max_fanouts[h];
+    ctx->cap_edges[h] = ctx->cap_dst[h] * (int64_t)max_fanouts[h];
+    ctx->cap_dst[h + 1] = ctx->cap_dst[h] + ctx->cap_edges[h];
+    max_edges = std::max(max_edges, ctx->cap_edges[h]);
+    if (ctx->cap_dst[h + 1] > 0x7FFFFFFFLL) {
+      delete ctx;
+      return fail(nullptr, A3_ERR_CAPACITY,
+                  "a3_create: seeds x fanouts exceed 2^31-1 local ids per mini-batch");
+    }
+  }
+  if (flags & A3_HOST_ONLY) {
+    *out = ctx;
+    return A3_OK;
+  }
+
+  hipError_t e = hipSetDevice(hip_device);
+  if (e != hipSuccess) {
+    int rc = hip_fail(nullptr, e, "a3_create: hipSetDevice");
+    delete ctx;
+    return rc;
+  }
+  const int64_t max_items = std::max(max_edges, ctx->cap_dst[max_hops]);
+  ctx->cap_tiles = (max_items + a3::kScanTile - 1) / a3::kScanTile + 1;
+  int rc = A3_OK;
+  auto chk = [&](int r) { if (rc == A3_OK) rc = r; };
+  chk(dev_alloc(ctx, (int64_t**)&ctx->S, ctx->cap_dst[max_hops]));
+  chk(dev_alloc(ctx, (int64_t**)&ctx->gid, max_edges));
+  chk(dev_alloc(ctx, &ctx->vals, max_items));
+  chk(dev_alloc(ctx, &ctx->first_pos, max_edges));
+  chk(dev_alloc(ctx, &ctx->new_rank, max_edges));
+  chk(dev_alloc(ctx, &ctx->tile_sums, ctx->cap_tiles));
+  chk(dev_alloc(ctx, &ctx->tile_offs, ctx->cap_tiles));
+  chk(dev_alloc(ctx, &ctx->d_state, 1));
+  for (int h = 0; h < max_hops && rc == A3_OK; ++h) {
+    chk(dev_alloc(ctx, &ctx->blk_indptr[h], ctx->cap_dst[h] + 1));
+    chk(dev_alloc(ctx, &ctx->blk_indices[h], ctx->cap_edges[h]));
+    if (!(flags & A3_NO_EIDS)) chk(dev_alloc(ctx, &ctx->blk_eids[h], ctx->cap_edges[h]));
+  }
+  if (rc == A3_OK) {
+    void* hp = nullptr;
+    e = hipHostMalloc(&hp, sizeof(DevState), hipHostMallocDefault);
+    if (e != hipSuccess)
+      rc = hip_fail(ctx, e, "a3_create: hipHostMalloc");
+    else
+      ctx->h_state = (DevState*)hp;
+  }
+  if (rc != A3_OK) {
+    g_create_err = ctx->err;
+    free_all(ctx);
+    delete ctx;
+    return rc;
+  }
+  *out = ctx;
+  return A3_OK;
+}
+
+extern "C" int a3_destroy(a3_ctx* ctx) {
+  if (!ctx) return A3_OK;
+  if (!(ctx->flags & A3_HOST_ONLY)) {
+    (void)hipSetDevice(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    free_all(ctx);
+  }
+  delete ctx;
+  return A3_OK;
+}
+
+extern "C" int a3_set_stream(a3_ctx* ctx, void* hip_stream) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_set_stream: ctx is null");
+  if (!(ctx->flags & A3_HOST_ONLY)) {
+    A3_HIP(ctx, hipSetDevice(ctx->device));
+    A3_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  }
+  ctx->stream = (hipStream_t)hip_stream;
+  return A3_OK;
+}
+
+extern "C" int a3_sample_blocks(a3_ctx* ctx, const int64_t* indptr, const void* indices,
+                                int32_t idx_bytes, int64_t num_nodes, const void* seeds,
+                                int64_t num_seeds, const int32_t* fanouts, int32_t num_hops,
+                                const int32_t* cache_map, uint32_t bias_q16, uint64_t rng_seed,
+                                a3_blocks* out) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_sample_blocks: ctx is null");
+  if (!out) return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: out is null");
+  if (!indptr) return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: indptr is null");
+  if (!fanouts) return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: fanouts is null");
+  if (idx_bytes != 4 && idx_bytes != 8)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: idx_bytes must be 4 or 8");
+  if (num_nodes < 0 || num_seeds < 0)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: negative size");
+  if (idx_bytes == 4 && num_nodes > 0x7FFFFFFFLL)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: num_nodes needs 8-byte ids");
+  if (num_seeds > 0 && (!seeds || !indices))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: seeds or indices is null");
+  if (num_hops < 1 || num_hops > A3_MAX_HOPS)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: num_hops must be in [1, A3_MAX_HOPS]");
+  for (int h = 0; h < num_hops; ++h)
+    if (fanouts[h] < 1)
+      return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: fanout < 1");
+  if (bias_q16 < 65536u)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: bias rate below 1 (bias_q16 < 65536)");
+  if (num_seeds > ctx->max_seeds)
+    return fail(ctx, A3_ERR_CAPACITY, "a3_sample_blocks: num_seeds exceeds the context's max_seeds");
+  if (num_hops > ctx->max_hops)
+    return fail(ctx, A3_ERR_CAPACITY, "a3_sample_blocks: num_hops exceeds the context's max_hops");
+  for (int h = 0; h < num_hops; ++h)
+    if (fanouts[h] > ctx->max_fanouts[h])
+      return fail(ctx, A3_ERR_CAPACITY, "a3_sample_blocks: fanout exceeds the context's max_fanouts");
+  if (ctx->flags & A3_HOST_ONLY)
+    return fail(ctx, A3_ERR_HIP, "a3_sample_blocks: context was created without a device");
+  A3_HIP(ctx, hipSetDevice(ctx->device));
+  if (idx_bytes == 4)
+    return sample_impl<int32_t>(ctx, indptr, (const int32_t*)indices, num_nodes,
+                                (const int32_t*)seeds, num_seeds, fanouts, num_hops, cache_map,
+                                bias_q16, rng_seed, out);
+  return sample_impl<int64_t>(ctx, indptr, (const int64_t*)indices, num_nodes,
+                              (const int64_t*)seeds, num_seeds, fanouts, num_hops, cache_map,
+                              bias_q16, rng_seed, out);
+}
+
+extern "C" int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
+                                  const int32_t* cache_map, const void* ids, int32_t idx_bytes,
+                                  int64_t n_ids, int64_t row_bytes, void* out) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_gather_features: ctx is null");
+  if (idx_bytes != 4 && idx_bytes != 8)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: idx_bytes must be 4 or 8");
+  if (n_ids < 0) return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: n_ids < 0");
+  if (row_bytes <= 0 || (row_bytes & 1))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: row_bytes must be positive and even");
+  if (row_bytes > (1ll << 30))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: row_bytes above 2^30");
+  if (n_ids > 0 && (!ids || !out))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: ids or out is null");
+  if (n_ids > 0 && !feat_dev && !feat_host)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: both feature stores are null");
+  if (n_ids > 0 && !cache_map && !feat_dev)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: no device map needs feat_dev");
+  if (ctx->flags & A3_HOST_ONLY)
+    return fail(ctx, A3_ERR_HIP, "a3_gather_features: context was created without a device");
+  if (n_ids == 0) return A3_OK;
+  A3_HIP(ctx, hipSetDevice(ctx->device));
+  // widest vector that divides the row and keeps every row start aligned in all three buffers
+  const uintptr_t align_bits = (uintptr_t)feat_dev | (uintptr_t)feat_host | (uintptr_t)out |
+                               (uintptr_t)row_bytes;
+  int width = 16;
+  while (width > 2 && (align_bits & (uintptr_t)(width - 1))) width >>= 1;
+  if (align_bits & 1)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: buffers must be 2-byte aligned");
+  if (idx_bytes == 4)
+    gather_by_width<int32_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out);
+  else
+    gather_by_width<int64_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out);
+  A3_HIP(ctx, hipGetLastError());
+  return A3_OK;
+}

@@ -1,0 +1,112 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every declared
+symbol, and rejects bad arguments before touching a device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2511_07421_amd as a3
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(a3.library_path()):
+        from paper_2511_07421_amd import build
+        build.build()
+    return a3.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(a3_[a-z_]+)\s*\(", text))
+    assert {"a3_create", "a3_destroy", "a3_set_stream", "a3_last_error", "a3_sample_blocks",
+            "a3_gather_features"} <= names
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def _create(L, max_seeds, fanouts, flags):
+    h = C.c_void_p()
+    fan = (C.c_int32 * len(fanouts))(*fanouts)
+    rc = L.a3_create(C.byref(h), 0, None, max_seeds, len(fanouts), fan, flags)
+    return rc, h
+
+
+def test_create_argument_errors(L):
+    assert _create(L, -1, [2], a3.A3_HOST_ONLY)[0] == a3.A3_ERR_INVALID_ARG
+    assert _create(L, 4, [0], a3.A3_HOST_ONLY)[0] == a3.A3_ERR_INVALID_ARG
+    assert _create(L, 4, [a3.A3_MAX_FANOUT + 1], a3.A3_HOST_ONLY)[0] == a3.A3_ERR_INVALID_ARG
+    assert _create(L, 4, [2] * 9, a3.A3_HOST_ONLY)[0] == a3.A3_ERR_INVALID_ARG
+    assert b"max_hops" in L.a3_last_error(None)
+    # 2^20 seeds x 1024 x 1024 local ids do not fit int32
+    assert _create(L, 1 << 20, [1024, 1024], a3.A3_HOST_ONLY)[0] == a3.A3_ERR_CAPACITY
+    assert L.a3_create(None, 0, None, 4, 1, (C.c_int32 * 1)(2), a3.A3_HOST_ONLY) == a3.A3_ERR_INVALID_ARG
+    rc, h = _create(L, 4, [2, 2], a3.A3_HOST_ONLY)
+    assert rc == a3.A3_OK and h.value
+    assert L.a3_destroy(h) == a3.A3_OK
+    assert L.a3_destroy(None) == a3.A3_OK
+
+
+def test_sample_and_gather_argument_errors(L):
+    rc, h = _create(L, 8, [3, 2], a3.A3_HOST_ONLY)
+    assert rc == a3.A3_OK
+    blocks = a3.binding._CBlocks()
+    dummy = C.create_string_buffer(64)
+    p = C.cast(dummy, C.c_void_p)
+    fan = (C.c_int32 * 2)(3, 2)
+
+    def sample(indptr=p, indices=p, ib=4, n=10, seeds=p, ns=4, f=fan, nh=2, cm=None, bias=65536,
+               out=C.byref(blocks)):
+        return L.a3_sample_blocks(h, indptr, indices, ib, n, seeds, ns, f, nh, cm, bias, 0, out)
+
+    assert sample(indptr=None) == a3.A3_ERR_INVALID_ARG
+    assert sample(ib=2) == a3.A3_ERR_INVALID_ARG
+    assert sample(seeds=None) == a3.A3_ERR_INVALID_ARG
+    assert sample(ns=-1) == a3.A3_ERR_INVALID_ARG
+    assert sample(nh=0) == a3.A3_ERR_INVALID_ARG
+    assert sample(f=(C.c_int32 * 2)(3, 0)) == a3.A3_ERR_INVALID_ARG
+    assert sample(bias=65535) == a3.A3_ERR_INVALID_ARG
+    assert b"bias" in L.a3_last_error(h)
+    assert sample(out=None) == a3.A3_ERR_INVALID_ARG
+    assert sample(ns=9) == a3.A3_ERR_CAPACITY
+    assert sample(f=(C.c_int32 * 2)(4, 2)) == a3.A3_ERR_CAPACITY
+    assert sample(f=(C.c_int32 * 3)(3, 2, 2), nh=3) == a3.A3_ERR_CAPACITY
+    # valid arguments, but the context has no device: fails loudly instead of computing elsewhere
+    assert sample() == a3.A3_ERR_HIP
+    assert b"without a device" in L.a3_last_error(h)
+
+    def gather(fd=p, fh=None, cm=None, ids=p, ib=4, n=2, rb=8, out=p):
+        return L.a3_gather_features(h, fd, fh, cm, ids, ib, n, rb, out)
+
+    assert gather(ib=3) == a3.A3_ERR_INVALID_ARG
+    assert gather(n=-1) == a3.A3_ERR_INVALID_ARG
+    assert gather(rb=0) == a3.A3_ERR_INVALID_ARG
+    assert gather(rb=7) == a3.A3_ERR_INVALID_ARG
+    assert gather(ids=None) == a3.A3_ERR_INVALID_ARG
+    assert gather(out=None) == a3.A3_ERR_INVALID_ARG
+    assert gather(fd=None, fh=None) == a3.A3_ERR_INVALID_ARG
+    assert gather(fd=None, fh=p, cm=None) == a3.A3_ERR_INVALID_ARG
+    assert gather() == a3.A3_ERR_HIP
+    assert L.a3_sample_blocks(None, p, p, 4, 10, p, 4, fan, 2, None, 65536, 0, C.byref(blocks)) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_destroy(h) == a3.A3_OK
+
+
+def test_python_wrapper_raises_with_message():
+    ctx = a3.Context(8, [3, 2], flags=a3.A3_HOST_ONLY)
+    import torch
+    indptr = torch.zeros(5, dtype=torch.int64)
+    idx = torch.zeros(4, dtype=torch.int32)
+    with pytest.raises(a3.A3Error) as ei:
+        ctx.sample_blocks(indptr, idx, idx[:2], [3, 2])
+    assert ei.value.code == a3.A3_ERR_HIP
+    with pytest.raises(a3.A3Error) as ei:
+        ctx.sample_blocks(indptr, idx, idx[:2], [9, 2])
+    assert ei.value.code == a3.A3_ERR_CAPACITY
+    ctx.close()

@@ -1,0 +1,170 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle.
+Bit-exact on every index array; byte-exact on gathered rows (they are copies)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2511_07421_amd as a3
+from helpers import blocks_equal, check_block_invariants
+from workloads import get_config, make_graph, make_features, degree_ranked_cache, seed_batch
+
+pytestmark = pytest.mark.gpu
+Q = 65536
+DEV = "cuda:0"
+_graphs = {}
+
+
+def _graph(name):
+    if name not in _graphs:
+        w = get_config(name)
+        g = make_graph(w.num_nodes, w.mean_degree, w.d_min, w.d_max, w.a, w.symmetric, w.graph_seed,
+                       w.idx_dtype)
+        _graphs[name] = (w, g, g.indptr.to(DEV), g.indices.to(DEV))
+    return _graphs[name]
+
+
+def _compare(ctx, w, g, d_indptr, d_indices, seeds, fanouts, cm_host, gamma, rng_seed, tag=""):
+    print(f"[case] {tag} graph={w.name} seeds={len(seeds)} fanouts={fanouts} gamma={gamma} "
+          f"rng_seed={rng_seed}", flush=True)
+    d_seeds = torch.from_numpy(seeds).to(DEV)
+    d_cm = None if cm_host is None else torch.from_numpy(cm_host).to(DEV)
+    got = ctx.sample_blocks(d_indptr, d_indices, d_seeds, fanouts, d_cm, int(gamma * Q), rng_seed)
+    got = got.to_host()
+    want = oracle.sample_blocks(g.indptr.numpy(), g.indices.numpy(), seeds, fanouts, cm_host,
+                                int(gamma * Q), rng_seed)
+    blocks_equal(got, want)
+    return got
+
+
+@pytest.mark.parametrize("name", ["tiny", "mini_social", "mini_copurchase", "mini_citation"])
+def test_sample_blocks_matches_oracle(name):
+    w, g, d_ip, d_ix = _graph(name)
+    ctx = a3.Context(w.batch, w.fanouts)
+    cm = degree_ranked_cache(g, None, w.cache_frac).cache_map.numpy()
+    n_batches = 8 if name == "tiny" else 2
+    for gamma in w.bias_rates:
+        for b in range(n_batches):
+            seeds = seed_batch(w.num_nodes, w.batch, 0, b, dtype=g.indices.numpy().dtype)
+            got = _compare(ctx, w, g, d_ip, d_ix, seeds, w.fanouts, cm, gamma, b, "main")
+            if b == 0:
+                check_block_invariants(g.indptr.numpy(), g.indices.numpy(), seeds, w.fanouts, got)
+    ctx.close()
+
+
+@pytest.mark.parametrize("gamma", [1.5, 2.0, 8.0, 64.0, 65535.0])
+def test_weighted_selection_matches_oracle(gamma):
+    """partial cache: both weight classes present; large gamma floods the challenger buffer"""
+    w, g, d_ip, d_ix = _graph("mini_social")
+    ctx = a3.Context(128, [25, 10])
+    for frac in [0.05, 0.5]:
+        cm = degree_ranked_cache(g, None, frac).cache_map.numpy()
+        seeds = seed_batch(w.num_nodes, 100, 1, 0)
+        _compare(ctx, w, g, d_ip, d_ix, seeds, [25, 10], cm, gamma, 11, f"frac={frac}")
+    ctx.close()
+
+
+def test_exhaustive_selection_path_matches_oracle():
+    for name in ["tiny", "mini_copurchase"]:
+        w, g, d_ip, d_ix = _graph(name)
+        ctx = a3.Context(w.batch, w.fanouts, flags=a3.A3_FORCE_RADIX)
+        cm = degree_ranked_cache(g, None, 0.2).cache_map.numpy()
+        seeds = seed_batch(w.num_nodes, min(w.batch, 64), 2, 0)
+        _compare(ctx, w, g, d_ip, d_ix, seeds, w.fanouts, cm, 1.0, 5, "radix uniform")
+        _compare(ctx, w, g, d_ip, d_ix, seeds, w.fanouts, cm, 4.0, 5, "radix weighted")
+        ctx.close()
+
+
+def test_fanout_shapes_and_edge_cases():
+    w, g, d_ip, d_ix = _graph("mini_social")
+    ctx = a3.Context(300, [70, 3, 2, 1], flags=a3.A3_VALIDATE)
+    cm = degree_ranked_cache(g, None, 0.3).cache_map.numpy()
+    # empty batch
+    empty = ctx.sample_blocks(d_ip, d_ix, torch.zeros(0, dtype=torch.int32, device=DEV), [3, 2])
+    assert empty.n_dst == [0, 0] and empty.n_edges == [0, 0] and empty.input_nodes.numel() == 0
+    # one seed; fanout above 64 (more than one candidate per lane); four hops; fanout 1
+    for seeds_n, fan in [(1, [5]), (7, [70]), (300, [1, 1, 1, 1]), (33, [70, 3, 2, 1]), (257, [2, 2])]:
+        seeds = seed_batch(w.num_nodes, seeds_n, 3, seeds_n)
+        _compare(ctx, w, g, d_ip, d_ix, seeds, fan, cm, 1.0, 9, "shape")
+        _compare(ctx, w, g, d_ip, d_ix, seeds, fan, cm, 3.0, 9, "shape weighted")
+    # capacity and input errors come back as codes, and the context keeps working
+    with pytest.raises(a3.A3Error) as ei:
+        ctx.sample_blocks(d_ip, d_ix, torch.arange(301, dtype=torch.int32, device=DEV), [2])
+    assert ei.value.code == a3.A3_ERR_CAPACITY
+    with pytest.raises(a3.A3Error) as ei:
+        ctx.sample_blocks(d_ip, d_ix, torch.tensor([5, 9, 5], dtype=torch.int32, device=DEV), [2])
+    assert ei.value.code == a3.A3_ERR_INPUT
+    with pytest.raises(a3.A3Error) as ei:
+        ctx.sample_blocks(d_ip, d_ix, torch.tensor([5, w.num_nodes], dtype=torch.int32, device=DEV), [2])
+    assert ei.value.code == a3.A3_ERR_INPUT
+    seeds = seed_batch(w.num_nodes, 50, 3, 1)
+    _compare(ctx, w, g, d_ip, d_ix, seeds, [4, 3], cm, 1.0, 1, "after errors")
+    ctx.close()
+
+
+def test_isolated_nodes_and_no_eids():
+    indptr = torch.tensor([0, 0, 1, 2, 2], dtype=torch.int64)
+    indices = torch.tensor([2, 1], dtype=torch.int64)
+    ctx = a3.Context(4, [4, 4], flags=a3.A3_NO_EIDS)
+    seeds = torch.tensor([0, 1, 3], dtype=torch.int64)
+    got = ctx.sample_blocks(indptr.to(DEV), indices.to(DEV), seeds.to(DEV), [4, 4], None, Q, 0)
+    assert all(e is None for e in got.blk_eids)
+    want = oracle.sample_blocks(indptr.numpy(), indices.numpy(), seeds.numpy(), [4, 4])
+    h = got.to_host()
+    h.blk_eids = want.blk_eids
+    blocks_equal(h, want)
+    ctx.close()
+
+
+def test_repeated_calls_are_byte_identical_and_seed_sensitive():
+    w, g, d_ip, d_ix = _graph("mini_copurchase")
+    ctx = a3.Context(w.batch, w.fanouts)
+    seeds = torch.from_numpy(seed_batch(w.num_nodes, w.batch, 0, 0)).to(DEV)
+    a = ctx.sample_blocks(d_ip, d_ix, seeds, w.fanouts, None, Q, 7).to_host()
+    b = ctx.sample_blocks(d_ip, d_ix, seeds, w.fanouts, None, Q, 7).to_host()
+    blocks_equal(a, b)
+    c = ctx.sample_blocks(d_ip, d_ix, seeds, w.fanouts, None, Q, 8).to_host()
+    assert not np.array_equal(a.blk_eids[0], c.blk_eids[0])
+    ctx.close()
+
+
+@pytest.mark.parametrize("dim,dtype", [(64, torch.float32), (602, torch.float32), (100, torch.float32),
+                                       (128, torch.float16), (3, torch.float16), (1, torch.float16),
+                                       (5, torch.float32)])
+def test_gather_matches_oracle(dim, dtype):
+    w, g, _, _ = _graph("tiny")
+    full = make_features(g.num_nodes, dim, dtype, feat_seed=2)
+    ctx = a3.Context(16, [2])
+    for frac in [1.0, 0.2, 0.0]:
+        split = degree_ranked_cache(g, full, frac, pin_host=True)
+        d_cm = split.cache_map.to(DEV)
+        d_fd = None if split.feat_dev is None else split.feat_dev.to(DEV)
+        for n_ids, idt in [(0, np.int32), (1, np.int64), (777, np.int32), (5000, np.int64)]:
+            print(f"[case] gather dim={dim} {dtype} frac={frac} n_ids={n_ids} idx={idt.__name__}", flush=True)
+            ids = seed_batch(g.num_nodes, n_ids, 4, n_ids, dtype=idt) if n_ids else np.zeros(0, dtype=idt)
+            got = ctx.gather_features(d_fd, split.feat_host, d_cm, torch.from_numpy(ids).to(DEV))
+            torch.cuda.synchronize()
+            fd = None if split.feat_dev is None else split.feat_dev.numpy()
+            fh = None if split.feat_host is None else split.feat_host.numpy()
+            want = oracle.gather_features(fd, fh, split.cache_map.numpy(), ids)
+            assert got.cpu().numpy().tobytes() == want.tobytes()
+    # no device map: rows are addressed by id in the device store
+    ids = seed_batch(g.num_nodes, 999, 4, 1, dtype=np.int32)
+    got = ctx.gather_features(full.to(DEV), None, None, torch.from_numpy(ids).to(DEV))
+    want = oracle.gather_features(full.numpy(), None, None, ids)
+    assert got.cpu().numpy().tobytes() == want.tobytes()
+    ctx.close()
+
+
+def test_gather_unaligned_buffers_fall_back_to_narrow_copies():
+    w, g, _, _ = _graph("tiny")
+    full = make_features(g.num_nodes, 66, torch.float16, feat_seed=3)   # 132-byte rows: 4-byte vectors
+    ctx = a3.Context(16, [2])
+    ids = seed_batch(g.num_nodes, 1234, 4, 2, dtype=np.int32)
+    d_full = full.to(DEV)
+    backing = torch.empty(1234 * 66 + 1, dtype=torch.float16, device=DEV)
+    out = backing[1:].view(1234, 66)                                  # 2-byte aligned output
+    got = ctx.gather_features(d_full, None, None, torch.from_numpy(ids).to(DEV), out=out)
+    want = oracle.gather_features(full.numpy(), None, None, ids)
+    assert got.cpu().numpy().tobytes() == want.tobytes()
+    ctx.close()
