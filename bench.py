@@ -33,6 +33,9 @@ def parse():
                    help="budget of the oracle (CPU baseline) leg; 0 disables it")
     p.add_argument("--traffic-bytes", type=float, default=None,
                    help="measured HBM bytes per gather launch (from rocprofv3 --pmc), if known")
+    p.add_argument("--pmc-calibration", action="store_true",
+                   help="also run plain device copies of 256 MiB (a known size) so that a rocprofv3 "
+                        "--pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
     return p.parse_args()
 
 
@@ -76,7 +79,7 @@ def main():
     ib = stats["idx_bytes"]
     row_bytes = w.row_bytes
 
-    ctx = a3.Context(batch, w.fanouts)
+    ctx = a3.Context(batch, w.fanouts, flags=a3.A3_PROFILE)
     bias_q16 = int(round(gamma * 65536))
     # output rows: at most every node, at most seeds x prod(1 + fanout)
     cap_rows = batch
@@ -85,42 +88,45 @@ def main():
     cap_rows = min(cap_rows, w.num_nodes)
     out = torch.empty((cap_rows, w.feat_dim), dtype=w.feat_dtype, device=dev)
 
-    ev = lambda: torch.cuda.Event(enable_timing=True)
-    n_edges = n_in = n_cached_in = 0
-    marks = []
+    n_edges = n_in = 0
+    last_ids = None
 
     def step(b, timed):
-        nonlocal n_edges, n_in, n_cached_in
-        e0, e1, e2 = (ev(), ev(), ev()) if timed else (None, None, None)
-        if timed:
-            e0.record()
+        nonlocal n_edges, n_in, last_ids
         blocks = ctx.sample_blocks(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b)
-        if timed:
-            e1.record()
         rows = blocks.n_src[-1]
         ctx.gather_features(split.feat_dev, split.feat_host, d_cm, blocks.input_nodes, out=out[:rows])
         if timed:
-            e2.record()
-            marks.append((e0, e1, e2, rows, sum(blocks.n_edges), blocks.input_nodes))
             n_edges += sum(blocks.n_edges)
             n_in += rows
+            last_ids = blocks.input_nodes
         return blocks
 
+    if args.pmc_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for b in range(W):
         step(b, False)
     torch.cuda.synchronize()
+    ctx.profile_read(0), ctx.profile_read(1)   # drop the warm-up calls' timings
     t0 = time.perf_counter()
     for b in range(W, W + K):
         step(b, True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     total_s = t1 - t0
-    ms_sample = sum(m[0].elapsed_time(m[1]) for m in marks)
-    ms_gather = sum(m[1].elapsed_time(m[2]) for m in marks)
+    # device time of each call's kernels, from HIP events the library records on its stream
+    ms_s, ms_g = ctx.profile_read(0), ctx.profile_read(1)
+    assert len(ms_s) == len(ms_g) == min(K, a3.A3_PROFILE_DEPTH)
+    ms_sample = sum(ms_s) * K / len(ms_s)
+    ms_gather = sum(ms_g) * K / len(ms_g)
     # hit rate of the last timed batch (outside the timed region)
-    last_ids = marks[-1][5].long()
-    hit_rate = float((d_cm[last_ids] >= 0).float().mean().item()) if last_ids.numel() else 1.0
-    cached_rows = n_in * hit_rate  # rows served from HBM (exact when the cache holds everything)
+    ids_l = last_ids.long()
+    hit_rate = float((d_cm[ids_l] >= 0).float().mean().item()) if ids_l.numel() else 1.0
 
     gather_payload_gbps = n_in * row_bytes / (ms_gather * 1e-3) / 1e9
     algo_bytes_per_launch = (n_in / K) * (2 * row_bytes + ib + 4)

@@ -47,6 +47,8 @@ extern "C" {
 #define A3_NO_EIDS 2u        /* do not produce blk_eids */
 #define A3_HOST_ONLY 4u      /* no device: calls validate their arguments, then fail with A3_ERR_HIP */
 #define A3_FORCE_RADIX 8u    /* testing: always use the exhaustive selection path */
+#define A3_PROFILE 16u       /* bracket the kernels of every call with HIP events (see a3_profile_read) */
+#define A3_PROFILE_DEPTH 256 /* calls remembered per kind */
 
 typedef struct a3_ctx a3_ctx;
 
@@ -124,6 +126,14 @@ int a3_sample_blocks(a3_ctx* ctx, const int64_t* indptr, const void* indices, in
 int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
                        const int32_t* cache_map, const void* ids, int32_t idx_bytes, int64_t n_ids,
                        int64_t row_bytes, void* out);
+
+/* Measurement aid (Sec. IV-A reports averages over runs; this gives per-call device times).
+ * With A3_PROFILE every a3_sample_blocks (kind 0) and a3_gather_features (kind 1) brackets its
+ * kernels with HIP events on the context's stream.  a3_profile_read waits for the newest event
+ * and returns the device durations in milliseconds of the calls made since the previous read of
+ * that kind, oldest first: ms (host) receives min(*n, max) values; at most A3_PROFILE_DEPTH calls
+ * per kind are remembered.  A3_ERR_INVALID_ARG without A3_PROFILE. */
+int a3_profile_read(a3_ctx* ctx, int kind, float* ms, int max, int* n);
 
 #ifdef __cplusplus
 }

@@ -13,7 +13,8 @@ import torch
 A3_MAX_HOPS = 8
 A3_MAX_FANOUT = 1024
 A3_OK, A3_ERR_INVALID_ARG, A3_ERR_CAPACITY, A3_ERR_HIP, A3_ERR_INPUT = 0, -1, -2, -3, -4
-A3_VALIDATE, A3_NO_EIDS, A3_HOST_ONLY, A3_FORCE_RADIX = 1, 2, 4, 8
+A3_VALIDATE, A3_NO_EIDS, A3_HOST_ONLY, A3_FORCE_RADIX, A3_PROFILE = 1, 2, 4, 8, 16
+A3_PROFILE_DEPTH = 256
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _lib = None
@@ -61,6 +62,9 @@ def lib():
         L.a3_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_int32, C.c_int64, C.c_int64, C.c_void_p]
         L.a3_gather_features.restype = C.c_int
+        L.a3_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float), C.c_int,
+                                      C.POINTER(C.c_int)]
+        L.a3_profile_read.restype = C.c_int
         _lib = L
     return _lib
 
@@ -145,6 +149,13 @@ class Context:
 
     def set_stream(self, stream: int):
         self._check(lib().a3_set_stream(self._h, C.c_void_p(stream)))
+
+    def profile_read(self, kind: int) -> List[float]:
+        """device milliseconds of the calls of this kind (0 sample, 1 gather) since the last read"""
+        buf = (C.c_float * A3_PROFILE_DEPTH)()
+        n = C.c_int(0)
+        self._check(lib().a3_profile_read(self._h, kind, buf, A3_PROFILE_DEPTH, C.byref(n)))
+        return [float(buf[i]) for i in range(n.value)]
 
     def sample_blocks(self, indptr: torch.Tensor, indices: torch.Tensor, seeds: torch.Tensor,
                       fanouts: Sequence[int], cache_map: Optional[torch.Tensor] = None,

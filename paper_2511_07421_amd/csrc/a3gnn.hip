@@ -45,6 +45,10 @@ struct a3_ctx {
   DevState* h_state = nullptr;  // pinned
   std::vector<void*> allocs;
   std::string err;
+  // A3_PROFILE: rings of (start, stop) events per kind of call
+  hipEvent_t prof_ev[2][A3_PROFILE_DEPTH][2] = {};
+  int64_t prof_written[2] = {0, 0};
+  int64_t prof_read[2] = {0, 0};
 };
 
 namespace {
@@ -97,7 +101,22 @@ size_t sample_lds_bytes(int32_t fanout, bool weighted) {
   return entries * sizeof(uint64_t);
 }
 
+// A3_PROFILE: record the start (which = 0) or stop (which = 1) event of the running call
+void prof_mark(a3_ctx* ctx, int kind, int which) {
+  if (!(ctx->flags & A3_PROFILE)) return;
+  const int slot = (int)(ctx->prof_written[kind] % A3_PROFILE_DEPTH);
+  (void)hipEventRecord(ctx->prof_ev[kind][slot][which], ctx->stream);
+  if (which == 1) ctx->prof_written[kind]++;
+}
+
 void free_all(a3_ctx* ctx) {
+  for (auto& kind : ctx->prof_ev)
+    for (auto& pair : kind)
+      for (auto& ev : pair)
+        if (ev) {
+          (void)hipEventDestroy(ev);
+          ev = nullptr;
+        }
   for (void* p : ctx->allocs) (void)hipFree(p);
   ctx->allocs.clear();
   if (ctx->node_map) (void)hipFree(ctx->node_map);
@@ -154,6 +173,7 @@ int sample_impl(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int64_t
   if (rc != A3_OK) return rc;
   ctx->node_map_dirty = true;  // until the call has cleaned up after itself
 
+  prof_mark(ctx, 0, 0);
   hipLaunchKernelGGL(a3::k_init_seeds<IdxT>, dim3(blocks_for(num_seeds, 256)), dim3(256), 0, st,
                      seeds, num_seeds, num_nodes, S, ctx->node_map, ds, validate);
   if (validate) {
@@ -212,6 +232,7 @@ int sample_impl(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int64_t
   // leave the relabel map empty for the next call
   hipLaunchKernelGGL(a3::k_reset_map<IdxT>, dim3(blocks_for(bound_dst[num_hops], 256)), dim3(256),
                      0, st, S, ds, num_hops - 1, num_nodes, ctx->node_map);
+  prof_mark(ctx, 0, 1);
   A3_HIP(ctx, hipGetLastError());
   A3_HIP(ctx, hipMemcpyAsync(ctx->h_state, ds, sizeof(DevState), hipMemcpyDeviceToHost, st));
   A3_HIP(ctx, hipStreamSynchronize(st));
@@ -329,6 +350,15 @@ extern "C" int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t
     chk(dev_alloc(ctx, &ctx->blk_indices[h], ctx->cap_edges[h]));
     if (!(flags & A3_NO_EIDS)) chk(dev_alloc(ctx, &ctx->blk_eids[h], ctx->cap_edges[h]));
   }
+  if (rc == A3_OK && (flags & A3_PROFILE)) {
+    for (auto& kind : ctx->prof_ev)
+      for (auto& pair : kind)
+        for (auto& ev : pair)
+          if (rc == A3_OK) {
+            e = hipEventCreate(&ev);
+            if (e != hipSuccess) rc = hip_fail(ctx, e, "a3_create: hipEventCreate");
+          }
+  }
   if (rc == A3_OK) {
     void* hp = nullptr;
     e = hipHostMalloc(&hp, sizeof(DevState), hipHostMallocDefault);
@@ -439,10 +469,32 @@ extern "C" int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void*
   while (width > 2 && (align_bits & (uintptr_t)(width - 1))) width >>= 1;
   if (align_bits & 1)
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: buffers must be 2-byte aligned");
+  prof_mark(ctx, 1, 0);
   if (idx_bytes == 4)
     gather_by_width<int32_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out);
   else
     gather_by_width<int64_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out);
+  prof_mark(ctx, 1, 1);
   A3_HIP(ctx, hipGetLastError());
+  return A3_OK;
+}
+
+extern "C" int a3_profile_read(a3_ctx* ctx, int kind, float* ms, int max, int* n) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_profile_read: ctx is null");
+  if (!(ctx->flags & A3_PROFILE) || (ctx->flags & A3_HOST_ONLY))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_profile_read: context was created without A3_PROFILE");
+  if (kind < 0 || kind > 1 || !n || max < 0 || (max > 0 && !ms))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_profile_read: bad argument");
+  A3_HIP(ctx, hipSetDevice(ctx->device));
+  int64_t first = std::max(ctx->prof_read[kind], ctx->prof_written[kind] - A3_PROFILE_DEPTH);
+  int count = 0;
+  for (int64_t c = first; c < ctx->prof_written[kind] && count < max; ++c, ++count) {
+    const int slot = (int)(c % A3_PROFILE_DEPTH);
+    A3_HIP(ctx, hipEventSynchronize(ctx->prof_ev[kind][slot][1]));
+    A3_HIP(ctx, hipEventElapsedTime(&ms[count], ctx->prof_ev[kind][slot][0],
+                                    ctx->prof_ev[kind][slot][1]));
+  }
+  ctx->prof_read[kind] = first + count;
+  *n = count;
   return A3_OK;
 }
