@@ -90,26 +90,69 @@ def _view(ptr, n: int, dtype: torch.dtype, device) -> torch.Tensor:
     return torch.as_tensor(_DevView(int(ptr), int(n), typestr), device=device)
 
 
-@dataclass
 class Blocks:
-    """Views into context-owned device memory: valid until the next sample_blocks on the context."""
+    """Result of Context.sample_blocks.  Counts are plain ints; the arrays are zero-copy tensor
+    views of context-owned device memory, created on first access and valid until the next
+    sample_blocks on the context."""
+
+    def __init__(self, cb: "_CBlocks", idx_dtype: torch.dtype, device):
+        H = cb.num_hops
+        self.num_hops = H
+        self.n_dst = list(cb.n_dst[:H])
+        self.n_src = list(cb.n_src[:H])
+        self.n_edges = list(cb.n_edges[:H])
+        self._ptr_indptr = list(cb.blk_indptr[:H])
+        self._ptr_indices = list(cb.blk_indices[:H])
+        self._ptr_eids = list(cb.blk_eids[:H])
+        self._ptr_input = cb.input_nodes
+        self._idx_dtype = idx_dtype
+        self._device = device
+        self._cache = {}
+
+    def _get(self, name, make):
+        if name not in self._cache:
+            self._cache[name] = make()
+        return self._cache[name]
+
+    @property
+    def blk_indptr(self) -> List[torch.Tensor]:
+        return self._get("indptr", lambda: [_view(p, n + 1, torch.int32, self._device)
+                                            for p, n in zip(self._ptr_indptr, self.n_dst)])
+
+    @property
+    def blk_indices(self) -> List[torch.Tensor]:
+        return self._get("indices", lambda: [_view(p, n, torch.int32, self._device)
+                                             for p, n in zip(self._ptr_indices, self.n_edges)])
+
+    @property
+    def blk_eids(self) -> List[Optional[torch.Tensor]]:
+        return self._get("eids", lambda: [None if not p else _view(p, n, torch.int64, self._device)
+                                          for p, n in zip(self._ptr_eids, self.n_edges)])
+
+    @property
+    def input_nodes(self) -> torch.Tensor:
+        return self._get("input", lambda: _view(self._ptr_input, self.n_src[-1], self._idx_dtype,
+                                                self._device))
+
+    def to_host(self) -> "HostBlocks":
+        """Independent host copies (numpy arrays), for comparisons."""
+        return HostBlocks(self.num_hops, list(self.n_dst), list(self.n_src), list(self.n_edges),
+                          [t.cpu().numpy() for t in self.blk_indptr],
+                          [t.cpu().numpy() for t in self.blk_indices],
+                          [None if t is None else t.cpu().numpy() for t in self.blk_eids],
+                          self.input_nodes.cpu().numpy())
+
+
+@dataclass
+class HostBlocks:
     num_hops: int
     n_dst: List[int]
     n_src: List[int]
     n_edges: List[int]
-    blk_indptr: List[torch.Tensor] = field(default_factory=list)
-    blk_indices: List[torch.Tensor] = field(default_factory=list)
-    blk_eids: List[Optional[torch.Tensor]] = field(default_factory=list)
-    input_nodes: torch.Tensor = None
-
-    def to_host(self) -> "Blocks":
-        """Independent host copies (numpy arrays), for comparisons."""
-        b = Blocks(self.num_hops, list(self.n_dst), list(self.n_src), list(self.n_edges))
-        b.blk_indptr = [t.cpu().numpy() for t in self.blk_indptr]
-        b.blk_indices = [t.cpu().numpy() for t in self.blk_indices]
-        b.blk_eids = [None if t is None else t.cpu().numpy() for t in self.blk_eids]
-        b.input_nodes = self.input_nodes.cpu().numpy()
-        return b
+    blk_indptr: list = field(default_factory=list)
+    blk_indices: list = field(default_factory=list)
+    blk_eids: list = field(default_factory=list)
+    input_nodes: object = None
 
 
 def _dptr(t: Optional[torch.Tensor]):
@@ -171,16 +214,7 @@ class Context:
                                     num_nodes, _dptr(seeds), seeds.shape[0], fan, len(fanouts),
                                     _dptr(cache_map), bias_q16, rng_seed, C.byref(cb))
         self._check(rc)
-        H = cb.num_hops
-        b = Blocks(H, list(cb.n_dst[:H]), list(cb.n_src[:H]), list(cb.n_edges[:H]))
-        dev = indices.device
-        for h in range(H):
-            b.blk_indptr.append(_view(cb.blk_indptr[h], b.n_dst[h] + 1, torch.int32, dev))
-            b.blk_indices.append(_view(cb.blk_indices[h], b.n_edges[h], torch.int32, dev))
-            b.blk_eids.append(None if not cb.blk_eids[h] else
-                              _view(cb.blk_eids[h], b.n_edges[h], torch.int64, dev))
-        b.input_nodes = _view(cb.input_nodes, b.n_src[H - 1], indices.dtype, dev)
-        return b
+        return Blocks(cb, indices.dtype, indices.device)
 
     def gather_features(self, feat_dev: Optional[torch.Tensor], feat_host: Optional[torch.Tensor],
                         cache_map: Optional[torch.Tensor], ids: torch.Tensor,

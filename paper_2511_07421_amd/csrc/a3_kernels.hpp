@@ -530,49 +530,72 @@ __global__ void k_relabel(const IdxT* gid, const int32_t* first_pos, const int32
 }
 
 // ---------------------------------------------------------------------------
-// step a6: feature gather.  The output is seen as a flat array of n_ids * vecs_per_row vectors;
-// consecutive threads copy consecutive vectors, so stores are fully coalesced and loads are
-// coalesced inside each source row.
+// step a6: feature gather.  A group of G = 2^log2_g lanes copies R rows; a row is vecs_per_row
+// vectors of sizeof(VecT) bytes, G the smallest power of two that covers the row (at most 64).
+// Each lane first issues the loads of all its vectors of all R rows (R*U independent loads in
+// flight), then stores them; stores are streaming (the output is not read again by this kernel
+// and should not evict feature rows that the next mini-batch is likely to hit again).
+// With G = 64 the id and device-map lookups are wave-uniform and go through the scalar unit.
 // ---------------------------------------------------------------------------
 constexpr int kGatherThreads = 256;
-constexpr int kGatherUnroll = 8;
 
-template <typename VecT, typename IdxT>
+typedef uint32_t vec16_t __attribute__((ext_vector_type(4)));
+typedef uint32_t vec8_t __attribute__((ext_vector_type(2)));
+typedef uint32_t vec4_t;
+typedef uint16_t vec2_t;
+
+template <typename VecT, typename IdxT, int U, int R, bool kWaveRow>
 __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restrict__ feat_dev,
                                                            const char* __restrict__ feat_host,
                                                            const int32_t* __restrict__ cache_map,
                                                            const IdxT* __restrict__ ids,
                                                            int64_t n_ids, uint32_t vecs_per_row,
-                                                           int64_t row_bytes,
+                                                           int64_t row_bytes, int log2_g,
                                                            VecT* __restrict__ out) {
-  const int64_t total = n_ids * (int64_t)vecs_per_row;
-  const int64_t g0 = (int64_t)blockIdx.x * (kGatherThreads * kGatherUnroll);
-  const int64_t row0 = g0 / vecs_per_row;
-  const uint32_t col0 = (uint32_t)(g0 - row0 * vecs_per_row);
-  const char* src[kGatherUnroll];
-  bool live[kGatherUnroll];
+  const uint32_t G = 1u << log2_g;
+  const uint32_t lane = threadIdx.x & (G - 1);
+  const int64_t group = ((int64_t)blockIdx.x * kGatherThreads + threadIdx.x) >> log2_g;
+  const int64_t r0 = group * R;
+  if (r0 >= n_ids) return;
+  const VecT* src[R];
 #pragma unroll
-  for (int k = 0; k < kGatherUnroll; ++k) {
-    const uint32_t off = col0 + (uint32_t)k * kGatherThreads + threadIdx.x;
-    const uint32_t dr = off / vecs_per_row;
-    const uint32_t c = off - dr * vecs_per_row;
-    const int64_t g = g0 + (int64_t)k * kGatherThreads + threadIdx.x;
-    live[k] = g < total;
-    src[k] = nullptr;
-    if (live[k]) {
-      const int64_t id = (int64_t)ids[row0 + dr];
-      const int64_t slot = cache_map ? (int64_t)cache_map[id] : id;
-      const char* rowp = slot >= 0 ? feat_dev + slot * row_bytes : feat_host + (-slot - 1) * row_bytes;
-      src[k] = rowp + (int64_t)c * (int64_t)sizeof(VecT);
+  for (int r = 0; r < R; ++r) {
+    const int64_t rr = (r0 + r < n_ids) ? r0 + r : n_ids - 1;
+    int64_t id = (int64_t)ids[rr];
+    if (kWaveRow) {
+      id = ((int64_t)__builtin_amdgcn_readfirstlane((int32_t)(id >> 32)) << 32) |
+           (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)id);
+    }
+    int64_t slot = id;
+    if (cache_map) {
+      int32_t c = cache_map[id];
+      if (kWaveRow) c = __builtin_amdgcn_readfirstlane(c);
+      slot = c;
+    }
+    const char* rowp = slot >= 0 ? feat_dev + slot * row_bytes : feat_host + (-slot - 1) * row_bytes;
+    src[r] = reinterpret_cast<const VecT*>(rowp);
+  }
+  for (uint32_t c0 = 0; c0 < vecs_per_row; c0 += G * U) {
+    VecT v[R][U];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int k = 0; k < U; ++k) {
+        const uint32_t c = c0 + (uint32_t)k * G + lane;
+        if (c < vecs_per_row) v[r][k] = src[r][c];
+      }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if (r0 + r < n_ids) {
+        VecT* dst = out + (r0 + r) * (int64_t)vecs_per_row;
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+          const uint32_t c = c0 + (uint32_t)k * G + lane;
+          if (c < vecs_per_row) __builtin_nontemporal_store(v[r][k], &dst[c]);
+        }
+      }
     }
   }
-  VecT val[kGatherUnroll];
-#pragma unroll
-  for (int k = 0; k < kGatherUnroll; ++k)
-    if (live[k]) val[k] = *reinterpret_cast<const VecT*>(src[k]);
-#pragma unroll
-  for (int k = 0; k < kGatherUnroll; ++k)
-    if (live[k]) out[g0 + (int64_t)k * kGatherThreads + threadIdx.x] = val[k];
 }
 
 }  // namespace a3

@@ -260,16 +260,39 @@ int sample_impl(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int64_t
   return A3_OK;
 }
 
+template <typename VecT, typename IdxT, int U, int R, bool kWaveRow>
+void launch_gather_as(a3_ctx* ctx, int log2_g, const void* feat_dev, const void* feat_host,
+                      const int32_t* cache_map, const void* ids, int64_t n_ids, int64_t row_bytes,
+                      uint32_t vpr, void* out) {
+  const int64_t groups = (n_ids + R - 1) / R;
+  const unsigned grid = blocks_for(groups << log2_g, a3::kGatherThreads);
+  hipLaunchKernelGGL((a3::k_gather<VecT, IdxT, U, R, kWaveRow>), dim3(grid),
+                     dim3(a3::kGatherThreads), 0, ctx->stream, (const char*)feat_dev,
+                     (const char*)feat_host, cache_map, (const IdxT*)ids, n_ids, vpr, row_bytes,
+                     log2_g, (VecT*)out);
+}
+
+// lanes per row: the smallest power of two covering the row's vectors, at most a wavefront;
+// vectors per lane and step U in {1,2,4,8}; rows per group chosen so that 4..8 loads are in flight
 template <typename VecT, typename IdxT>
 void launch_gather(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
                    const int32_t* cache_map, const void* ids, int64_t n_ids, int64_t row_bytes,
                    void* out) {
   const uint32_t vpr = (uint32_t)(row_bytes / (int64_t)sizeof(VecT));
-  const int64_t total = n_ids * (int64_t)vpr;
-  const unsigned grid = blocks_for(total, a3::kGatherThreads * a3::kGatherUnroll);
-  hipLaunchKernelGGL((a3::k_gather<VecT, IdxT>), dim3(grid), dim3(a3::kGatherThreads), 0,
-                     ctx->stream, (const char*)feat_dev, (const char*)feat_host, cache_map,
-                     (const IdxT*)ids, n_ids, vpr, row_bytes, (VecT*)out);
+  int log2_g = 0;
+  while (log2_g < 6 && (1u << log2_g) < vpr) ++log2_g;
+#define A3_GATHER(U, R, W) \
+  launch_gather_as<VecT, IdxT, U, R, W>(ctx, log2_g, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, vpr, out)
+  if (log2_g < 6) {
+    A3_GATHER(1, 4, false);
+  } else {
+    const uint32_t per_lane = (vpr + 63) / 64;
+    if (per_lane <= 1) A3_GATHER(1, 4, true);
+    else if (per_lane <= 2) A3_GATHER(2, 2, true);
+    else if (per_lane <= 4) A3_GATHER(4, 1, true);
+    else A3_GATHER(8, 1, true);
+  }
+#undef A3_GATHER
 }
 
 template <typename IdxT>
@@ -277,10 +300,10 @@ void gather_by_width(a3_ctx* ctx, int width, const void* feat_dev, const void* f
                      const int32_t* cache_map, const void* ids, int64_t n_ids, int64_t row_bytes,
                      void* out) {
   switch (width) {
-    case 16: launch_gather<uint4, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
-    case 8: launch_gather<uint2, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
-    case 4: launch_gather<uint32_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
-    default: launch_gather<uint16_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
+    case 16: launch_gather<a3::vec16_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
+    case 8: launch_gather<a3::vec8_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
+    case 4: launch_gather<a3::vec4_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
+    default: launch_gather<a3::vec2_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
   }
 }
 
