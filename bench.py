@@ -2,8 +2,9 @@
 """Benchmark of the A3GNN mini-batch hot path on one MI355X.
 
 A step is one pass of the whole path over one mini-batch of synthetic input that is already
-resident in HBM: a3_sample_blocks (frontier degrees, keyed selection, dedup/relabel into block
-CSRs, every hop) followed by a3_gather_features for the input nodes.  Prints ONE JSON line.
+resident in HBM: a3_sample_blocks_begin/_end (frontier degrees, keyed selection, dedup/relabel
+into block CSRs, every hop) and a3_gather_input_features for the input nodes.  Prints ONE JSON
+line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload social|copurchase|citation|tiny]
 """
@@ -93,9 +94,13 @@ def main():
 
     def step(b, timed):
         nonlocal n_edges, n_in, last_ids
-        blocks = ctx.sample_blocks(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b)
+        # queue sampling, then the gather of its input nodes (row count taken on the device),
+        # then wait for the sampling counts: the host never stalls the GPU between the two
+        ctx.sample_blocks_begin(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b)
+        ctx.gather_input_features(split.feat_dev, split.feat_host, d_cm, out)
+        blocks = ctx.sample_blocks_end()
         rows = blocks.n_src[-1]
-        ctx.gather_features(split.feat_dev, split.feat_host, d_cm, blocks.input_nodes, out=out[:rows])
+        assert rows <= cap_rows
         if timed:
             n_edges += sum(blocks.n_edges)
             n_in += rows

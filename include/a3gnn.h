@@ -111,6 +111,18 @@ int a3_sample_blocks(a3_ctx* ctx, const int64_t* indptr, const void* indices, in
                      const int32_t* fanouts, int32_t num_hops, const int32_t* cache_map,
                      uint32_t bias_q16, uint64_t rng_seed, a3_blocks* out);
 
+/* The same call split in two, so that the host does not wait between sampling and feature
+ * retrieve (Sec. III-B counts that wait as lost throughput).  a3_sample_blocks_begin checks the
+ * arguments exactly as a3_sample_blocks does, queues all work on the context's stream and
+ * returns; a3_sample_blocks_end waits for that work (not for anything queued after it), fills
+ * *out and reports A3_ERR_INPUT / A3_ERR_CAPACITY found on the device.  A begun call must be
+ * ended before the next begin (A3_ERR_INVALID_ARG otherwise).  a3_sample_blocks is begin + end. */
+int a3_sample_blocks_begin(a3_ctx* ctx, const int64_t* indptr, const void* indices,
+                           int32_t idx_bytes, int64_t num_nodes, const void* seeds,
+                           int64_t num_seeds, const int32_t* fanouts, int32_t num_hops,
+                           const int32_t* cache_map, uint32_t bias_q16, uint64_t rng_seed);
+int a3_sample_blocks_end(a3_ctx* ctx, a3_blocks* out);
+
 /* Feature retrieve (Alg. 0 line 10): out[i,:] = feat_dev[c,:] if
  * c = cache_map[ids[i]] >= 0, else feat_host[-c-1,:].
  *   feat_dev    device [n_cached, row_bytes]; may be NULL if no id maps to it.
@@ -126,6 +138,16 @@ int a3_sample_blocks(a3_ctx* ctx, const int64_t* indptr, const void* indices, in
 int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
                        const int32_t* cache_map, const void* ids, int32_t idx_bytes, int64_t n_ids,
                        int64_t row_bytes, void* out);
+
+/* Feature retrieve for the input nodes of the context's most recent a3_sample_blocks(_begin),
+ * i.e. ids = a3_blocks.input_nodes, with the row count taken on the device: it may be queued
+ * right after a3_sample_blocks_begin, before the host knows the count.
+ *   out        device [out_rows, row_bytes]; min(n_input_nodes, out_rows) rows are written, so
+ *              the caller compares a3_blocks.n_src[num_hops-1] with out_rows afterwards.
+ * Other arguments, errors and asynchrony as a3_gather_features. */
+int a3_gather_input_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
+                             const int32_t* cache_map, int64_t row_bytes, void* out,
+                             int64_t out_rows);
 
 /* Measurement aid (Sec. IV-A reports averages over runs; this gives per-call device times).
  * With A3_PROFILE every a3_sample_blocks (kind 0) and a3_gather_features (kind 1) brackets its

@@ -62,6 +62,13 @@ def lib():
         L.a3_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_int32, C.c_int64, C.c_int64, C.c_void_p]
         L.a3_gather_features.restype = C.c_int
+        L.a3_sample_blocks_begin.argtypes = L.a3_sample_blocks.argtypes[:-1]
+        L.a3_sample_blocks_begin.restype = C.c_int
+        L.a3_sample_blocks_end.argtypes = [C.c_void_p, C.POINTER(_CBlocks)]
+        L.a3_sample_blocks_end.restype = C.c_int
+        L.a3_gather_input_features.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                               C.c_int64, C.c_void_p, C.c_int64]
+        L.a3_gather_input_features.restype = C.c_int
         L.a3_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float), C.c_int,
                                       C.POINTER(C.c_int)]
         L.a3_profile_read.restype = C.c_int
@@ -215,6 +222,40 @@ class Context:
                                     _dptr(cache_map), bias_q16, rng_seed, C.byref(cb))
         self._check(rc)
         return Blocks(cb, indices.dtype, indices.device)
+
+    def sample_blocks_begin(self, indptr: torch.Tensor, indices: torch.Tensor, seeds: torch.Tensor,
+                            fanouts: Sequence[int], cache_map: Optional[torch.Tensor] = None,
+                            bias_q16: int = 65536, rng_seed: int = 0) -> None:
+        assert indptr.dtype == torch.int64 and indptr.is_contiguous()
+        assert indices.dtype in (torch.int32, torch.int64) and indices.is_contiguous()
+        assert seeds.dtype == indices.dtype and seeds.is_contiguous()
+        assert cache_map is None or (cache_map.dtype == torch.int32 and cache_map.is_contiguous())
+        fan = (C.c_int32 * len(fanouts))(*fanouts)
+        rc = lib().a3_sample_blocks_begin(self._h, _dptr(indptr), _dptr(indices),
+                                          indices.element_size(), indptr.shape[0] - 1, _dptr(seeds),
+                                          seeds.shape[0], fan, len(fanouts), _dptr(cache_map),
+                                          bias_q16, rng_seed)
+        self._check(rc)
+        self._begun = (indices.dtype, indices.device)
+
+    def sample_blocks_end(self) -> Blocks:
+        cb = _CBlocks()
+        self._check(lib().a3_sample_blocks_end(self._h, C.byref(cb)))
+        return Blocks(cb, *self._begun)
+
+    def gather_input_features(self, feat_dev: Optional[torch.Tensor],
+                              feat_host: Optional[torch.Tensor], cache_map: Optional[torch.Tensor],
+                              out: torch.Tensor) -> torch.Tensor:
+        """rows of the last sampled input nodes -> out[:n]; may be queued before sample_blocks_end"""
+        ref = feat_dev if feat_dev is not None else feat_host
+        assert ref is not None and ref.dim() == 2
+        assert feat_host is None or feat_host.is_pinned(), "feat_host must be pinned host memory"
+        assert out.is_contiguous() and out.dim() == 2 and out.shape[1] == ref.shape[1] and out.dtype == ref.dtype
+        row_bytes = ref.shape[1] * ref.element_size()
+        rc = lib().a3_gather_input_features(self._h, _dptr(feat_dev), _dptr(feat_host),
+                                            _dptr(cache_map), row_bytes, _dptr(out), out.shape[0])
+        self._check(rc)
+        return out
 
     def gather_features(self, feat_dev: Optional[torch.Tensor], feat_host: Optional[torch.Tensor],
                         cache_map: Optional[torch.Tensor], ids: torch.Tensor,

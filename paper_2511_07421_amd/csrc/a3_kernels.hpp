@@ -96,10 +96,12 @@ __global__ void k_gate_on_error(DevState* st) {
 }
 
 // undo the map entries of every node in S (all nodes the call touched)
+// and publish the call's counts to the host (host_state is pinned host memory)
 template <typename IdxT>
 __global__ void k_reset_map(const IdxT* S, const DevState* st, int last_hop, int64_t num_nodes,
-                            int32_t* node_map) {
+                            int32_t* node_map, DevState* host_state) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i == 0) *host_state = *st;
   const int64_t n = st->n_src[last_hop];
   if (i >= n) return;
   const int64_t v = (int64_t)S[i];
@@ -549,9 +551,17 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restric
                                                            const char* __restrict__ feat_host,
                                                            const int32_t* __restrict__ cache_map,
                                                            const IdxT* __restrict__ ids,
-                                                           int64_t n_ids, uint32_t vecs_per_row,
+                                                           int64_t n_ids,
+                                                           const int32_t* __restrict__ n_ids_dev,
+                                                           uint32_t vecs_per_row,
                                                            int64_t row_bytes, int log2_g,
                                                            VecT* __restrict__ out) {
+  // the row count may live on the device (gather queued before the host knows it); n_ids then
+  // is the launch bound and the output capacity
+  if (n_ids_dev) {
+    const int64_t n_dev = *n_ids_dev;
+    n_ids = n_dev < n_ids ? n_dev : n_ids;
+  }
   const uint32_t G = 1u << log2_g;
   const uint32_t lane = threadIdx.x & (G - 1);
   const int64_t group = ((int64_t)blockIdx.x * kGatherThreads + threadIdx.x) >> log2_g;

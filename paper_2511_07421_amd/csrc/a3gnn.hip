@@ -42,7 +42,13 @@ struct a3_ctx {
   int64_t node_map_cap = 0;
   bool node_map_dirty = false;
   DevState* d_state = nullptr;
-  DevState* h_state = nullptr;  // pinned
+  DevState* h_state = nullptr;      // pinned host copy of the counts, written by the last kernel
+  DevState* h_state_dev = nullptr;  // the same memory as the device addresses it
+  hipEvent_t sampled = nullptr;     // recorded after the last sampling kernel of a call
+  bool pending = false;             // a begun call has not been ended yet
+  int32_t last_hops = 0;            // shape of the most recent begun call
+  int32_t last_idx_bytes = 0;
+  int64_t last_bound_in = 0;        // launch bound on its number of input nodes
   std::vector<void*> allocs;
   std::string err;
   // A3_PROFILE: rings of (start, stop) events per kind of call
@@ -123,6 +129,8 @@ void free_all(a3_ctx* ctx) {
   ctx->node_map = nullptr;
   if (ctx->h_state) (void)hipHostFree(ctx->h_state);
   ctx->h_state = nullptr;
+  if (ctx->sampled) (void)hipEventDestroy(ctx->sampled);
+  ctx->sampled = nullptr;
 }
 
 int ensure_node_map(a3_ctx* ctx, int64_t num_nodes) {
@@ -149,9 +157,9 @@ int ensure_node_map(a3_ctx* ctx, int64_t num_nodes) {
 }
 
 template <typename IdxT>
-int sample_impl(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int64_t num_nodes,
-                const IdxT* seeds, int64_t num_seeds, const int32_t* fanouts, int32_t num_hops,
-                const int32_t* cache_map, uint32_t bias_q16, uint64_t rng_seed, a3_blocks* out) {
+int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int64_t num_nodes,
+                   const IdxT* seeds, int64_t num_seeds, const int32_t* fanouts, int32_t num_hops,
+                   const int32_t* cache_map, uint32_t bias_q16, uint64_t rng_seed) {
   hipStream_t st = ctx->stream;
   IdxT* S = (IdxT*)ctx->S;
   IdxT* gid = (IdxT*)ctx->gid;
@@ -229,13 +237,22 @@ int sample_impl(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int64_t
                        gid, ctx->first_pos, ctx->new_rank, ds, h, S, ctx->node_map,
                        ctx->blk_indices[h]);
   }
-  // leave the relabel map empty for the next call
+  // leave the relabel map empty for the next call; the same kernel publishes the counts
   hipLaunchKernelGGL(a3::k_reset_map<IdxT>, dim3(blocks_for(bound_dst[num_hops], 256)), dim3(256),
-                     0, st, S, ds, num_hops - 1, num_nodes, ctx->node_map);
+                     0, st, S, ds, num_hops - 1, num_nodes, ctx->node_map, ctx->h_state_dev);
   prof_mark(ctx, 0, 1);
   A3_HIP(ctx, hipGetLastError());
-  A3_HIP(ctx, hipMemcpyAsync(ctx->h_state, ds, sizeof(DevState), hipMemcpyDeviceToHost, st));
-  A3_HIP(ctx, hipStreamSynchronize(st));
+  A3_HIP(ctx, hipEventRecord(ctx->sampled, st));
+  ctx->pending = true;
+  ctx->last_hops = num_hops;
+  ctx->last_idx_bytes = (int32_t)sizeof(IdxT);
+  ctx->last_bound_in = bound_dst[num_hops];
+  return A3_OK;
+}
+
+int sample_finish(a3_ctx* ctx, a3_blocks* out) {
+  A3_HIP(ctx, hipEventSynchronize(ctx->sampled));
+  ctx->pending = false;
   const DevState& hs = *ctx->h_state;
   if (hs.error & (a3::kErrBadSeed | a3::kErrDupSeed)) {
     return fail(ctx, A3_ERR_INPUT,
@@ -246,6 +263,7 @@ int sample_impl(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int64_t
     return fail(ctx, A3_ERR_CAPACITY, "a3_sample_blocks: a CSR row has more than 2^31-1 entries");
   ctx->node_map_dirty = false;
 
+  const int num_hops = ctx->last_hops;
   std::memset(out, 0, sizeof(*out));
   out->num_hops = num_hops;
   for (int h = 0; h < num_hops; ++h) {
@@ -262,27 +280,27 @@ int sample_impl(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int64_t
 
 template <typename VecT, typename IdxT, int U, int R, bool kWaveRow>
 void launch_gather_as(a3_ctx* ctx, int log2_g, const void* feat_dev, const void* feat_host,
-                      const int32_t* cache_map, const void* ids, int64_t n_ids, int64_t row_bytes,
-                      uint32_t vpr, void* out) {
+                      const int32_t* cache_map, const void* ids, int64_t n_ids,
+                      const int32_t* n_ids_dev, int64_t row_bytes, uint32_t vpr, void* out) {
   const int64_t groups = (n_ids + R - 1) / R;
   const unsigned grid = blocks_for(groups << log2_g, a3::kGatherThreads);
   hipLaunchKernelGGL((a3::k_gather<VecT, IdxT, U, R, kWaveRow>), dim3(grid),
                      dim3(a3::kGatherThreads), 0, ctx->stream, (const char*)feat_dev,
-                     (const char*)feat_host, cache_map, (const IdxT*)ids, n_ids, vpr, row_bytes,
-                     log2_g, (VecT*)out);
+                     (const char*)feat_host, cache_map, (const IdxT*)ids, n_ids, n_ids_dev, vpr,
+                     row_bytes, log2_g, (VecT*)out);
 }
 
 // lanes per row: the smallest power of two covering the row's vectors, at most a wavefront;
 // vectors per lane and step U in {1,2,4,8}; rows per group chosen so that 4..8 loads are in flight
 template <typename VecT, typename IdxT>
 void launch_gather(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
-                   const int32_t* cache_map, const void* ids, int64_t n_ids, int64_t row_bytes,
-                   void* out) {
+                   const int32_t* cache_map, const void* ids, int64_t n_ids,
+                   const int32_t* n_ids_dev, int64_t row_bytes, void* out) {
   const uint32_t vpr = (uint32_t)(row_bytes / (int64_t)sizeof(VecT));
   int log2_g = 0;
   while (log2_g < 6 && (1u << log2_g) < vpr) ++log2_g;
 #define A3_GATHER(U, R, W) \
-  launch_gather_as<VecT, IdxT, U, R, W>(ctx, log2_g, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, vpr, out)
+  launch_gather_as<VecT, IdxT, U, R, W>(ctx, log2_g, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, vpr, out)
   if (log2_g < 6) {
     A3_GATHER(1, 4, false);
   } else {
@@ -297,14 +315,48 @@ void launch_gather(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
 
 template <typename IdxT>
 void gather_by_width(a3_ctx* ctx, int width, const void* feat_dev, const void* feat_host,
-                     const int32_t* cache_map, const void* ids, int64_t n_ids, int64_t row_bytes,
-                     void* out) {
+                     const int32_t* cache_map, const void* ids, int64_t n_ids,
+                     const int32_t* n_ids_dev, int64_t row_bytes, void* out) {
   switch (width) {
-    case 16: launch_gather<a3::vec16_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
-    case 8: launch_gather<a3::vec8_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
-    case 4: launch_gather<a3::vec4_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
-    default: launch_gather<a3::vec2_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out); break;
+    case 16: launch_gather<a3::vec16_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, out); break;
+    case 8: launch_gather<a3::vec8_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, out); break;
+    case 4: launch_gather<a3::vec4_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, out); break;
+    default: launch_gather<a3::vec2_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, out); break;
   }
+}
+
+// shared by the two gather entry points; arguments already validated
+int gather_enqueue(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
+                   const int32_t* cache_map, const void* ids, int32_t idx_bytes, int64_t n_ids,
+                   const int32_t* n_ids_dev, int64_t row_bytes, void* out) {
+  // widest vector that divides the row and keeps every row start aligned in all three buffers
+  const uintptr_t align_bits = (uintptr_t)feat_dev | (uintptr_t)feat_host | (uintptr_t)out |
+                               (uintptr_t)row_bytes;
+  if (align_bits & 1)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: buffers must be 2-byte aligned");
+  int width = 16;
+  while (width > 2 && (align_bits & (uintptr_t)(width - 1))) width >>= 1;
+  prof_mark(ctx, 1, 0);
+  if (idx_bytes == 4)
+    gather_by_width<int32_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, out);
+  else
+    gather_by_width<int64_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, out);
+  prof_mark(ctx, 1, 1);
+  A3_HIP(ctx, hipGetLastError());
+  return A3_OK;
+}
+
+int check_gather_args(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
+                      const int32_t* cache_map, int64_t row_bytes) {
+  if (row_bytes <= 0 || (row_bytes & 1))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: row_bytes must be positive and even");
+  if (row_bytes > (1ll << 30))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: row_bytes above 2^30");
+  if (!feat_dev && !feat_host)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: both feature stores are null");
+  if (!cache_map && !feat_dev)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: no device map needs feat_dev");
+  return A3_OK;
 }
 
 }  // namespace
@@ -384,11 +436,23 @@ extern "C" int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t
   }
   if (rc == A3_OK) {
     void* hp = nullptr;
-    e = hipHostMalloc(&hp, sizeof(DevState), hipHostMallocDefault);
+    e = hipHostMalloc(&hp, sizeof(DevState), hipHostMallocMapped);
     if (e != hipSuccess)
       rc = hip_fail(ctx, e, "a3_create: hipHostMalloc");
     else
       ctx->h_state = (DevState*)hp;
+  }
+  if (rc == A3_OK) {
+    void* dp = nullptr;
+    e = hipHostGetDevicePointer(&dp, ctx->h_state, 0);
+    if (e != hipSuccess)
+      rc = hip_fail(ctx, e, "a3_create: hipHostGetDevicePointer");
+    else
+      ctx->h_state_dev = (DevState*)dp;
+  }
+  if (rc == A3_OK) {
+    e = hipEventCreateWithFlags(&ctx->sampled, hipEventDisableTiming);
+    if (e != hipSuccess) rc = hip_fail(ctx, e, "a3_create: hipEventCreate");
   }
   if (rc != A3_OK) {
     g_create_err = ctx->err;
@@ -421,13 +485,14 @@ extern "C" int a3_set_stream(a3_ctx* ctx, void* hip_stream) {
   return A3_OK;
 }
 
-extern "C" int a3_sample_blocks(a3_ctx* ctx, const int64_t* indptr, const void* indices,
-                                int32_t idx_bytes, int64_t num_nodes, const void* seeds,
-                                int64_t num_seeds, const int32_t* fanouts, int32_t num_hops,
-                                const int32_t* cache_map, uint32_t bias_q16, uint64_t rng_seed,
-                                a3_blocks* out) {
+extern "C" int a3_sample_blocks_begin(a3_ctx* ctx, const int64_t* indptr, const void* indices,
+                                      int32_t idx_bytes, int64_t num_nodes, const void* seeds,
+                                      int64_t num_seeds, const int32_t* fanouts, int32_t num_hops,
+                                      const int32_t* cache_map, uint32_t bias_q16,
+                                      uint64_t rng_seed) {
   if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_sample_blocks: ctx is null");
-  if (!out) return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: out is null");
+  if (ctx->pending)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks_begin: the previous call was not ended");
   if (!indptr) return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: indptr is null");
   if (!fanouts) return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: fanouts is null");
   if (idx_bytes != 4 && idx_bytes != 8)
@@ -456,12 +521,33 @@ extern "C" int a3_sample_blocks(a3_ctx* ctx, const int64_t* indptr, const void* 
     return fail(ctx, A3_ERR_HIP, "a3_sample_blocks: context was created without a device");
   A3_HIP(ctx, hipSetDevice(ctx->device));
   if (idx_bytes == 4)
-    return sample_impl<int32_t>(ctx, indptr, (const int32_t*)indices, num_nodes,
-                                (const int32_t*)seeds, num_seeds, fanouts, num_hops, cache_map,
-                                bias_q16, rng_seed, out);
-  return sample_impl<int64_t>(ctx, indptr, (const int64_t*)indices, num_nodes,
-                              (const int64_t*)seeds, num_seeds, fanouts, num_hops, cache_map,
-                              bias_q16, rng_seed, out);
+    return sample_enqueue<int32_t>(ctx, indptr, (const int32_t*)indices, num_nodes,
+                                   (const int32_t*)seeds, num_seeds, fanouts, num_hops, cache_map,
+                                   bias_q16, rng_seed);
+  return sample_enqueue<int64_t>(ctx, indptr, (const int64_t*)indices, num_nodes,
+                                 (const int64_t*)seeds, num_seeds, fanouts, num_hops, cache_map,
+                                 bias_q16, rng_seed);
+}
+
+extern "C" int a3_sample_blocks_end(a3_ctx* ctx, a3_blocks* out) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_sample_blocks_end: ctx is null");
+  if (!out) return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: out is null");
+  if (!ctx->pending)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks_end: no call was begun");
+  A3_HIP(ctx, hipSetDevice(ctx->device));
+  return sample_finish(ctx, out);
+}
+
+extern "C" int a3_sample_blocks(a3_ctx* ctx, const int64_t* indptr, const void* indices,
+                                int32_t idx_bytes, int64_t num_nodes, const void* seeds,
+                                int64_t num_seeds, const int32_t* fanouts, int32_t num_hops,
+                                const int32_t* cache_map, uint32_t bias_q16, uint64_t rng_seed,
+                                a3_blocks* out) {
+  if (ctx && !out) return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks: out is null");
+  const int rc = a3_sample_blocks_begin(ctx, indptr, indices, idx_bytes, num_nodes, seeds,
+                                        num_seeds, fanouts, num_hops, cache_map, bias_q16, rng_seed);
+  if (rc != A3_OK) return rc;
+  return a3_sample_blocks_end(ctx, out);
 }
 
 extern "C" int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
@@ -473,33 +559,37 @@ extern "C" int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void*
   if (n_ids < 0) return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: n_ids < 0");
   if (row_bytes <= 0 || (row_bytes & 1))
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: row_bytes must be positive and even");
-  if (row_bytes > (1ll << 30))
-    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: row_bytes above 2^30");
   if (n_ids > 0 && (!ids || !out))
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: ids or out is null");
-  if (n_ids > 0 && !feat_dev && !feat_host)
-    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: both feature stores are null");
-  if (n_ids > 0 && !cache_map && !feat_dev)
-    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: no device map needs feat_dev");
+  if (n_ids > 0) {
+    const int rc = check_gather_args(ctx, feat_dev, feat_host, cache_map, row_bytes);
+    if (rc != A3_OK) return rc;
+  }
   if (ctx->flags & A3_HOST_ONLY)
     return fail(ctx, A3_ERR_HIP, "a3_gather_features: context was created without a device");
   if (n_ids == 0) return A3_OK;
   A3_HIP(ctx, hipSetDevice(ctx->device));
-  // widest vector that divides the row and keeps every row start aligned in all three buffers
-  const uintptr_t align_bits = (uintptr_t)feat_dev | (uintptr_t)feat_host | (uintptr_t)out |
-                               (uintptr_t)row_bytes;
-  int width = 16;
-  while (width > 2 && (align_bits & (uintptr_t)(width - 1))) width >>= 1;
-  if (align_bits & 1)
-    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: buffers must be 2-byte aligned");
-  prof_mark(ctx, 1, 0);
-  if (idx_bytes == 4)
-    gather_by_width<int32_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out);
-  else
-    gather_by_width<int64_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, row_bytes, out);
-  prof_mark(ctx, 1, 1);
-  A3_HIP(ctx, hipGetLastError());
-  return A3_OK;
+  return gather_enqueue(ctx, feat_dev, feat_host, cache_map, ids, idx_bytes, n_ids, nullptr,
+                        row_bytes, out);
+}
+
+extern "C" int a3_gather_input_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
+                                        const int32_t* cache_map, int64_t row_bytes, void* out,
+                                        int64_t out_rows) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_gather_input_features: ctx is null");
+  if (out_rows < 0 || (out_rows > 0 && !out))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_input_features: bad output buffer");
+  const int rc = check_gather_args(ctx, feat_dev, feat_host, cache_map, row_bytes);
+  if (rc != A3_OK) return rc;
+  if (ctx->flags & A3_HOST_ONLY)
+    return fail(ctx, A3_ERR_HIP, "a3_gather_features: context was created without a device");
+  if (ctx->last_hops == 0)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_input_features: nothing was sampled yet");
+  const int64_t bound = std::min(ctx->last_bound_in, out_rows);
+  if (bound == 0) return A3_OK;
+  A3_HIP(ctx, hipSetDevice(ctx->device));
+  return gather_enqueue(ctx, feat_dev, feat_host, cache_map, ctx->S, ctx->last_idx_bytes, bound,
+                        &ctx->d_state->n_src[ctx->last_hops - 1], row_bytes, out);
 }
 
 extern "C" int a3_profile_read(a3_ctx* ctx, int kind, float* ms, int max, int* n) {

@@ -156,6 +156,38 @@ def test_gather_matches_oracle(dim, dtype):
     ctx.close()
 
 
+def test_split_call_and_device_count_gather_match_oracle():
+    """begin -> gather of the input nodes (count read on the device) -> end"""
+    w, g, d_ip, d_ix = _graph("mini_copurchase")
+    full = make_features(g.num_nodes, w.feat_dim, w.feat_dtype, feat_seed=5)
+    split = degree_ranked_cache(g, full, 0.2, pin_host=True)
+    d_cm, d_fd = split.cache_map.to(DEV), split.feat_dev.to(DEV)
+    ctx = a3.Context(w.batch, w.fanouts)
+    with pytest.raises(a3.A3Error):
+        ctx.sample_blocks_end()                      # nothing begun
+    with pytest.raises(a3.A3Error):
+        ctx.gather_input_features(d_fd, split.feat_host, d_cm,
+                                  torch.empty((4, w.feat_dim), dtype=w.feat_dtype, device=DEV))
+    for b, cap in [(0, 200_000), (1, 200_000), (2, 1000)]:
+        seeds = seed_batch(w.num_nodes, w.batch, 0, b)
+        out = torch.full((cap, w.feat_dim), 7.0, dtype=w.feat_dtype, device=DEV)
+        ctx.sample_blocks_begin(d_ip, d_ix, torch.from_numpy(seeds).to(DEV), w.fanouts, d_cm, 4 * Q, b)
+        with pytest.raises(a3.A3Error):              # a second begin before end is refused
+            ctx.sample_blocks_begin(d_ip, d_ix, torch.from_numpy(seeds).to(DEV), w.fanouts, d_cm, 4 * Q, b)
+        ctx.gather_input_features(d_fd, split.feat_host, d_cm, out)
+        got = ctx.sample_blocks_end().to_host()
+        torch.cuda.synchronize()
+        want = oracle.sample_blocks(g.indptr.numpy(), g.indices.numpy(), seeds, w.fanouts,
+                                    split.cache_map.numpy(), 4 * Q, b)
+        blocks_equal(got, want)
+        n = min(cap, want.n_src[-1])
+        want_rows = oracle.gather_features(split.feat_dev.numpy(), split.feat_host.numpy(),
+                                           split.cache_map.numpy(), want.input_nodes[:n])
+        assert out[:n].cpu().numpy().tobytes() == want_rows.tobytes()
+        assert bool((out[n:] == 7.0).all()), "rows beyond the count or the capacity stay untouched"
+    ctx.close()
+
+
 def test_gather_unaligned_buffers_fall_back_to_narrow_copies():
     w, g, _, _ = _graph("tiny")
     full = make_features(g.num_nodes, 66, torch.float16, feat_seed=3)   # 132-byte rows: 4-byte vectors
