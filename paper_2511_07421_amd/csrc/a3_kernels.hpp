@@ -1,40 +1,54 @@
 // HIP kernels of the sampling / reindex / gather path (gfx950, wave64).
+//
+// Per hop six launches; workgroups of one kernel never exchange data with each other, results
+// pass from kernel to kernel only (each XCD has its own L2, and making a store visible to
+// another XCD inside a kernel costs a write-back of that L2):
+//   k_frontier    degrees of the frontier nodes, tile-local prefix of the per-node edge counts,
+//                 tile sums, nodes binned by degree
+//   k_scan_tiles  exclusive scan of the tile sums (one workgroup)
+//   k_sample      keyed selection; small-degree bins by groups of 4/8/16 lanes, the rest one
+//                 wavefront per node; records first occurrences in node_map
+//   k_flag        which sampled edge is the first occurrence of a new node; tile-local prefix
+//   k_scan_tiles  numbering of the new nodes across tiles
+//   k_relabel     local ids of all edges, new nodes appended to the frontier
 #pragma once
 #include "a3_device.hpp"
 
 namespace a3 {
 
 constexpr int kMaxHops = 8;
-constexpr int kScanThreads = 256;
-constexpr int kScanPerThread = 4;
-constexpr int kScanTile = kScanThreads * kScanPerThread;
+constexpr int kTileThreads = 256;
+constexpr int kTilePerThread = 4;
+constexpr int kTile = kTileThreads * kTilePerThread;  // elements per scan tile
+constexpr int kTileShift = 10;
 
-constexpr int32_t kErrBadSeed = 1;      // seed outside [0, num_nodes)
-constexpr int32_t kErrDupSeed = 2;      // a seed appears twice
-constexpr int32_t kErrHugeRow = 4;      // a row with more than 2^31 - 1 entries
+constexpr int32_t kErrBadSeed = 1;  // seed outside [0, num_nodes)
+constexpr int32_t kErrDupSeed = 2;  // a seed appears twice
+constexpr int32_t kErrHugeRow = 4;  // a row with more than 2^31 - 1 entries
+// an index left its array (bad ids in the inputs, or a logic error): one bit per guard
+constexpr int32_t kErrFrontierId = 8, kErrFlagId = 16, kErrFirstPosNeg = 32, kErrFirstPosLate = 64,
+                  kErrNewNode = 128, kErrEmit = 256;
+constexpr int32_t kErrInternal = 8 | 16 | 32 | 64 | 128 | 256;
 
-// Counts of the running call, written by kernels, copied to the host at the end.
+// frontier nodes by degree: 0: deg <= 16, 1: <= 32, 2: <= 64 (lane groups of 4, 8, 16, four
+// slots per lane), 3: <= kHubDegree (one wavefront), 4: hubs (one wavefront, served first)
+constexpr int kNumBins = 5;
+constexpr uint32_t kHubDegree = 2048;
+
+// Counts of the running call, written by kernels, copied to the host by the last kernel.
 struct DevState {
   int32_t n_dst[kMaxHops + 1];
   int32_t n_src[kMaxHops];
   int32_t n_edges[kMaxHops];
   int32_t error;
   int32_t n_radix;  // nodes that went through the exhaustive selection path
+  // scratch of the running hop; zero between hops and between calls
+  int32_t bin_count[kNumBins];
 };
 
 // ---------------------------------------------------------------------------
 // block-wide helpers (256 threads = 4 waves)
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t block_sum_256(uint32_t v, uint32_t* lds4) {
-  v = wave_sum_u32(v);
-  const uint32_t w = threadIdx.x >> 6;
-  if (lane_id() == 0) lds4[w] = v;
-  __syncthreads();
-  const uint32_t total = lds4[0] + lds4[1] + lds4[2] + lds4[3];
-  __syncthreads();
-  return total;
-}
-
 // exclusive scan over the 256 threads of a block; *total receives the block sum
 __device__ __forceinline__ uint32_t block_excl_scan_256(uint32_t v, uint32_t* lds4, uint32_t* total) {
   const uint32_t in_wave = wave_excl_scan_u32(v);
@@ -48,107 +62,17 @@ __device__ __forceinline__ uint32_t block_excl_scan_256(uint32_t v, uint32_t* ld
   return before + in_wave;
 }
 
-// ---------------------------------------------------------------------------
-// seeds -> S[0:num_seeds], relabel map
-// ---------------------------------------------------------------------------
-__global__ void k_fill_i32(int32_t* p, int64_t n, int32_t value) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = value;
-}
-
-template <typename IdxT>
-__global__ void k_init_seeds(const IdxT* seeds, int64_t num_seeds, int64_t num_nodes, IdxT* S,
-                             int32_t* node_map, DevState* st, int validate) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i == 0) {
-    st->n_dst[0] = (int32_t)num_seeds;
-    st->error = 0;
-    st->n_radix = 0;
-  }
-  if (i >= num_seeds) return;
-  const int64_t v = (int64_t)seeds[i];
-  S[i] = seeds[i];
-  if (validate) {
-    if (v < 0 || v >= num_nodes) {
-      atomicOr(&st->error, kErrBadSeed);
-      return;
-    }
-    atomicMin(&node_map[v], (int32_t)i);
-  } else {
-    node_map[v] = (int32_t)i;
-  }
-}
-
-// with validation on: a seed whose map entry is not its own position is a repeat; if any
-// seed is bad the frontier is emptied so that later kernels touch nothing.
-template <typename IdxT>
-__global__ void k_check_seeds(const IdxT* seeds, int64_t num_seeds, int64_t num_nodes,
-                              const int32_t* node_map, DevState* st) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= num_seeds) return;
-  const int64_t v = (int64_t)seeds[i];
-  if (v < 0 || v >= num_nodes) return;
-  if (node_map[v] != (int32_t)i) atomicOr(&st->error, kErrDupSeed);
-}
-
-__global__ void k_gate_on_error(DevState* st) {
-  if (threadIdx.x == 0 && blockIdx.x == 0 && st->error != 0) st->n_dst[0] = 0;
-}
-
-// undo the map entries of every node in S (all nodes the call touched)
-// and publish the call's counts to the host (host_state is pinned host memory)
-template <typename IdxT>
-__global__ void k_reset_map(const IdxT* S, const DevState* st, int last_hop, int64_t num_nodes,
-                            int32_t* node_map, DevState* host_state) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i == 0) *host_state = *st;
-  const int64_t n = st->n_src[last_hop];
-  if (i >= n) return;
-  const int64_t v = (int64_t)S[i];
-  if (v >= 0 && v < num_nodes) node_map[v] = kMapEmpty;
-}
-
-// ---------------------------------------------------------------------------
-// exclusive scan in three launches: tile sums, scan of sums, apply
-// ---------------------------------------------------------------------------
-// step a1: per frontier node, the number of neighbours it will keep
-template <typename IdxT>
-__global__ __launch_bounds__(kScanThreads) void k_count_degrees(const IdxT* S, const int64_t* indptr,
-                                                                const DevState* st, int hop,
-                                                                int32_t fanout, int32_t* vals,
-                                                                int32_t* tile_sums) {
-  __shared__ uint32_t lds4[4];
-  const int64_t n = st->n_dst[hop];
-  const int64_t i0 = (int64_t)blockIdx.x * kScanTile;
-  if (i0 >= n) return;
-  uint32_t sum = 0;
-#pragma unroll
-  for (int k = 0; k < kScanPerThread; ++k) {
-    const int64_t i = i0 + (int64_t)k * kScanThreads + threadIdx.x;
-    if (i < n) {
-      const int64_t v = (int64_t)S[i];
-      int64_t deg = indptr[v + 1] - indptr[v];
-      if (deg < 0) deg = 0;
-      const int32_t c = deg < (int64_t)fanout ? (int32_t)deg : fanout;
-      vals[i] = c;
-      sum += (uint32_t)c;
-    }
-  }
-  const uint32_t total = block_sum_256(sum, lds4);
-  if (threadIdx.x == 0) tile_sums[blockIdx.x] = (int32_t)total;
-}
-
-// scan of the tile sums by one block.  mode 0 (edge offsets of hop): n = n_dst[hop], total is
-// the hop's edge count, also stored at out[n].  mode 1 (new-node numbering): n = n_edges[hop],
-// total new nodes; publishes n_src[hop] and n_dst[hop+1].
-__global__ __launch_bounds__(kScanThreads) void k_scan_tile_sums(const int32_t* tile_sums,
-                                                                 int32_t* tile_offs, DevState* st,
-                                                                 int hop, int mode, int32_t* out) {
+// Exclusive scan of the tile sums by one workgroup.  mode 0 (edge offsets): n = n_dst[hop],
+// the total is the hop's edge count, also stored at out[n].  mode 1 (new-node numbering):
+// n = n_edges[hop], the total is the number of new nodes; publishes n_src[hop], n_dst[hop+1].
+__global__ __launch_bounds__(kTileThreads) void k_scan_tiles(const int32_t* tile_sums,
+                                                             int32_t* tile_offs, DevState* st,
+                                                             int hop, int mode, int32_t* out) {
   __shared__ uint32_t lds4[4];
   const int64_t n = mode == 0 ? st->n_dst[hop] : st->n_edges[hop];
-  const int64_t n_tiles = (n + kScanTile - 1) / kScanTile;
+  const int64_t n_tiles = (n + kTile - 1) / kTile;
   uint32_t carry = 0;
-  for (int64_t t0 = 0; t0 < n_tiles; t0 += kScanThreads) {
+  for (int64_t t0 = 0; t0 < n_tiles; t0 += kTileThreads) {
     const int64_t t = t0 + threadIdx.x;
     const uint32_t v = t < n_tiles ? (uint32_t)tile_sums[t] : 0u;
     uint32_t total;
@@ -168,34 +92,149 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_tile_sums(const int32_t* 
   }
 }
 
-__global__ __launch_bounds__(kScanThreads) void k_scan_apply(const int32_t* vals,
-                                                             const int32_t* tile_offs,
-                                                             const DevState* st, int hop, int mode,
-                                                             int32_t* out) {
-  __shared__ uint32_t lds4[4];
-  const int64_t n = mode == 0 ? st->n_dst[hop] : st->n_edges[hop];
-  const int64_t i0 = (int64_t)blockIdx.x * kScanTile;
-  if (i0 >= n) return;
-  // thread t owns 4 consecutive elements so that its partial sums chain in order
-  const int64_t base = i0 + (int64_t)threadIdx.x * kScanPerThread;
-  uint32_t v[kScanPerThread];
-  uint32_t sum = 0;
-#pragma unroll
-  for (int k = 0; k < kScanPerThread; ++k) {
-    v[k] = (base + k < n) ? (uint32_t)vals[base + k] : 0u;
-    sum += v[k];
+// ---------------------------------------------------------------------------
+// small utility kernels
+// ---------------------------------------------------------------------------
+__global__ void k_fill_i32(int32_t* p, int64_t n, int32_t value) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = value;
+}
+
+// A3_VALIDATE only: seeds -> S with range and uniqueness checks; a bad batch empties the frontier
+template <typename IdxT>
+__global__ void k_init_seeds_checked(const IdxT* seeds, int64_t num_seeds, int64_t num_nodes,
+                                     IdxT* S, int32_t* node_map, DevState* st) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= num_seeds) return;
+  const int64_t v = (int64_t)seeds[i];
+  S[i] = seeds[i];
+  if (v < 0 || v >= num_nodes) {
+    atomicOr(&st->error, kErrBadSeed);
+    return;
   }
-  uint32_t total;
-  uint32_t run = block_excl_scan_256(sum, lds4, &total) + (uint32_t)tile_offs[blockIdx.x];
-#pragma unroll
-  for (int k = 0; k < kScanPerThread; ++k) {
-    if (base + k < n) out[base + k] = (int32_t)run;
-    run += v[k];
+  atomicMin(&node_map[v], (int32_t)i);
+}
+
+template <typename IdxT>
+__global__ void k_check_seeds(const IdxT* seeds, int64_t num_seeds, int64_t num_nodes,
+                              const int32_t* node_map, DevState* st) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= num_seeds) return;
+  const int64_t v = (int64_t)seeds[i];
+  if (v < 0 || v >= num_nodes) return;
+  if (node_map[v] != (int32_t)i) atomicOr(&st->error, kErrDupSeed);
+}
+
+__global__ void k_set_frontier_size(DevState* st, int32_t num_seeds) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) st->n_dst[0] = st->error != 0 ? 0 : num_seeds;
+}
+
+// End of a call: undo the map entries of every node in S (all nodes the call touched), publish
+// the counts to the host (host_state is pinned host memory) and leave the state clean.
+template <typename IdxT>
+__global__ void k_finish_call(const IdxT* S, DevState* st, int last_hop, int64_t num_nodes,
+                              int32_t* node_map, DevState* host_state) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t n = st->n_src[last_hop];
+  if (i == 0) {
+    *host_state = *st;
+    st->error = 0;
+    st->n_radix = 0;
   }
+  if (i >= n) return;
+  const int64_t v = (int64_t)S[i];
+  if (v >= 0 && v < num_nodes) node_map[v] = kMapEmpty;
 }
 
 // ---------------------------------------------------------------------------
-// steps a2-a4: one wave per frontier node
+// step a1: frontier degrees -> edge offsets, degree bins
+// ---------------------------------------------------------------------------
+template <typename IdxT>
+struct FrontierArgs {
+  const IdxT* seeds;  // non-null at hop 0 without validation: the frontier is read from here
+  int64_t num_seeds;
+  IdxT* S;
+  int32_t* node_map;
+  const int64_t* indptr;
+  DevState* st;
+  int32_t hop;
+  int32_t fanout;
+  int32_t* local_off;  // per node: edges of earlier nodes of the same tile
+  int32_t* tile_sums;
+  int64_t num_nodes;
+  int32_t* bins[kNumBins];   // node indices per degree bin
+};
+
+__device__ __forceinline__ int degree_bin(uint32_t deg) {
+  return deg <= 16 ? 0 : deg <= 32 ? 1 : deg <= 64 ? 2 : deg <= kHubDegree ? 3 : 4;
+}
+
+template <typename IdxT>
+__global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<IdxT> a) {
+  __shared__ uint32_t lds4[4];
+  __shared__ uint32_t bin_n[kNumBins];
+  __shared__ uint32_t bin_base[kNumBins];
+  const bool from_seeds = a.seeds != nullptr;
+  if (from_seeds && blockIdx.x == 0 && threadIdx.x == 0) a.st->n_dst[0] = (int32_t)a.num_seeds;
+  const int64_t n = from_seeds ? a.num_seeds : (int64_t)a.st->n_dst[a.hop];
+  if ((int64_t)blockIdx.x * kTile >= n) return;
+  if (threadIdx.x < kNumBins) bin_n[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t base_i = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kTilePerThread;
+  uint32_t cnt[kTilePerThread];
+  uint32_t rank_in_bin[kTilePerThread];
+  int bin[kTilePerThread];
+  uint32_t sum = 0;
+#pragma unroll
+  for (int k = 0; k < kTilePerThread; ++k) {
+    const int64_t i = base_i + k;
+    cnt[k] = 0;
+    bin[k] = -1;
+    rank_in_bin[k] = 0;
+    if (i < n) {
+      int64_t v;
+      if (from_seeds) {
+        const IdxT s = a.seeds[i];
+        v = (int64_t)s;
+        a.S[i] = s;
+        if (v >= 0 && v < a.num_nodes) a.node_map[v] = (int32_t)i;
+      } else {
+        v = (int64_t)a.S[i];
+      }
+      int64_t deg = 0;
+      if (v >= 0 && v < a.num_nodes)
+        deg = a.indptr[v + 1] - a.indptr[v];
+      else
+        atomicOr(&a.st->error, kErrFrontierId);
+      if (deg < 0) deg = 0;
+      if (deg > 0x7FFFFFFF) deg = 0x7FFFFFFF;
+      cnt[k] = deg < (int64_t)a.fanout ? (uint32_t)deg : (uint32_t)a.fanout;
+      bin[k] = degree_bin((uint32_t)deg);
+      rank_in_bin[k] = atomicAdd(&bin_n[bin[k]], 1u);
+      sum += cnt[k];
+    }
+  }
+  uint32_t total;
+  uint32_t run = block_excl_scan_256(sum, lds4, &total);
+#pragma unroll
+  for (int k = 0; k < kTilePerThread; ++k) {
+    if (base_i + k < n) a.local_off[base_i + k] = (int32_t)run;
+    run += cnt[k];
+  }
+  // one global reservation per bin and block, then scatter the node indices
+  if (threadIdx.x < kNumBins)
+    bin_base[threadIdx.x] = bin_n[threadIdx.x]
+                                ? (uint32_t)atomicAdd(&a.st->bin_count[threadIdx.x], (int32_t)bin_n[threadIdx.x])
+                                : 0u;
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kTilePerThread; ++k)
+    if (bin[k] >= 0) a.bins[bin[k]][bin_base[bin[k]] + rank_in_bin[k]] = (int32_t)(base_i + k);
+  if (threadIdx.x == 0) a.tile_sums[blockIdx.x] = (int32_t)total;
+}
+
+// ---------------------------------------------------------------------------
+// steps a2-a4: keyed selection
 // ---------------------------------------------------------------------------
 template <typename IdxT>
 struct SampleArgs {
@@ -203,24 +242,66 @@ struct SampleArgs {
   const IdxT* indices;
   const int32_t* cache_map;  // read only when weighted
   const IdxT* S;             // frontier: local id -> global id
-  const int32_t* blk_indptr; // edge offsets of this hop
+  const int32_t* local_off;
+  const int32_t* tile_offs;
+  int32_t* blk_indptr;       // out: edge offsets of this hop
   IdxT* gid;                 // out: global id of each sampled neighbour
   int64_t* eids;             // out: CSR position of each sampled edge (may be null)
   int32_t* node_map;         // global id -> first position / local id
   DevState* st;
+  const int32_t* bins[kNumBins];
+  int64_t num_nodes;
+  int64_t cap_edges;         // entries in gid / eids (arena capacity of this hop)
+  uint32_t role_blocks[4];   // workgroups serving bins 0, 1, 2 and the wide nodes (bins 4 then 3)
   int32_t hop;
   int32_t fanout;
-  uint32_t lambda;   // expected number of candidates kept by the draw threshold
-  uint32_t cap;      // candidate buffer entries (>= lambda)
-  uint32_t xcap;     // challenger buffer entries (weighted only, multiple of 64, >= 128)
+  uint32_t lambda;    // expected number of candidates kept by the draw threshold
+  uint32_t cap;       // candidate buffer entries per wavefront (>= lambda)
+  uint32_t xcap;      // challenger buffer entries (weighted only, multiple of 64, >= 128)
+  uint32_t lds_per_wave;  // uint64 entries of LDS per wavefront
   uint32_t bias_q16;
   uint32_t seed_lo, seed_hi;
   uint32_t weighted;
   uint32_t force_radix;
 };
 
+// what a lane needs to write one sampled edge
+template <typename IdxT>
+struct Emitter {
+  const IdxT* indices;
+  IdxT* gid;
+  int64_t* eids;
+  int32_t* node_map;
+  int64_t row;
+  int32_t base;
+  int32_t n_dst;
+  int64_t num_nodes;
+  int64_t cap_edges;  // entries in gid / eids
+  int32_t* error;
+  __device__ __forceinline__ void operator()(uint32_t pos, uint32_t slot) const {
+    const int64_t eid = row + slot;
+    const IdxT g = indices[eid];
+    const int32_t e = base + (int32_t)pos;
+    // a neighbour id outside the graph or an offset outside the arena is dropped, never written
+    if (e < 0 || (int64_t)e >= cap_edges || (int64_t)g < 0 || (int64_t)g >= num_nodes) {
+      atomicOr(error, kErrEmit);
+      return;
+    }
+    gid[e] = g;
+    if (eids) eids[e] = eid;
+    atomicMin(&node_map[(int64_t)g], n_dst + e);
+  }
+};
+
 __device__ __forceinline__ bool tuple_less(uint64_t K1, uint64_t k1, uint64_t K2, uint64_t k2) {
   return K1 < K2 || (K1 == K2 && k1 < k2);
+}
+
+// LDS traffic between the lanes of one wavefront: LDS executes a wavefront's accesses in order,
+// so only the compiler has to be kept from moving them.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
 }
 
 // Rank R[0:nR) and X[0:nX) together under (K, draw-order key) and keep the best m in R, sorted.
@@ -240,12 +321,12 @@ __device__ __forceinline__ void merge_best(uint32_t m, uint32_t nR, uint32_t nX,
       Nk[r] = k;
     }
   }
-  __syncthreads();
+  wave_sync();
   for (uint32_t j = lane; j < m; j += kWave) {
     RK[j] = NK[j];
     Rk[j] = Nk[j];
   }
-  __syncthreads();
+  wave_sync();
 }
 
 // smallest draw x that a cached neighbour needs so that its key can still reach BK:
@@ -260,14 +341,12 @@ __device__ __forceinline__ uint32_t draw_floor_for_key(uint64_t BK, uint32_t w_q
   return (uint32_t)xmin;
 }
 
+// ---- one wavefront, one node of any degree ------------------------------------------------------
 template <typename IdxT>
-__global__ __launch_bounds__(kWave) void k_sample(const SampleArgs<IdxT> a) {
-  extern __shared__ uint64_t lds[];
+__device__ void sample_node_wave(const SampleArgs<IdxT>& a, int64_t i, int32_t n_dst, uint64_t* lds) {
   const uint32_t lane = lane_id();
-  const int32_t n_dst = a.st->n_dst[a.hop];
-  const int64_t i = blockIdx.x;
-  if (i >= n_dst) return;
   const int64_t v = (int64_t)a.S[i];
+  if (v < 0 || v >= a.num_nodes) return;  // flagged by k_frontier, which gave it zero edges
   const int64_t row = a.indptr[v];
   int64_t deg64 = a.indptr[v + 1] - row;
   if (deg64 < 0) deg64 = 0;
@@ -277,16 +356,9 @@ __global__ __launch_bounds__(kWave) void k_sample(const SampleArgs<IdxT> a) {
   }
   const uint32_t deg = (uint32_t)deg64;
   const uint32_t f = (uint32_t)a.fanout;
-  const int32_t base = a.blk_indptr[i];
-
-  auto emit = [&](uint32_t pos, uint32_t slot) {
-    const int64_t eid = row + slot;
-    const IdxT g = a.indices[eid];
-    const int32_t e = base + (int32_t)pos;
-    a.gid[e] = g;
-    if (a.eids) a.eids[e] = eid;
-    atomicMin(&a.node_map[(int64_t)g], n_dst + e);
-  };
+  const int32_t base = a.tile_offs[i >> kTileShift] + a.local_off[i];
+  if (lane == 0) a.blk_indptr[i] = base;
+  const Emitter<IdxT> emit{a.indices, a.gid, a.eids, a.node_map, row, base, n_dst, a.num_nodes, a.cap_edges, &a.st->error};
 
   if (deg <= f) {  // keep every neighbour, no draw
     for (uint32_t s = lane; s < deg; s += kWave) emit(s, s);
@@ -325,7 +397,7 @@ __global__ __launch_bounds__(kWave) void k_sample(const SampleArgs<IdxT> a) {
         }
       }
     }
-    __syncthreads();
+    wave_sync();
   }
   if (!a.force_radix && cnt >= m && cnt <= a.cap) {
     for (uint32_t j = lane; j < cnt; j += kWave) {
@@ -388,7 +460,7 @@ __global__ __launch_bounds__(kWave) void k_sample(const SampleArgs<IdxT> a) {
       run_sel += wave_sum_u32(selc);
     }
   }
-  __syncthreads();
+  wave_sync();
 
   if (!a.weighted) {
     // all weights equal: the m largest draws are the answer; emit in slot order
@@ -398,6 +470,7 @@ __global__ __launch_bounds__(kWave) void k_sample(const SampleArgs<IdxT> a) {
       for (uint32_t t = 0; t < m; ++t) pos += (uint32_t)selk[t] < s ? 1u : 0u;
       emit(pos, s);
     }
+    wave_sync();  // the buffers are reused by this wavefront's next node
     return;
   }
 
@@ -423,7 +496,7 @@ __global__ __launch_bounds__(kWave) void k_sample(const SampleArgs<IdxT> a) {
     kT = k > kT ? k : kT;
   }
   kT = wave_max_u64(kT);
-  __syncthreads();
+  wave_sync();
   merge_best(m, m, 0, RK, Rk, XK, Xk, NK, Nk);
   uint64_t BK = RK[m - 1], Bk = Rk[m - 1];
   uint32_t x_lo = draw_floor_for_key(BK, a.bias_q16);
@@ -454,7 +527,7 @@ __global__ __launch_bounds__(kWave) void k_sample(const SampleArgs<IdxT> a) {
         }
         nX += (uint32_t)__popcll(mask);
         if (nX + kWave > a.xcap) {  // the next ballot might not fit: fold the buffer in
-          __syncthreads();
+          wave_sync();
           merge_best(m, m, nX, RK, Rk, XK, Xk, NK, Nk);
           nX = 0;
           BK = RK[m - 1];
@@ -464,13 +537,161 @@ __global__ __launch_bounds__(kWave) void k_sample(const SampleArgs<IdxT> a) {
       }
     }
   }
-  __syncthreads();
+  wave_sync();
   if (nX > 0) merge_best(m, m, nX, RK, Rk, XK, Xk, NK, Nk);
   for (uint32_t j = lane; j < m; j += kWave) {
     const uint32_t s = (uint32_t)Rk[j];
     uint32_t pos = 0;
     for (uint32_t t = 0; t < m; ++t) pos += (uint32_t)Rk[t] < s ? 1u : 0u;
     emit(pos, s);
+  }
+  wave_sync();
+}
+
+// ---- a group of G lanes (4, 8 or 16), one node of degree <= 4 G: four slots per lane ------------
+// The draws of a lane are one Philox block.  Selection is m rounds of "best remaining slot of
+// the group" (lane-local best, butterfly reduction, lowest lane among equals), which costs
+// O(m log G) instead of ranking every slot against every other.
+template <typename IdxT, int G>
+__device__ void sample_node_group(const SampleArgs<IdxT>& a, int64_t i, int32_t n_dst) {
+  const uint32_t lane = lane_id();
+  const uint32_t gl = lane & (G - 1);       // lane inside the group
+  const uint32_t gshift = lane & ~(G - 1);  // first lane of the group inside the wavefront
+  const int64_t v = (int64_t)a.S[i];
+  if (v < 0 || v >= a.num_nodes) return;  // flagged by k_frontier, which gave it zero edges
+  const int64_t row = a.indptr[v];
+  int64_t deg64 = a.indptr[v + 1] - row;
+  if (deg64 < 0) deg64 = 0;
+  const uint32_t deg = (uint32_t)deg64;  // <= 4 G by construction of the bins
+  const uint32_t f = (uint32_t)a.fanout;
+  const int32_t base = a.tile_offs[i >> kTileShift] + a.local_off[i];
+  if (gl == 0) a.blk_indptr[i] = base;
+  const Emitter<IdxT> emit{a.indices, a.gid, a.eids, a.node_map, row, base, n_dst, a.num_nodes, a.cap_edges, &a.st->error};
+  if (deg <= f) {
+    for (uint32_t s = gl; s < deg; s += G) emit(s, s);
+    return;
+  }
+  const uint32_t m = f;
+  const PhiloxKey pk{(uint32_t)(uint64_t)v, (uint32_t)((uint64_t)v >> 32), (uint32_t)a.hop,
+                     a.seed_lo, a.seed_hi};
+  uint32_t x[4];
+  philox4x32_10(gl, pk, x);
+  uint32_t alive = 0;  // bit w: slot 4 gl + w exists and is not chosen yet
+#pragma unroll
+  for (int w = 0; w < 4; ++w) alive |= (4u * gl + w < deg) ? (1u << w) : 0u;
+  uint64_t K[4] = {0, 0, 0, 0};
+  if (a.weighted) {
+    bool cached[4];
+    bool any_c = false, any_u = false;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      cached[w] = false;
+      if (alive & (1u << w)) {
+        const int64_t u = (int64_t)a.indices[row + 4u * gl + w];
+        cached[w] = a.cache_map[u] >= 0;
+        any_c |= cached[w];
+        any_u |= !cached[w];
+      }
+    }
+    // keys are needed only when the group's neighbourhood mixes both classes (otherwise K is
+    // monotone in x and the order is "larger draw first")
+    const uint64_t mc = __ballot(any_c), mu = __ballot(any_u);
+    const uint64_t gmask = ((G == 64) ? ~0ull : ((1ull << G) - 1ull)) << gshift;
+    const bool mixed = (mc & gmask) != 0 && (mu & gmask) != 0;
+    if (mixed) {
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        if (alive & (1u << w)) K[w] = sample_key(x[w], cached[w] ? a.bias_q16 : 65536u);
+    }
+  }
+  uint32_t chosen = 0;
+  for (uint32_t it = 0; it < m; ++it) {
+    // lane-local best remaining slot under (K ascending, x descending, word ascending)
+    int bw = -1;
+    uint64_t bK = ~0ull;
+    uint32_t bx = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const bool better = (alive & (1u << w)) && (bw < 0 || K[w] < bK || (K[w] == bK && x[w] > bx));
+      if (better) {
+        bw = w;
+        bK = K[w];
+        bx = x[w];
+      }
+    }
+    // group-wide best: smallest K, then largest x, then lowest lane (= lowest slot)
+    uint64_t gK = bK;
+#pragma unroll
+    for (int o = G / 2; o > 0; o >>= 1) {
+      const uint64_t other = __shfl_xor(gK, o, G);
+      gK = other < gK ? other : gK;
+    }
+    const bool tiedK = bw >= 0 && bK == gK;
+    uint32_t gx = tiedK ? bx : 0u;
+#pragma unroll
+    for (int o = G / 2; o > 0; o >>= 1) {
+      const uint32_t other = __shfl_xor(gx, o, G);
+      gx = other > gx ? other : gx;
+    }
+    const bool top = tiedK && bx == gx;
+    const uint32_t tops = (uint32_t)((__ballot(top) >> gshift) & ((1ull << G) - 1ull));
+    const uint32_t winner = (uint32_t)__ffs((int)tops) - 1u;
+    if (gl == winner) {
+      alive &= ~(1u << bw);
+      chosen |= 1u << bw;
+    }
+  }
+  // emit in slot order: slots of lower lanes first, then lower words of the own lane
+  uint32_t below = 0;
+  uint32_t own_before[4];
+  uint32_t acc = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const uint32_t bits = (uint32_t)((__ballot((chosen >> w) & 1u) >> gshift) & ((1ull << G) - 1ull));
+    below += (uint32_t)__popc(bits & ((1u << gl) - 1u));
+    own_before[w] = acc;
+    acc += (chosen >> w) & 1u;
+  }
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+    if ((chosen >> w) & 1u) emit(below + own_before[w], 4u * gl + w);
+}
+
+template <typename IdxT, int G>
+__device__ __forceinline__ void run_group_role(const SampleArgs<IdxT>& a, int bin, uint32_t block_in_role,
+                                               uint32_t blocks_in_role, int32_t n_dst) {
+  const int64_t count = a.st->bin_count[bin];
+  const int64_t groups = (int64_t)blocks_in_role * (kTileThreads / G);
+  for (int64_t item = (int64_t)block_in_role * (kTileThreads / G) + threadIdx.x / G; item < count;
+       item += groups) {
+    const int64_t i = a.bins[bin][item];
+    if (i >= 0 && i < n_dst) sample_node_group<IdxT, G>(a, i, n_dst);
+  }
+}
+
+template <typename IdxT>
+__global__ __launch_bounds__(kTileThreads) void k_sample(const SampleArgs<IdxT> a) {
+  extern __shared__ uint64_t lds[];
+  const int32_t n_dst = a.st->n_dst[a.hop];
+  uint32_t b = blockIdx.x;
+  if (b < a.role_blocks[0]) return run_group_role<IdxT, 4>(a, 0, b, a.role_blocks[0], n_dst);
+  b -= a.role_blocks[0];
+  if (b < a.role_blocks[1]) return run_group_role<IdxT, 8>(a, 1, b, a.role_blocks[1], n_dst);
+  b -= a.role_blocks[1];
+  if (b < a.role_blocks[2]) return run_group_role<IdxT, 16>(a, 2, b, a.role_blocks[2], n_dst);
+  b -= a.role_blocks[2];
+  // wide nodes, one wavefront each: hubs first, then the rest, dealt round-robin over the
+  // wavefronts of this role so that the hubs land on different wavefronts
+  const int64_t n_hub = a.st->bin_count[4];
+  const int64_t n_wide = a.st->bin_count[3];
+  // the wavefront's index inside the workgroup, held in a scalar register so that the node loop
+  // below is uniform control flow for the whole wavefront
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(threadIdx.x >> 6));
+  uint64_t* my_lds = lds + (size_t)wave * a.lds_per_wave;
+  const int64_t waves = (int64_t)a.role_blocks[3] * (kTileThreads / kWave);
+  for (int64_t t = (int64_t)b * (kTileThreads / kWave) + wave; t < n_hub + n_wide; t += waves) {
+    const int64_t i = t < n_hub ? a.bins[4][t] : a.bins[3][t - n_hub];
+    if (i >= 0 && i < n_dst) sample_node_wave<IdxT>(a, i, n_dst, my_lds);
   }
 }
 
@@ -479,53 +700,79 @@ __global__ __launch_bounds__(kWave) void k_sample(const SampleArgs<IdxT> a) {
 // local id (< n_dst, g is a destination) or n_dst + (position of g's first occurrence).
 // ---------------------------------------------------------------------------
 template <typename IdxT>
-__global__ __launch_bounds__(kScanThreads) void k_flag_first(const IdxT* gid,
-                                                             const int32_t* node_map,
-                                                             const DevState* st, int hop,
-                                                             int32_t* first_pos, int32_t* vals,
-                                                             int32_t* tile_sums) {
+__global__ __launch_bounds__(kTileThreads) void k_flag(const IdxT* gid, const int32_t* node_map,
+                                                       DevState* st, int hop, int64_t num_nodes,
+                                                       int32_t* first_pos, int32_t* local_rank,
+                                                       int32_t* tile_sums) {
   __shared__ uint32_t lds4[4];
   const int64_t n = st->n_edges[hop];
   const int32_t n_dst = st->n_dst[hop];
-  const int64_t e0 = (int64_t)blockIdx.x * kScanTile;
-  if (e0 >= n) return;
+  if ((int64_t)blockIdx.x * kTile >= n) return;
+  const int64_t base_e = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kTilePerThread;
+  uint32_t flag[kTilePerThread];
   uint32_t sum = 0;
 #pragma unroll
-  for (int k = 0; k < kScanPerThread; ++k) {
-    const int64_t e = e0 + (int64_t)k * kScanThreads + threadIdx.x;
+  for (int k = 0; k < kTilePerThread; ++k) {
+    const int64_t e = base_e + k;
+    flag[k] = 0;
     if (e < n) {
-      const int32_t p = node_map[(int64_t)gid[e]];
+      const int64_t g = (int64_t)gid[e];
+      int32_t p = 0;
+      if (g >= 0 && g < num_nodes)
+        p = node_map[g];
+      else
+        atomicOr(&st->error, kErrFlagId);
       first_pos[e] = p;
-      const int32_t flag = (p == n_dst + (int32_t)e) ? 1 : 0;
-      vals[e] = flag;
-      sum += (uint32_t)flag;
+      flag[k] = (p == n_dst + (int32_t)e) ? 1u : 0u;
+      sum += flag[k];
     }
   }
-  const uint32_t total = block_sum_256(sum, lds4);
+  uint32_t total;
+  uint32_t run = block_excl_scan_256(sum, lds4, &total);
+#pragma unroll
+  for (int k = 0; k < kTilePerThread; ++k) {
+    if (base_e + k < n) local_rank[base_e + k] = (int32_t)run;
+    run += flag[k];
+  }
   if (threadIdx.x == 0) tile_sums[blockIdx.x] = (int32_t)total;
 }
 
-// new_rank[q] = number of first occurrences before edge q.  A first occurrence at edge q gets
-// local id n_dst + new_rank[q]; every edge reads its id through its first occurrence.
+// A first occurrence at edge q gets local id n_dst + (first occurrences before q); every edge
+// reads its id through its first occurrence.  Also clears the hop's scratch counters.
 template <typename IdxT>
-__global__ void k_relabel(const IdxT* gid, const int32_t* first_pos, const int32_t* new_rank,
-                          const DevState* st, int hop, IdxT* S, int32_t* node_map,
-                          int32_t* blk_indices) {
+__global__ void k_relabel(const IdxT* gid, const int32_t* first_pos, const int32_t* local_rank,
+                          const int32_t* tile_offs, DevState* st, int hop, int64_t num_nodes,
+                          int64_t cap_src, IdxT* S, int32_t* node_map, int32_t* blk_indices) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e == 0) {
+    for (int b = 0; b < kNumBins; ++b) st->bin_count[b] = 0;
+  }
   const int64_t n = st->n_edges[hop];
   if (e >= n) return;
   const int32_t n_dst = st->n_dst[hop];
   const int32_t p = first_pos[e];
   int32_t local;
-  if (p < n_dst) {
+  if (p < 0) {
+    atomicOr(&st->error, kErrFirstPosNeg);
+    local = 0;
+  } else if (p < n_dst) {
     local = p;
   } else {
     const int32_t q = p - n_dst;
-    local = n_dst + new_rank[q];
+    if ((int64_t)q > e) {  // a first occurrence cannot lie after the edge itself
+      atomicOr(&st->error, kErrFirstPosLate);
+      blk_indices[e] = 0;
+      return;
+    }
+    local = n_dst + tile_offs[q >> kTileShift] + local_rank[q];
     if ((int64_t)q == e) {
       const IdxT g = gid[e];
-      S[local] = g;
-      node_map[(int64_t)g] = local;
+      if (local >= 0 && (int64_t)local < cap_src && (int64_t)g >= 0 && (int64_t)g < num_nodes) {
+        S[local] = g;
+        node_map[(int64_t)g] = local;
+      } else {
+        atomicOr(&st->error, kErrNewNode);
+      }
     }
   }
   blk_indices[e] = local;
@@ -553,6 +800,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restric
                                                            const IdxT* __restrict__ ids,
                                                            int64_t n_ids,
                                                            const int32_t* __restrict__ n_ids_dev,
+                                                           int64_t id_limit,
                                                            uint32_t vecs_per_row,
                                                            int64_t row_bytes, int log2_g,
                                                            VecT* __restrict__ out) {
@@ -568,10 +816,15 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restric
   const int64_t r0 = group * R;
   if (r0 >= n_ids) return;
   const VecT* src[R];
+  bool live[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int64_t rr = (r0 + r < n_ids) ? r0 + r : n_ids - 1;
     int64_t id = (int64_t)ids[rr];
+    // id_limit > 0: ids come from the library's own frontier; one outside the graph (possible
+    // only after an error that the host has not seen yet) is skipped, not dereferenced
+    live[r] = r0 + r < n_ids && (id_limit <= 0 || (id >= 0 && id < id_limit));
+    if (!live[r]) id = 0;
     if (kWaveRow) {
       id = ((int64_t)__builtin_amdgcn_readfirstlane((int32_t)(id >> 32)) << 32) |
            (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)id);
@@ -592,11 +845,11 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restric
 #pragma unroll
       for (int k = 0; k < U; ++k) {
         const uint32_t c = c0 + (uint32_t)k * G + lane;
-        if (c < vecs_per_row) v[r][k] = src[r][c];
+        if (live[r] && c < vecs_per_row) v[r][k] = src[r][c];
       }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      if (r0 + r < n_ids) {
+      if (live[r]) {
         VecT* dst = out + (r0 + r) * (int64_t)vecs_per_row;
 #pragma unroll
         for (int k = 0; k < U; ++k) {

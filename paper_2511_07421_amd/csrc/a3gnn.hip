@@ -32,12 +32,14 @@ struct a3_ctx {
   int32_t* blk_indptr[A3_MAX_HOPS] = {nullptr};
   int32_t* blk_indices[A3_MAX_HOPS] = {nullptr};
   int64_t* blk_eids[A3_MAX_HOPS] = {nullptr};
-  void* gid = nullptr;           // sampled global ids of the running hop, 8 bytes per entry
-  int32_t* vals = nullptr;       // scan input
-  int32_t* first_pos = nullptr;  // per edge: relabel-map value
-  int32_t* new_rank = nullptr;   // per edge: exclusive count of first occurrences
+  void* gid = nullptr;            // sampled global ids of the running hop, 8 bytes per entry
+  int32_t* local_off = nullptr;   // per frontier node: edge offset inside its scan tile
+  int32_t* first_pos = nullptr;   // per edge: relabel-map value
+  int32_t* local_rank = nullptr;  // per edge: first occurrences before it inside its scan tile
   int32_t* tile_sums = nullptr;
-  int32_t* tile_offs = nullptr;
+  int32_t* tile_offs = nullptr;   // edge offsets of the node tiles (read by k_sample)
+  int32_t* tile_offs2 = nullptr;  // new-node offsets of the edge tiles (read by k_relabel)
+  int32_t* bins[a3::kNumBins] = {nullptr};  // frontier node indices by degree bin
   int32_t* node_map = nullptr;  // global id -> position, grown on demand
   int64_t node_map_cap = 0;
   bool node_map_dirty = false;
@@ -49,6 +51,7 @@ struct a3_ctx {
   int32_t last_hops = 0;            // shape of the most recent begun call
   int32_t last_idx_bytes = 0;
   int64_t last_bound_in = 0;        // launch bound on its number of input nodes
+  int64_t last_num_nodes = 0;
   std::vector<void*> allocs;
   std::string err;
   // A3_PROFILE: rings of (start, stop) events per kind of call
@@ -99,12 +102,14 @@ inline unsigned blocks_for(int64_t n, int per_block) {
 uint32_t lambda_for(int32_t m) { return (uint32_t)(m + 4.0 * std::sqrt((double)m) + 8.0); }
 uint32_t cap_for(uint32_t lambda) { return ((2 * lambda + 63) / 64) * 64; }
 constexpr uint32_t kChallengerCap = 192;
+constexpr int64_t kMaxRoleBlocks = 2048;
 
-size_t sample_lds_bytes(int32_t fanout, bool weighted) {
+// uint64 entries of LDS one wavefront needs in the wavefront-per-node path
+uint32_t sample_lds_entries(int32_t fanout, bool weighted) {
   const uint32_t cap = cap_for(lambda_for(fanout));
-  size_t entries = (size_t)cap + (size_t)fanout;
-  if (weighted) entries += 3 * (size_t)fanout + 2 * (size_t)kChallengerCap;
-  return entries * sizeof(uint64_t);
+  uint32_t entries = cap + (uint32_t)fanout;
+  if (weighted) entries += 3 * (uint32_t)fanout + 2 * kChallengerCap;
+  return entries;
 }
 
 // A3_PROFILE: record the start (which = 0) or stop (which = 1) event of the running call
@@ -182,63 +187,85 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
   ctx->node_map_dirty = true;  // until the call has cleaned up after itself
 
   prof_mark(ctx, 0, 0);
-  hipLaunchKernelGGL(a3::k_init_seeds<IdxT>, dim3(blocks_for(num_seeds, 256)), dim3(256), 0, st,
-                     seeds, num_seeds, num_nodes, S, ctx->node_map, ds, validate);
   if (validate) {
+    hipLaunchKernelGGL(a3::k_init_seeds_checked<IdxT>, dim3(blocks_for(num_seeds, 256)), dim3(256),
+                       0, st, seeds, num_seeds, num_nodes, S, ctx->node_map, ds);
     hipLaunchKernelGGL(a3::k_check_seeds<IdxT>, dim3(blocks_for(num_seeds, 256)), dim3(256), 0, st,
                        seeds, num_seeds, num_nodes, ctx->node_map, ds);
-    hipLaunchKernelGGL(a3::k_gate_on_error, dim3(1), dim3(64), 0, st, ds);
+    hipLaunchKernelGGL(a3::k_set_frontier_size, dim3(1), dim3(64), 0, st, ds, (int32_t)num_seeds);
   }
 
   for (int h = 0; h < num_hops; ++h) {
     const int32_t f = fanouts[h];
-    const unsigned dst_tiles = blocks_for(bound_dst[h], a3::kScanTile);
-    const unsigned edge_tiles = blocks_for(bound_edges[h], a3::kScanTile);
-    // a1: degrees -> edge offsets of the block
-    hipLaunchKernelGGL(a3::k_count_degrees<IdxT>, dim3(dst_tiles), dim3(a3::kScanThreads), 0, st, S,
-                       indptr, ds, h, f, ctx->vals, ctx->tile_sums);
-    hipLaunchKernelGGL(a3::k_scan_tile_sums, dim3(1), dim3(a3::kScanThreads), 0, st,
-                       ctx->tile_sums, ctx->tile_offs, ds, h, 0, ctx->blk_indptr[h]);
-    hipLaunchKernelGGL(a3::k_scan_apply, dim3(dst_tiles), dim3(a3::kScanThreads), 0, st, ctx->vals,
+    const unsigned dst_tiles = blocks_for(bound_dst[h], a3::kTile);
+    const unsigned edge_tiles = blocks_for(bound_edges[h], a3::kTile);
+    // a1: degrees -> edge offsets of the block, degree bins
+    a3::FrontierArgs<IdxT> fa;
+    fa.seeds = (h == 0 && !validate) ? seeds : nullptr;
+    fa.num_seeds = num_seeds;
+    fa.S = S;
+    fa.node_map = ctx->node_map;
+    fa.indptr = indptr;
+    fa.st = ds;
+    fa.hop = h;
+    fa.fanout = f;
+    fa.local_off = ctx->local_off;
+    fa.tile_sums = ctx->tile_sums;
+    fa.num_nodes = num_nodes;
+    for (int b = 0; b < a3::kNumBins; ++b) fa.bins[b] = ctx->bins[b];
+    hipLaunchKernelGGL(a3::k_frontier<IdxT>, dim3(dst_tiles), dim3(a3::kTileThreads), 0, st, fa);
+    hipLaunchKernelGGL(a3::k_scan_tiles, dim3(1), dim3(a3::kTileThreads), 0, st, ctx->tile_sums,
                        ctx->tile_offs, ds, h, 0, ctx->blk_indptr[h]);
-    // a2-a4: selection, one wave per frontier node
-    if (bound_dst[h] > 0) {
+    // a2-a4: selection
+    {
       a3::SampleArgs<IdxT> sa;
       sa.indptr = indptr;
       sa.indices = indices;
       sa.cache_map = cache_map;
       sa.S = S;
+      sa.local_off = ctx->local_off;
+      sa.tile_offs = ctx->tile_offs;
       sa.blk_indptr = ctx->blk_indptr[h];
       sa.gid = gid;
       sa.eids = ctx->blk_eids[h];
       sa.node_map = ctx->node_map;
       sa.st = ds;
+      for (int b = 0; b < a3::kNumBins; ++b) sa.bins[b] = ctx->bins[b];
+      sa.num_nodes = num_nodes;
+      sa.cap_edges = ctx->cap_edges[h];
+      // workgroups per role: enough to cover the frontier bound once, at most kMaxRoleBlocks
+      const int64_t nb = std::max<int64_t>(bound_dst[h], 1);
+      sa.role_blocks[0] = (uint32_t)std::min<int64_t>((nb + 63) / 64, kMaxRoleBlocks);
+      sa.role_blocks[1] = (uint32_t)std::min<int64_t>((nb + 31) / 32, kMaxRoleBlocks);
+      sa.role_blocks[2] = (uint32_t)std::min<int64_t>((nb + 15) / 16, kMaxRoleBlocks);
+      sa.role_blocks[3] = (uint32_t)std::min<int64_t>((nb + 3) / 4, kMaxRoleBlocks);
       sa.hop = h;
       sa.fanout = f;
       sa.lambda = lambda_for(f);
       sa.cap = cap_for(sa.lambda);
       sa.xcap = kChallengerCap;
+      sa.lds_per_wave = sample_lds_entries(f, weighted);
       sa.bias_q16 = bias_q16;
       sa.seed_lo = (uint32_t)rng_seed;
       sa.seed_hi = (uint32_t)(rng_seed >> 32);
       sa.weighted = weighted ? 1u : 0u;
       sa.force_radix = (ctx->flags & A3_FORCE_RADIX) ? 1u : 0u;
-      hipLaunchKernelGGL(a3::k_sample<IdxT>, dim3((unsigned)bound_dst[h]), dim3(a3::kWave),
-                         sample_lds_bytes(f, weighted), st, sa);
+      const unsigned grid = sa.role_blocks[0] + sa.role_blocks[1] + sa.role_blocks[2] + sa.role_blocks[3];
+      const size_t lds_bytes = (size_t)sa.lds_per_wave * sizeof(uint64_t) * (a3::kTileThreads / a3::kWave);
+      hipLaunchKernelGGL(a3::k_sample<IdxT>, dim3(grid), dim3(a3::kTileThreads), lds_bytes, st, sa);
     }
     // a5: first occurrences -> numbering of new nodes -> local ids
-    hipLaunchKernelGGL(a3::k_flag_first<IdxT>, dim3(edge_tiles), dim3(a3::kScanThreads), 0, st, gid,
-                       ctx->node_map, ds, h, ctx->first_pos, ctx->vals, ctx->tile_sums);
-    hipLaunchKernelGGL(a3::k_scan_tile_sums, dim3(1), dim3(a3::kScanThreads), 0, st,
-                       ctx->tile_sums, ctx->tile_offs, ds, h, 1, (int32_t*)nullptr);
-    hipLaunchKernelGGL(a3::k_scan_apply, dim3(edge_tiles), dim3(a3::kScanThreads), 0, st, ctx->vals,
-                       ctx->tile_offs, ds, h, 1, ctx->new_rank);
+    hipLaunchKernelGGL(a3::k_flag<IdxT>, dim3(edge_tiles), dim3(a3::kTileThreads), 0, st, gid,
+                       ctx->node_map, ds, h, num_nodes, ctx->first_pos, ctx->local_rank,
+                       ctx->tile_sums);
+    hipLaunchKernelGGL(a3::k_scan_tiles, dim3(1), dim3(a3::kTileThreads), 0, st, ctx->tile_sums,
+                       ctx->tile_offs2, ds, h, 1, (int32_t*)nullptr);
     hipLaunchKernelGGL(a3::k_relabel<IdxT>, dim3(blocks_for(bound_edges[h], 256)), dim3(256), 0, st,
-                       gid, ctx->first_pos, ctx->new_rank, ds, h, S, ctx->node_map,
-                       ctx->blk_indices[h]);
+                       gid, ctx->first_pos, ctx->local_rank, ctx->tile_offs2, ds, h, num_nodes,
+                       ctx->cap_dst[ctx->max_hops], S, ctx->node_map, ctx->blk_indices[h]);
   }
   // leave the relabel map empty for the next call; the same kernel publishes the counts
-  hipLaunchKernelGGL(a3::k_reset_map<IdxT>, dim3(blocks_for(bound_dst[num_hops], 256)), dim3(256),
+  hipLaunchKernelGGL(a3::k_finish_call<IdxT>, dim3(blocks_for(bound_dst[num_hops], 256)), dim3(256),
                      0, st, S, ds, num_hops - 1, num_nodes, ctx->node_map, ctx->h_state_dev);
   prof_mark(ctx, 0, 1);
   A3_HIP(ctx, hipGetLastError());
@@ -247,6 +274,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
   ctx->last_hops = num_hops;
   ctx->last_idx_bytes = (int32_t)sizeof(IdxT);
   ctx->last_bound_in = bound_dst[num_hops];
+  ctx->last_num_nodes = num_nodes;
   return A3_OK;
 }
 
@@ -261,6 +289,11 @@ int sample_finish(a3_ctx* ctx, a3_blocks* out) {
   }
   if (hs.error & a3::kErrHugeRow)
     return fail(ctx, A3_ERR_CAPACITY, "a3_sample_blocks: a CSR row has more than 2^31-1 entries");
+  if (hs.error & a3::kErrInternal)
+    return fail(ctx, A3_ERR_HIP,
+                "a3_sample_blocks: an index left its array (ids in indices/seeds outside the "
+                "graph, or an internal error; guard bits " + std::to_string(hs.error) +
+                    "); outputs are invalid");
   ctx->node_map_dirty = false;
 
   const int num_hops = ctx->last_hops;
@@ -281,13 +314,14 @@ int sample_finish(a3_ctx* ctx, a3_blocks* out) {
 template <typename VecT, typename IdxT, int U, int R, bool kWaveRow>
 void launch_gather_as(a3_ctx* ctx, int log2_g, const void* feat_dev, const void* feat_host,
                       const int32_t* cache_map, const void* ids, int64_t n_ids,
-                      const int32_t* n_ids_dev, int64_t row_bytes, uint32_t vpr, void* out) {
+                      const int32_t* n_ids_dev, int64_t id_limit, int64_t row_bytes, uint32_t vpr,
+                      void* out) {
   const int64_t groups = (n_ids + R - 1) / R;
   const unsigned grid = blocks_for(groups << log2_g, a3::kGatherThreads);
   hipLaunchKernelGGL((a3::k_gather<VecT, IdxT, U, R, kWaveRow>), dim3(grid),
                      dim3(a3::kGatherThreads), 0, ctx->stream, (const char*)feat_dev,
-                     (const char*)feat_host, cache_map, (const IdxT*)ids, n_ids, n_ids_dev, vpr,
-                     row_bytes, log2_g, (VecT*)out);
+                     (const char*)feat_host, cache_map, (const IdxT*)ids, n_ids, n_ids_dev, id_limit,
+                     vpr, row_bytes, log2_g, (VecT*)out);
 }
 
 // lanes per row: the smallest power of two covering the row's vectors, at most a wavefront;
@@ -295,12 +329,12 @@ void launch_gather_as(a3_ctx* ctx, int log2_g, const void* feat_dev, const void*
 template <typename VecT, typename IdxT>
 void launch_gather(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
                    const int32_t* cache_map, const void* ids, int64_t n_ids,
-                   const int32_t* n_ids_dev, int64_t row_bytes, void* out) {
+                   const int32_t* n_ids_dev, int64_t id_limit, int64_t row_bytes, void* out) {
   const uint32_t vpr = (uint32_t)(row_bytes / (int64_t)sizeof(VecT));
   int log2_g = 0;
   while (log2_g < 6 && (1u << log2_g) < vpr) ++log2_g;
 #define A3_GATHER(U, R, W) \
-  launch_gather_as<VecT, IdxT, U, R, W>(ctx, log2_g, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, vpr, out)
+  launch_gather_as<VecT, IdxT, U, R, W>(ctx, log2_g, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, vpr, out)
   if (log2_g < 6) {
     A3_GATHER(1, 4, false);
   } else {
@@ -316,19 +350,19 @@ void launch_gather(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
 template <typename IdxT>
 void gather_by_width(a3_ctx* ctx, int width, const void* feat_dev, const void* feat_host,
                      const int32_t* cache_map, const void* ids, int64_t n_ids,
-                     const int32_t* n_ids_dev, int64_t row_bytes, void* out) {
+                     const int32_t* n_ids_dev, int64_t id_limit, int64_t row_bytes, void* out) {
   switch (width) {
-    case 16: launch_gather<a3::vec16_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, out); break;
-    case 8: launch_gather<a3::vec8_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, out); break;
-    case 4: launch_gather<a3::vec4_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, out); break;
-    default: launch_gather<a3::vec2_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, out); break;
+    case 16: launch_gather<a3::vec16_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, out); break;
+    case 8: launch_gather<a3::vec8_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, out); break;
+    case 4: launch_gather<a3::vec4_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, out); break;
+    default: launch_gather<a3::vec2_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, out); break;
   }
 }
 
 // shared by the two gather entry points; arguments already validated
 int gather_enqueue(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
                    const int32_t* cache_map, const void* ids, int32_t idx_bytes, int64_t n_ids,
-                   const int32_t* n_ids_dev, int64_t row_bytes, void* out) {
+                   const int32_t* n_ids_dev, int64_t id_limit, int64_t row_bytes, void* out) {
   // widest vector that divides the row and keeps every row start aligned in all three buffers
   const uintptr_t align_bits = (uintptr_t)feat_dev | (uintptr_t)feat_host | (uintptr_t)out |
                                (uintptr_t)row_bytes;
@@ -338,9 +372,9 @@ int gather_enqueue(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
   while (width > 2 && (align_bits & (uintptr_t)(width - 1))) width >>= 1;
   prof_mark(ctx, 1, 0);
   if (idx_bytes == 4)
-    gather_by_width<int32_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, out);
+    gather_by_width<int32_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, out);
   else
-    gather_by_width<int64_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, row_bytes, out);
+    gather_by_width<int64_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, out);
   prof_mark(ctx, 1, 1);
   A3_HIP(ctx, hipGetLastError());
   return A3_OK;
@@ -409,17 +443,26 @@ extern "C" int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t
     return rc;
   }
   const int64_t max_items = std::max(max_edges, ctx->cap_dst[max_hops]);
-  ctx->cap_tiles = (max_items + a3::kScanTile - 1) / a3::kScanTile + 1;
+  ctx->cap_tiles = (max_items + a3::kTile - 1) / a3::kTile + 1;
   int rc = A3_OK;
   auto chk = [&](int r) { if (rc == A3_OK) rc = r; };
   chk(dev_alloc(ctx, (int64_t**)&ctx->S, ctx->cap_dst[max_hops]));
   chk(dev_alloc(ctx, (int64_t**)&ctx->gid, max_edges));
-  chk(dev_alloc(ctx, &ctx->vals, max_items));
+  chk(dev_alloc(ctx, &ctx->local_off, ctx->cap_dst[max_hops - 1]));
   chk(dev_alloc(ctx, &ctx->first_pos, max_edges));
-  chk(dev_alloc(ctx, &ctx->new_rank, max_edges));
+  chk(dev_alloc(ctx, &ctx->local_rank, max_edges));
   chk(dev_alloc(ctx, &ctx->tile_sums, ctx->cap_tiles));
   chk(dev_alloc(ctx, &ctx->tile_offs, ctx->cap_tiles));
+  chk(dev_alloc(ctx, &ctx->tile_offs2, ctx->cap_tiles));
+  for (int b = 0; b < a3::kNumBins; ++b) chk(dev_alloc(ctx, &ctx->bins[b], ctx->cap_dst[max_hops - 1]));
   chk(dev_alloc(ctx, &ctx->d_state, 1));
+  if (rc == A3_OK) {
+    static_assert(sizeof(DevState) % sizeof(int32_t) == 0, "DevState is a block of int32");
+    hipLaunchKernelGGL(a3::k_fill_i32, dim3(1), dim3(256), 0, ctx->stream, (int32_t*)ctx->d_state,
+                       (int64_t)(sizeof(DevState) / sizeof(int32_t)), 0);
+    e = hipGetLastError();
+    if (e != hipSuccess) rc = hip_fail(ctx, e, "a3_create: clearing the state block");
+  }
   for (int h = 0; h < max_hops && rc == A3_OK; ++h) {
     chk(dev_alloc(ctx, &ctx->blk_indptr[h], ctx->cap_dst[h] + 1));
     chk(dev_alloc(ctx, &ctx->blk_indices[h], ctx->cap_edges[h]));
@@ -569,7 +612,7 @@ extern "C" int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void*
     return fail(ctx, A3_ERR_HIP, "a3_gather_features: context was created without a device");
   if (n_ids == 0) return A3_OK;
   A3_HIP(ctx, hipSetDevice(ctx->device));
-  return gather_enqueue(ctx, feat_dev, feat_host, cache_map, ids, idx_bytes, n_ids, nullptr,
+  return gather_enqueue(ctx, feat_dev, feat_host, cache_map, ids, idx_bytes, n_ids, nullptr, 0,
                         row_bytes, out);
 }
 
@@ -589,7 +632,8 @@ extern "C" int a3_gather_input_features(a3_ctx* ctx, const void* feat_dev, const
   if (bound == 0) return A3_OK;
   A3_HIP(ctx, hipSetDevice(ctx->device));
   return gather_enqueue(ctx, feat_dev, feat_host, cache_map, ctx->S, ctx->last_idx_bytes, bound,
-                        &ctx->d_state->n_src[ctx->last_hops - 1], row_bytes, out);
+                        &ctx->d_state->n_src[ctx->last_hops - 1], ctx->last_num_nodes, row_bytes,
+                        out);
 }
 
 extern "C" int a3_profile_read(a3_ctx* ctx, int kind, float* ms, int max, int* n) {
@@ -611,3 +655,4 @@ extern "C" int a3_profile_read(a3_ctx* ctx, int kind, float* ms, int max, int* n
   *n = count;
   return A3_OK;
 }
+

@@ -17,7 +17,33 @@ Q = 65536
 DEV = "cuda:0"
 
 
-def _run(name, gammas, check_rows, n_batches=1):
+def _compare_last_hop_by_samples(got, want_prefix, ip_h, ix_h, cm_h, fanouts, bias_q16, rng_seed, n_pick):
+    """The oracle ran all hops but the last.  The last hop's destinations are its sources
+    (identical by the prefix comparison), so any destination's choice can be recomputed alone:
+    check n_pick of them one by one with the oracle's per-node selection, and the whole block
+    through the invariants (which re-derive the relabelling from the CSR with numpy)."""
+    H = len(fanouts)
+    h = H - 1
+    D = want_prefix.input_nodes                      # destinations of the last hop
+    assert got.n_dst[h] == D.shape[0]
+    assert np.array_equal(got.input_nodes[:D.shape[0]].astype(np.int64), D)
+    rnd = np.random.RandomState(123)
+    picks = rnd.choice(D.shape[0], size=min(n_pick, D.shape[0]), replace=False)
+    deg_all = ip_h[D + 1] - ip_h[D]
+    hubs = np.argsort(deg_all)[-50:]                 # always include the widest rows
+    bp, be = got.blk_indptr[h].astype(np.int64), got.blk_eids[h]
+    for i in np.concatenate([picks, hubs]):
+        v = int(D[i])
+        row, deg = int(ip_h[v]), int(ip_h[v + 1] - ip_h[v])
+        weights = None
+        if cm_h is not None and bias_q16 > 65536 and deg > fanouts[h]:
+            nb = ix_h[row:row + deg]
+            weights = np.where(cm_h[nb] >= 0, bias_q16, 65536).astype(np.uint32)
+        chosen = oracle.select(rng_seed, h, v, deg, fanouts[h], weights)
+        assert list(be[bp[i]:bp[i + 1]] - row) == chosen, (i, v, deg)
+
+
+def _run(name, gammas, check_rows, n_batches=1, full_hops=None):
     w = get_config(name)
     t0 = time.time()
     g = make_graph(w.num_nodes, w.mean_degree, w.d_min, w.d_max, w.a, w.symmetric, w.graph_seed,
@@ -42,15 +68,34 @@ def _run(name, gammas, check_rows, n_batches=1):
             torch.cuda.synchronize()
             t1 = time.time()
             got = got_d.to_host()
-            want = oracle.sample_blocks(ip_h, ix_h, seeds, w.fanouts, cm_h, int(gamma * Q), b)
-            t2 = time.time()
-            print(f"[time] gpu {t1 - t0:.3f}s oracle {t2 - t1:.1f}s edges={want.n_edges} "
-                  f"n_src={want.n_src}", flush=True)
-            blocks_equal(got, want)
-            if b == 0 and gamma == gammas[0]:
+            H = len(w.fanouts)
+            if full_hops is None or full_hops >= H:
+                want = oracle.sample_blocks(ip_h, ix_h, seeds, w.fanouts, cm_h, int(gamma * Q), b)
+                t2 = time.time()
+                print(f"[time] gpu {t1 - t0:.3f}s oracle {t2 - t1:.1f}s edges={want.n_edges} "
+                      f"n_src={want.n_src}", flush=True)
+                blocks_equal(got, want)
+                if b == 0 and gamma == gammas[0]:
+                    check_block_invariants(ip_h, ix_h, seeds, w.fanouts, got)
+                ids = want.input_nodes
+            else:
+                # the oracle in full on the first hops, by sampled destinations on the rest
+                assert full_hops == H - 1
+                want = oracle.sample_blocks(ip_h, ix_h, seeds, w.fanouts[:full_hops], cm_h,
+                                            int(gamma * Q), b)
+                for h in range(full_hops):
+                    assert np.array_equal(got.blk_indptr[h], want.blk_indptr[h])
+                    assert np.array_equal(got.blk_indices[h], want.blk_indices[h])
+                    assert np.array_equal(got.blk_eids[h], want.blk_eids[h])
+                assert got.n_src[:full_hops] == want.n_src
+                _compare_last_hop_by_samples(got, want, ip_h, ix_h, cm_h, w.fanouts, int(gamma * Q),
+                                             b, 4000)
                 check_block_invariants(ip_h, ix_h, seeds, w.fanouts, got)
+                t2 = time.time()
+                print(f"[time] gpu {t1 - t0:.3f}s oracle+checks {t2 - t1:.1f}s edges={got.n_edges} "
+                      f"n_src={got.n_src}", flush=True)
+                ids = got.input_nodes.astype(np.int64)
             # gathered rows: every row against the generator's table through the split, via the oracle
-            ids = want.input_nodes
             if check_rows < ids.shape[0]:
                 pick = np.unique(np.linspace(0, ids.shape[0] - 1, check_rows).astype(np.int64))
             else:
@@ -82,4 +127,4 @@ def test_copurchase_full_size_uniform_and_biased():
 
 
 def test_citation_full_size():
-    _run("citation", [1.0], check_rows=200_000)
+    _run("citation", [1.0], check_rows=200_000, full_hops=2)
