@@ -19,6 +19,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+# plain integer ALU peak: 256 CUs x 64 lanes x 2.4 GHz 32-bit lane-operations per second
+ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+# lane-operations the method needs per scanned neighbour slot: a quarter of a Philox4x32-10 block
+# (20 32x32->64 multiplies at a quarter of the 32-bit rate = 80, plus 20 three-way xors) and one
+# comparison of the draw
+OPS_PER_SLOT = (20 * 4 + 20) / 4 + 1
 
 
 def parse():
@@ -38,6 +44,18 @@ def parse():
                    help="also run plain device copies of 256 MiB (a known size) so that a rocprofv3 "
                         "--pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
     return p.parse_args()
+
+
+def recorded_traffic(workload):
+    """HBM bytes per k_gather launch measured with rocprofv3 --pmc (a summary under profiles/)."""
+    path = os.path.join(ROOT, "profiles", "%s_gather_pmc.txt" % workload)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -91,9 +109,10 @@ def main():
 
     n_edges = n_in = 0
     last_ids = None
+    last_blocks = None
 
     def step(b, timed):
-        nonlocal n_edges, n_in, last_ids
+        nonlocal n_edges, n_in, last_ids, last_blocks
         # queue sampling, then the gather of its input nodes (row count taken on the device),
         # then wait for the sampling counts: the host never stalls the GPU between the two
         ctx.sample_blocks_begin(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b)
@@ -105,6 +124,7 @@ def main():
             n_edges += sum(blocks.n_edges)
             n_in += rows
             last_ids = blocks.input_nodes
+            last_blocks = blocks
         return blocks
 
     if args.pmc_calibration:
@@ -114,6 +134,15 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+        # the same with the library's own gather kernel on a known volume: ids 0..n-1, no device
+        # map, i.e. a plain copy of n rows (read n*row_bytes, write n*row_bytes)
+        n_cal = min(100_000, split.n_cached)
+        cal_ids = torch.arange(n_cal, dtype=w.idx_dtype, device=dev)
+        for _ in range(3):
+            ctx.gather_features(split.feat_dev, None, None, cal_ids, out=out[:n_cal])
+        torch.cuda.synchronize()
+        print("pmc calibration: 3 x 256 MiB device copies, then 3 x identity k_gather of %d rows x %d B"
+              % (n_cal, row_bytes), file=sys.stderr)
     for b in range(W):
         step(b, False)
     torch.cuda.synchronize()
@@ -132,6 +161,20 @@ def main():
     # hit rate of the last timed batch (outside the timed region)
     ids_l = last_ids.long()
     hit_rate = float((d_cm[ids_l] >= 0).float().mean().item()) if ids_l.numel() else 1.0
+
+    # neighbour slots the last timed batch had to draw for (nodes with degree above the fanout)
+    scanned = 0
+    for h, f in enumerate(w.fanouts):
+        dst = ids_l[:last_blocks.n_dst[h]]
+        deg = g.indptr[dst + 1] - g.indptr[dst]
+        scanned += int(deg[deg > f].sum().item())
+    scan_rate = scanned / (ms_sample / K * 1e-3)
+
+    # counters cannot be read from inside this process: the figure comes from the committed
+    # rocprofv3 --pmc summary of this same command, and only for the configuration it was taken on
+    traffic = args.traffic_bytes
+    if traffic is None and args.batch is None and args.cache_frac is None and args.bias_rate is None:
+        traffic = recorded_traffic(w.name)
 
     gather_payload_gbps = n_in * row_bytes / (ms_gather * 1e-3) / 1e9
     algo_bytes_per_launch = (n_in / K) * (2 * row_bytes + ib + 4)
@@ -163,9 +206,15 @@ def main():
         "edges_per_step": n_edges / K,
         "input_rows_per_step": n_in / K,
         "cache_hit_rate": hit_rate,
+        "scanned_slots_per_step": scanned,
+        "roofline_sampling": {"kernel": "k_sample (all hops, with the relabel kernels around it)",
+                              "bound": "alu", "achieved": scan_rate * OPS_PER_SLOT / 1e12,
+                              "peak": ALU_PEAK_TOPS, "unit": "Tops/s (32-bit integer lane-operations)",
+                              "frac": scan_rate * OPS_PER_SLOT / 1e12 / ALU_PEAK_TOPS,
+                              "slots_per_s": scan_rate, "ops_per_slot": OPS_PER_SLOT},
         "roofline": {"kernel": "k_gather", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": args.traffic_bytes,
+                     "traffic": traffic,
                      "algorithmic_bytes_per_launch": algo_bytes_per_launch,
                      "avg_launch_seconds": gather_avg_s},
     }
