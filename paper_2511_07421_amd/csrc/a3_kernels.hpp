@@ -261,7 +261,6 @@ struct SampleArgs {
   uint32_t lds_per_wave;  // uint64 entries of LDS per wavefront
   uint32_t bias_q16;
   uint32_t seed_lo, seed_hi;
-  uint32_t weighted;
   uint32_t force_radix;
 };
 
@@ -341,74 +340,72 @@ __device__ __forceinline__ uint32_t draw_floor_for_key(uint64_t BK, uint32_t w_q
   return (uint32_t)xmin;
 }
 
-// ---- one wavefront, one node of any degree ------------------------------------------------------
-template <typename IdxT>
-__device__ void sample_node_wave(const SampleArgs<IdxT>& a, int64_t i, int32_t n_dst, uint64_t* lds) {
+__device__ __forceinline__ uint64_t readlane_u64(uint64_t v, uint32_t src_lane) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int32_t)(uint32_t)v, (int32_t)src_lane);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int32_t)(uint32_t)(v >> 32), (int32_t)src_lane);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// Ranking of up to 64*NK candidates held NK per lane in registers (candidate j lives in lane
+// j % 64, register j / 64).  Every candidate is broadcast once through the scalar unit and
+// compared by all lanes: no LDS traffic, no waits.  Candidates with rank < m are the m best;
+// each selected candidate's output position is its number of selected candidates with a smaller
+// slot.  Calls on_selected(rank, position, draw-order key) for every selected candidate.
+template <int NK, typename OnSelected>
+__device__ __forceinline__ void rank_in_registers(const uint64_t* cand, uint32_t cnt, uint32_t m,
+                                                  OnSelected on_selected) {
   const uint32_t lane = lane_id();
-  const int64_t v = (int64_t)a.S[i];
-  if (v < 0 || v >= a.num_nodes) return;  // flagged by k_frontier, which gave it zero edges
-  const int64_t row = a.indptr[v];
-  int64_t deg64 = a.indptr[v + 1] - row;
-  if (deg64 < 0) deg64 = 0;
-  if (deg64 > 0x7FFFFFFF) {
-    if (lane == 0) atomicOr(&a.st->error, kErrHugeRow);
-    deg64 = 0x7FFFFFFF;
-  }
-  const uint32_t deg = (uint32_t)deg64;
-  const uint32_t f = (uint32_t)a.fanout;
-  const int32_t base = a.tile_offs[i >> kTileShift] + a.local_off[i];
-  if (lane == 0) a.blk_indptr[i] = base;
-  const Emitter<IdxT> emit{a.indices, a.gid, a.eids, a.node_map, row, base, n_dst, a.num_nodes, a.cap_edges, &a.st->error};
-
-  if (deg <= f) {  // keep every neighbour, no draw
-    for (uint32_t s = lane; s < deg; s += kWave) emit(s, s);
-    return;
-  }
-  const uint32_t m = f;
-  const PhiloxKey pk{(uint32_t)(uint64_t)v, (uint32_t)((uint64_t)v >> 32), (uint32_t)a.hop,
-                     a.seed_lo, a.seed_hi};
-  const uint32_t n_quads = (deg + 3) >> 2;
-
-  uint64_t* cand = lds;          // [cap]
-  uint64_t* selk = cand + a.cap; // [m] draw-order keys of the m best draws
-
-  // ---- the m largest draws (order: x descending, slot ascending) --------------------------
-  // keep slots whose draw clears a threshold set so that about lambda survive, rank those
-  uint32_t X0 = 0;
-  if (deg > a.lambda)
-    X0 = (uint32_t)((1ull << 32) - ((((uint64_t)a.lambda << 32) + deg - 1) / deg));
-  uint32_t cnt = 0;  // same value in every lane
-  if (!a.force_radix) {
-    for (uint32_t q0 = 0; q0 < n_quads; q0 += kWave) {
-      const uint32_t q = q0 + lane;
-      uint32_t x[4];
-      philox4x32_10(q, pk, x);
+  uint64_t mine[NK];
+  uint32_t rank[NK];
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const uint32_t s = 4u * q + (uint32_t)w;
-        const bool pass = (s < deg) && (x[w] >= X0);
-        const uint64_t mask = __ballot(pass);
-        if (mask) {
-          if (pass) {
-            const uint32_t idx = cnt + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-            if (idx < a.cap) cand[idx] = draw_order_key(x[w], s);
-          }
-          cnt += (uint32_t)__popcll(mask);
-        }
-      }
-    }
-    wave_sync();
+  for (int k = 0; k < NK; ++k) {
+    const uint32_t idx = (uint32_t)k * kWave + lane;
+    mine[k] = idx < cnt ? cand[idx] : ~0ull;  // padding loses against everything
+    rank[k] = 0;
   }
-  if (!a.force_radix && cnt >= m && cnt <= a.cap) {
-    for (uint32_t j = lane; j < cnt; j += kWave) {
-      const uint64_t mine = cand[j];
-      uint32_t r = 0;
-      for (uint32_t t = 0; t < cnt; ++t) r += cand[t] < mine ? 1u : 0u;
-      if (r < m) selk[r] = mine;
+#pragma unroll
+  for (int k2 = 0; k2 < NK; ++k2) {
+    const uint32_t lim = cnt > (uint32_t)k2 * kWave ? min(cnt - (uint32_t)k2 * kWave, (uint32_t)kWave) : 0u;
+    for (uint32_t t = 0; t < lim; ++t) {
+      const uint64_t other = readlane_u64(mine[k2], t);
+#pragma unroll
+      for (int k = 0; k < NK; ++k) rank[k] += other < mine[k] ? 1u : 0u;
     }
-  } else {
+  }
+  bool sel[NK];
+  uint32_t pos[NK];
+#pragma unroll
+  for (int k = 0; k < NK; ++k) {
+    sel[k] = ((uint32_t)k * kWave + lane < cnt) && rank[k] < m;
+    pos[k] = 0;
+  }
+#pragma unroll
+  for (int k2 = 0; k2 < NK; ++k2) {
+    uint64_t pending = __ballot(sel[k2]);
+    while (pending) {
+      const uint32_t t = (uint32_t)__ffsll((long long)pending) - 1u;
+      pending &= pending - 1;
+      const uint32_t other_slot =
+          (uint32_t)__builtin_amdgcn_readlane((int32_t)(uint32_t)mine[k2], (int32_t)t);
+#pragma unroll
+      for (int k = 0; k < NK; ++k) pos[k] += other_slot < (uint32_t)mine[k] ? 1u : 0u;
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < NK; ++k)
+    if (sel[k]) on_selected(rank[k], pos[k], mine[k]);
+}
+
+// Exhaustive selection for one wavefront: the m-th largest draw value is found bit by bit, the
+// draws being recomputed in every pass; draws equal to it are taken in slot order.  Writes the m
+// winners' draw-order keys to selk.  Used when the threshold kept too few or too many
+// candidates (about one node in 10^5); kept out of line so that it costs the usual path no
+// registers.
+__device__ __noinline__ void radix_select(const PhiloxKey pk, uint32_t deg, uint32_t m, uint64_t* selk) {
+  const uint32_t lane = lane_id();
+  const uint32_t n_quads = (deg + 3) >> 2;
+  {
     // exhaustive path: find the m-th largest draw value bit by bit, recomputing the draws
-    if (lane == 0) atomicAdd(&a.st->n_radix, 1);
     uint32_t kth = 0;
     for (int bit = 31; bit >= 0; --bit) {
       const uint32_t trial = kth | (1u << bit);
@@ -459,10 +456,104 @@ __device__ void sample_node_wave(const SampleArgs<IdxT>& a, int64_t i, int32_t n
       run_eq += wave_sum_u32(eqc);
       run_sel += wave_sum_u32(selc);
     }
+    }
+}
+
+// ---- one wavefront, one node of any degree ------------------------------------------------------
+template <typename IdxT, bool kWeighted>
+__device__ void sample_node_wave(const SampleArgs<IdxT>& a, int64_t i, int32_t n_dst, uint64_t* lds) {
+  const uint32_t lane = lane_id();
+  const int64_t v = (int64_t)a.S[i];
+  if (v < 0 || v >= a.num_nodes) return;  // flagged by k_frontier, which gave it zero edges
+  const int64_t row = a.indptr[v];
+  int64_t deg64 = a.indptr[v + 1] - row;
+  if (deg64 < 0) deg64 = 0;
+  if (deg64 > 0x7FFFFFFF) {
+    if (lane == 0) atomicOr(&a.st->error, kErrHugeRow);
+    deg64 = 0x7FFFFFFF;
+  }
+  const uint32_t deg = (uint32_t)deg64;
+  const uint32_t f = (uint32_t)a.fanout;
+  const int32_t base = a.tile_offs[i >> kTileShift] + a.local_off[i];
+  if (lane == 0) a.blk_indptr[i] = base;
+  const Emitter<IdxT> emit{a.indices, a.gid, a.eids, a.node_map, row, base, n_dst, a.num_nodes, a.cap_edges, &a.st->error};
+
+  if (deg <= f) {  // keep every neighbour, no draw
+    for (uint32_t s = lane; s < deg; s += kWave) emit(s, s);
+    return;
+  }
+  const uint32_t m = f;
+  const PhiloxKey pk{(uint32_t)(uint64_t)v, (uint32_t)((uint64_t)v >> 32), (uint32_t)a.hop,
+                     a.seed_lo, a.seed_hi};
+  const uint32_t n_quads = (deg + 3) >> 2;
+
+  uint64_t* cand = lds;          // [cap]
+  uint64_t* selk = cand + a.cap; // [m] draw-order keys of the m best draws
+
+  // ---- the m largest draws (order: x descending, slot ascending) --------------------------
+  // keep slots whose draw clears a threshold set so that about lambda survive, rank those
+  // (any threshold gives the same result; this one only sets how many candidates survive)
+  uint32_t X0 = 0;
+  if (deg > a.lambda) {
+    const float keep = __fdividef((float)a.lambda, (float)deg) * 4294967296.0f;  // < 2^32
+    X0 = 0u - (uint32_t)keep;
+  }
+  uint32_t cnt = 0;  // same value in every lane
+  if (!a.force_radix) {
+    for (uint32_t q0 = 0; q0 < n_quads; q0 += kWave) {
+      const uint32_t q = q0 + lane;
+      uint32_t x[4];
+      philox4x32_10(q, pk, x);
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t s = 4u * q + (uint32_t)w;
+        const bool pass = (s < deg) && (x[w] >= X0);
+        const uint64_t mask = __ballot(pass);
+        if (mask) {
+          if (pass) {
+            const uint32_t idx = cnt + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+            if (idx < a.cap) cand[idx] = draw_order_key(x[w], s);
+          }
+          cnt += (uint32_t)__popcll(mask);
+        }
+      }
+    }
+    wave_sync();
+  }
+  if (!a.force_radix && cnt >= m && cnt <= a.cap && cnt <= 4 * kWave) {
+    // the usual case: few candidates, ranked in registers.  With equal weights the winners are
+    // final and are written out at once; otherwise they become the first reservoir.
+    constexpr bool final_now = !kWeighted;
+    auto take = [&](uint32_t rank, uint32_t pos, uint64_t key) {
+      if (final_now)
+        emit(pos, (uint32_t)key);
+      else
+        selk[rank] = key;
+    };
+    if (cnt <= kWave)
+      rank_in_registers<1>(cand, cnt, m, take);
+    else if (cnt <= 2 * kWave)
+      rank_in_registers<2>(cand, cnt, m, take);
+    else
+      rank_in_registers<4>(cand, cnt, m, take);
+    if (final_now) {
+      wave_sync();  // the candidate buffer is reused by this wavefront's next node
+      return;
+    }
+  } else if (!a.force_radix && cnt >= m && cnt <= a.cap) {
+    for (uint32_t j = lane; j < cnt; j += kWave) {
+      const uint64_t mine = cand[j];
+      uint32_t r = 0;
+      for (uint32_t t = 0; t < cnt; ++t) r += cand[t] < mine ? 1u : 0u;
+      if (r < m) selk[r] = mine;
+    }
+  } else {
+    if (lane == 0) atomicAdd(&a.st->n_radix, 1);
+    radix_select(pk, deg, m, selk);
   }
   wave_sync();
 
-  if (!a.weighted) {
+  if (!kWeighted) {
     // all weights equal: the m largest draws are the answer; emit in slot order
     for (uint32_t j = lane; j < m; j += kWave) {
       const uint32_t s = (uint32_t)selk[j];
@@ -552,7 +643,7 @@ __device__ void sample_node_wave(const SampleArgs<IdxT>& a, int64_t i, int32_t n
 // The draws of a lane are one Philox block.  Selection is m rounds of "best remaining slot of
 // the group" (lane-local best, butterfly reduction, lowest lane among equals), which costs
 // O(m log G) instead of ranking every slot against every other.
-template <typename IdxT, int G>
+template <typename IdxT, int G, bool kWeighted>
 __device__ void sample_node_group(const SampleArgs<IdxT>& a, int64_t i, int32_t n_dst) {
   const uint32_t lane = lane_id();
   const uint32_t gl = lane & (G - 1);       // lane inside the group
@@ -580,7 +671,7 @@ __device__ void sample_node_group(const SampleArgs<IdxT>& a, int64_t i, int32_t 
 #pragma unroll
   for (int w = 0; w < 4; ++w) alive |= (4u * gl + w < deg) ? (1u << w) : 0u;
   uint64_t K[4] = {0, 0, 0, 0};
-  if (a.weighted) {
+  if (kWeighted) {
     bool cached[4];
     bool any_c = false, any_u = false;
 #pragma unroll
@@ -657,7 +748,7 @@ __device__ void sample_node_group(const SampleArgs<IdxT>& a, int64_t i, int32_t 
     if ((chosen >> w) & 1u) emit(below + own_before[w], 4u * gl + w);
 }
 
-template <typename IdxT, int G>
+template <typename IdxT, int G, bool kWeighted>
 __device__ __forceinline__ void run_group_role(const SampleArgs<IdxT>& a, int bin, uint32_t block_in_role,
                                                uint32_t blocks_in_role, int32_t n_dst) {
   const int64_t count = a.st->bin_count[bin];
@@ -665,20 +756,20 @@ __device__ __forceinline__ void run_group_role(const SampleArgs<IdxT>& a, int bi
   for (int64_t item = (int64_t)block_in_role * (kTileThreads / G) + threadIdx.x / G; item < count;
        item += groups) {
     const int64_t i = a.bins[bin][item];
-    if (i >= 0 && i < n_dst) sample_node_group<IdxT, G>(a, i, n_dst);
+    if (i >= 0 && i < n_dst) sample_node_group<IdxT, G, kWeighted>(a, i, n_dst);
   }
 }
 
-template <typename IdxT>
+template <typename IdxT, bool kWeighted>
 __global__ __launch_bounds__(kTileThreads) void k_sample(const SampleArgs<IdxT> a) {
   extern __shared__ uint64_t lds[];
   const int32_t n_dst = a.st->n_dst[a.hop];
   uint32_t b = blockIdx.x;
-  if (b < a.role_blocks[0]) return run_group_role<IdxT, 4>(a, 0, b, a.role_blocks[0], n_dst);
+  if (b < a.role_blocks[0]) return run_group_role<IdxT, 4, kWeighted>(a, 0, b, a.role_blocks[0], n_dst);
   b -= a.role_blocks[0];
-  if (b < a.role_blocks[1]) return run_group_role<IdxT, 8>(a, 1, b, a.role_blocks[1], n_dst);
+  if (b < a.role_blocks[1]) return run_group_role<IdxT, 8, kWeighted>(a, 1, b, a.role_blocks[1], n_dst);
   b -= a.role_blocks[1];
-  if (b < a.role_blocks[2]) return run_group_role<IdxT, 16>(a, 2, b, a.role_blocks[2], n_dst);
+  if (b < a.role_blocks[2]) return run_group_role<IdxT, 16, kWeighted>(a, 2, b, a.role_blocks[2], n_dst);
   b -= a.role_blocks[2];
   // wide nodes, one wavefront each: hubs first, then the rest, dealt round-robin over the
   // wavefronts of this role so that the hubs land on different wavefronts
@@ -691,7 +782,7 @@ __global__ __launch_bounds__(kTileThreads) void k_sample(const SampleArgs<IdxT> 
   const int64_t waves = (int64_t)a.role_blocks[3] * (kTileThreads / kWave);
   for (int64_t t = (int64_t)b * (kTileThreads / kWave) + wave; t < n_hub + n_wide; t += waves) {
     const int64_t i = t < n_hub ? a.bins[4][t] : a.bins[3][t - n_hub];
-    if (i >= 0 && i < n_dst) sample_node_wave<IdxT>(a, i, n_dst, my_lds);
+    if (i >= 0 && i < n_dst) sample_node_wave<IdxT, kWeighted>(a, i, n_dst, my_lds);
   }
 }
 

@@ -248,11 +248,13 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       sa.bias_q16 = bias_q16;
       sa.seed_lo = (uint32_t)rng_seed;
       sa.seed_hi = (uint32_t)(rng_seed >> 32);
-      sa.weighted = weighted ? 1u : 0u;
       sa.force_radix = (ctx->flags & A3_FORCE_RADIX) ? 1u : 0u;
       const unsigned grid = sa.role_blocks[0] + sa.role_blocks[1] + sa.role_blocks[2] + sa.role_blocks[3];
       const size_t lds_bytes = (size_t)sa.lds_per_wave * sizeof(uint64_t) * (a3::kTileThreads / a3::kWave);
-      hipLaunchKernelGGL(a3::k_sample<IdxT>, dim3(grid), dim3(a3::kTileThreads), lds_bytes, st, sa);
+      if (weighted)
+        hipLaunchKernelGGL((a3::k_sample<IdxT, true>), dim3(grid), dim3(a3::kTileThreads), lds_bytes, st, sa);
+      else
+        hipLaunchKernelGGL((a3::k_sample<IdxT, false>), dim3(grid), dim3(a3::kTileThreads), lds_bytes, st, sa);
     }
     // a5: first occurrences -> numbering of new nodes -> local ids
     hipLaunchKernelGGL(a3::k_flag<IdxT>, dim3(edge_tiles), dim3(a3::kTileThreads), 0, st, gid,
