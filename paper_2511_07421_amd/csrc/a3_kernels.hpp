@@ -31,9 +31,9 @@ constexpr int32_t kErrFrontierId = 8, kErrFlagId = 16, kErrFirstPosNeg = 32, kEr
 constexpr int32_t kErrInternal = 8 | 16 | 32 | 64 | 128 | 256;
 
 // frontier nodes by degree: 0: deg <= 16, 1: <= 32, 2: <= 64 (lane groups of 4, 8, 16, four
-// slots per lane), 3: <= kHubDegree (one wavefront), 4: hubs (one wavefront, served first)
+// slots per lane), 3: <= kHubDegree (one wavefront), 4: hubs (one workgroup)
 constexpr int kNumBins = 5;
-constexpr uint32_t kHubDegree = 2048;
+constexpr uint32_t kHubDegree = 4096;
 
 // Counts of the running call, written by kernels, copied to the host by the last kernel.
 struct DevState {
@@ -252,7 +252,7 @@ struct SampleArgs {
   const int32_t* bins[kNumBins];
   int64_t num_nodes;
   int64_t cap_edges;         // entries in gid / eids (arena capacity of this hop)
-  uint32_t role_blocks[4];   // workgroups serving bins 0, 1, 2 and the wide nodes (bins 4 then 3)
+  uint32_t role_blocks[5];   // workgroups serving bins 0, 1, 2 (lane groups), 3 (wide), 4 (hubs)
   int32_t hop;
   int32_t fanout;
   uint32_t lambda;    // expected number of candidates kept by the draw threshold
@@ -346,54 +346,77 @@ __device__ __forceinline__ uint64_t readlane_u64(uint64_t v, uint32_t src_lane) 
   return ((uint64_t)hi << 32) | lo;
 }
 
-// Ranking of up to 64*NK candidates held NK per lane in registers (candidate j lives in lane
-// j % 64, register j / 64).  Every candidate is broadcast once through the scalar unit and
-// compared by all lanes: no LDS traffic, no waits.  Candidates with rank < m are the m best;
-// each selected candidate's output position is its number of selected candidates with a smaller
-// slot.  Calls on_selected(rank, position, draw-order key) for every selected candidate.
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {  // set bits of mask in lower lanes
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// The m smallest of up to 64*NK keys held NK per lane in registers (key j lives in lane j % 64,
+// register j / 64; keys are distinct).  Quickselect on wave-wide masks: a pivot is broadcast
+// through the scalar unit, one comparison per lane and a ballot split the still undecided keys;
+// about 2 ln(cnt) rounds of a dozen instructions, no LDS traffic.  The keys arrive in ascending
+// slot order, so a chosen key's output position is the number of chosen keys before it.
+// Calls on_selected(position, key) for each of the m chosen keys.
 template <int NK, typename OnSelected>
-__device__ __forceinline__ void rank_in_registers(const uint64_t* cand, uint32_t cnt, uint32_t m,
-                                                  OnSelected on_selected) {
+__device__ __forceinline__ void select_in_registers(const uint64_t* cand, uint32_t cnt, uint32_t m,
+                                                    OnSelected on_selected) {
   const uint32_t lane = lane_id();
-  uint64_t mine[NK];
-  uint32_t rank[NK];
+  uint64_t mine[NK], active[NK], chosen[NK];
 #pragma unroll
   for (int k = 0; k < NK; ++k) {
     const uint32_t idx = (uint32_t)k * kWave + lane;
-    mine[k] = idx < cnt ? cand[idx] : ~0ull;  // padding loses against everything
-    rank[k] = 0;
+    mine[k] = idx < cnt ? cand[idx] : ~0ull;
+    const uint32_t n_k = cnt > (uint32_t)k * kWave ? min(cnt - (uint32_t)k * kWave, (uint32_t)kWave) : 0u;
+    active[k] = n_k >= (uint32_t)kWave ? ~0ull : ((1ull << n_k) - 1ull);
+    chosen[k] = 0;
   }
+  uint32_t need = m, n_active = cnt;  // choose `need` of the n_active active keys; same in all lanes
+  while (need > 0) {
+    if (n_active == need) {
 #pragma unroll
-  for (int k2 = 0; k2 < NK; ++k2) {
-    const uint32_t lim = cnt > (uint32_t)k2 * kWave ? min(cnt - (uint32_t)k2 * kWave, (uint32_t)kWave) : 0u;
-    for (uint32_t t = 0; t < lim; ++t) {
-      const uint64_t other = readlane_u64(mine[k2], t);
+      for (int k = 0; k < NK; ++k) chosen[k] |= active[k];
+      break;
+    }
+    // pivot: the first undecided key
+    uint64_t pivot = 0;
+    int pivot_reg = -1;
+    uint64_t pivot_bit = 0;
 #pragma unroll
-      for (int k = 0; k < NK; ++k) rank[k] += other < mine[k] ? 1u : 0u;
+    for (int k = 0; k < NK; ++k) {
+      if (pivot_reg < 0 && active[k] != 0) {
+        const uint32_t pl = (uint32_t)__ffsll((long long)active[k]) - 1u;
+        pivot = readlane_u64(mine[k], pl);
+        pivot_reg = k;
+        pivot_bit = 1ull << pl;
+      }
+    }
+    uint64_t less[NK];
+    uint32_t n_less = 0;
+#pragma unroll
+    for (int k = 0; k < NK; ++k) {
+      less[k] = __ballot(mine[k] < pivot) & active[k];
+      n_less += (uint32_t)__popcll(less[k]);
+    }
+    if (n_less >= need) {  // all wanted keys are below the pivot
+#pragma unroll
+      for (int k = 0; k < NK; ++k) active[k] = less[k];
+      n_active = n_less;
+    } else {               // everything below the pivot and the pivot itself are in
+#pragma unroll
+      for (int k = 0; k < NK; ++k) {
+        const uint64_t taken = less[k] | (k == pivot_reg ? pivot_bit : 0ull);
+        chosen[k] |= taken;
+        active[k] &= ~taken;
+      }
+      need -= n_less + 1;
+      n_active -= n_less + 1;
     }
   }
-  bool sel[NK];
-  uint32_t pos[NK];
+  uint32_t before = 0;
 #pragma unroll
   for (int k = 0; k < NK; ++k) {
-    sel[k] = ((uint32_t)k * kWave + lane < cnt) && rank[k] < m;
-    pos[k] = 0;
+    if ((chosen[k] >> lane) & 1ull) on_selected(before + lanes_below(chosen[k]), mine[k]);
+    before += (uint32_t)__popcll(chosen[k]);
   }
-#pragma unroll
-  for (int k2 = 0; k2 < NK; ++k2) {
-    uint64_t pending = __ballot(sel[k2]);
-    while (pending) {
-      const uint32_t t = (uint32_t)__ffsll((long long)pending) - 1u;
-      pending &= pending - 1;
-      const uint32_t other_slot =
-          (uint32_t)__builtin_amdgcn_readlane((int32_t)(uint32_t)mine[k2], (int32_t)t);
-#pragma unroll
-      for (int k = 0; k < NK; ++k) pos[k] += other_slot < (uint32_t)mine[k] ? 1u : 0u;
-    }
-  }
-#pragma unroll
-  for (int k = 0; k < NK; ++k)
-    if (sel[k]) on_selected(rank[k], pos[k], mine[k]);
 }
 
 // Exhaustive selection for one wavefront: the m-th largest draw value is found bit by bit, the
@@ -460,8 +483,12 @@ __device__ __noinline__ void radix_select(const PhiloxKey pk, uint32_t deg, uint
 }
 
 // ---- one wavefront, one node of any degree ------------------------------------------------------
+// cand [cap] and rest [m (+ 3 m + 2 xcap when weighted)] are this wavefront's LDS buffers.  With
+// prefiltered set, cand already holds pre_cnt candidates in slot order (a workgroup scanned the
+// row together) and the scan is skipped.
 template <typename IdxT, bool kWeighted>
-__device__ void sample_node_wave(const SampleArgs<IdxT>& a, int64_t i, int32_t n_dst, uint64_t* lds) {
+__device__ void sample_node_wave(const SampleArgs<IdxT>& a, int64_t i, int32_t n_dst, uint64_t* cand,
+                                 uint64_t* rest, bool prefiltered, uint32_t pre_cnt) {
   const uint32_t lane = lane_id();
   const int64_t v = (int64_t)a.S[i];
   if (v < 0 || v >= a.num_nodes) return;  // flagged by k_frontier, which gave it zero edges
@@ -487,8 +514,7 @@ __device__ void sample_node_wave(const SampleArgs<IdxT>& a, int64_t i, int32_t n
                      a.seed_lo, a.seed_hi};
   const uint32_t n_quads = (deg + 3) >> 2;
 
-  uint64_t* cand = lds;          // [cap]
-  uint64_t* selk = cand + a.cap; // [m] draw-order keys of the m best draws
+  uint64_t* selk = rest;  // [m] draw-order keys of the m best draws
 
   // ---- the m largest draws (order: x descending, slot ascending) --------------------------
   // keep slots whose draw clears a threshold set so that about lambda survive, rank those
@@ -498,44 +524,50 @@ __device__ void sample_node_wave(const SampleArgs<IdxT>& a, int64_t i, int32_t n
     const float keep = __fdividef((float)a.lambda, (float)deg) * 4294967296.0f;  // < 2^32
     X0 = 0u - (uint32_t)keep;
   }
-  uint32_t cnt = 0;  // same value in every lane
-  if (!a.force_radix) {
+  uint32_t cnt = pre_cnt;  // same value in every lane
+  if (!a.force_radix && !prefiltered) {
     for (uint32_t q0 = 0; q0 < n_quads; q0 += kWave) {
       const uint32_t q = q0 + lane;
       uint32_t x[4];
       philox4x32_10(q, pk, x);
+      bool pass[4];
+      uint64_t mk[4];
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        const uint32_t s = 4u * q + (uint32_t)w;
-        const bool pass = (s < deg) && (x[w] >= X0);
-        const uint64_t mask = __ballot(pass);
-        if (mask) {
-          if (pass) {
-            const uint32_t idx = cnt + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-            if (idx < a.cap) cand[idx] = draw_order_key(x[w], s);
+        pass[w] = (4u * q + (uint32_t)w < deg) && (x[w] >= X0);
+        mk[w] = __ballot(pass[w]);
+      }
+      if (mk[0] | mk[1] | mk[2] | mk[3]) {
+        // append in slot order: all passing slots of lower lanes first, then the own words
+        uint32_t idx = cnt + lanes_below(mk[0]) + lanes_below(mk[1]) + lanes_below(mk[2]) + lanes_below(mk[3]);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          if (pass[w]) {
+            if (idx < a.cap) cand[idx] = draw_order_key(x[w], 4u * q + (uint32_t)w);
+            ++idx;
           }
-          cnt += (uint32_t)__popcll(mask);
         }
+        cnt += (uint32_t)(__popcll(mk[0]) + __popcll(mk[1]) + __popcll(mk[2]) + __popcll(mk[3]));
       }
     }
     wave_sync();
   }
   if (!a.force_radix && cnt >= m && cnt <= a.cap && cnt <= 4 * kWave) {
-    // the usual case: few candidates, ranked in registers.  With equal weights the winners are
-    // final and are written out at once; otherwise they become the first reservoir.
+    // the usual case: few candidates, selected in registers.  With equal weights the winners
+    // are final and are written out at once; otherwise they become the first reservoir.
     constexpr bool final_now = !kWeighted;
-    auto take = [&](uint32_t rank, uint32_t pos, uint64_t key) {
+    auto take = [&](uint32_t pos, uint64_t key) {
       if (final_now)
         emit(pos, (uint32_t)key);
       else
-        selk[rank] = key;
+        selk[pos] = key;
     };
     if (cnt <= kWave)
-      rank_in_registers<1>(cand, cnt, m, take);
+      select_in_registers<1>(cand, cnt, m, take);
     else if (cnt <= 2 * kWave)
-      rank_in_registers<2>(cand, cnt, m, take);
+      select_in_registers<2>(cand, cnt, m, take);
     else
-      rank_in_registers<4>(cand, cnt, m, take);
+      select_in_registers<4>(cand, cnt, m, take);
     if (final_now) {
       wave_sync();  // the candidate buffer is reused by this wavefront's next node
       return;
@@ -748,20 +780,105 @@ __device__ void sample_node_group(const SampleArgs<IdxT>& a, int64_t i, int32_t 
     if ((chosen >> w) & 1u) emit(below + own_before[w], 4u * gl + w);
 }
 
+// ---- a workgroup, one hub ---------------------------------------------------------------------
+// The wavefronts of the workgroup scan contiguous parts of the row, each collecting its
+// candidates (in slot order) in its own LDS region; the regions are then laid end to end, which
+// is slot order again, and wavefront 0 finishes the node as it would one it scanned alone.
+constexpr uint32_t kHubRegion = 64;  // candidates one wavefront may contribute
+
+template <typename IdxT, bool kWeighted>
+__device__ void sample_hub_block(const SampleArgs<IdxT>& a, int64_t i, int32_t n_dst, uint64_t* lds) {
+  const uint32_t lane = lane_id();
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(threadIdx.x >> 6));
+  const uint32_t n_waves = blockDim.x >> 6;
+  uint64_t* region = lds + (size_t)wave * kHubRegion;         // [kHubRegion]
+  uint64_t* joined = lds + (size_t)n_waves * kHubRegion;      // [cap]
+  uint32_t* counts = (uint32_t*)(joined + a.cap);             // [n_waves] (<= 16 -> 8 entries)
+  uint64_t* rest = joined + a.cap + 8;
+  const int64_t v = (int64_t)a.S[i];
+  uint32_t deg = 0;
+  if (v >= 0 && v < a.num_nodes) {
+    int64_t deg64 = a.indptr[v + 1] - a.indptr[v];
+    if (deg64 < 0) deg64 = 0;
+    if (deg64 > 0x7FFFFFFF) deg64 = 0x7FFFFFFF;
+    deg = (uint32_t)deg64;
+  }
+  uint32_t mine = 0;
+  if (deg > (uint32_t)a.fanout && !a.force_radix) {
+    const PhiloxKey pk{(uint32_t)(uint64_t)v, (uint32_t)((uint64_t)v >> 32), (uint32_t)a.hop,
+                       a.seed_lo, a.seed_hi};
+    const uint32_t n_quads = (deg + 3) >> 2;
+    uint32_t X0 = 0;
+    if (deg > a.lambda) {
+      const float keep = __fdividef((float)a.lambda, (float)deg) * 4294967296.0f;
+      X0 = 0u - (uint32_t)keep;
+    }
+    // contiguous share of the row per wavefront, a whole number of 64-quad steps
+    const uint32_t share = (((n_quads + n_waves - 1) / n_waves) + kWave - 1) & ~(uint32_t)(kWave - 1);
+    const uint32_t q_begin = wave * share;
+    const uint32_t q_end = min(q_begin + share, n_quads);
+    for (uint32_t q0 = q_begin; q0 < q_end; q0 += kWave) {
+      const uint32_t q = q0 + lane;
+      uint32_t x[4];
+      philox4x32_10(q, pk, x);
+      bool pass[4];
+      uint64_t mk[4];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        pass[w] = (4u * q + (uint32_t)w < deg) && (x[w] >= X0);
+        mk[w] = __ballot(pass[w]);
+      }
+      if (mk[0] | mk[1] | mk[2] | mk[3]) {
+        uint32_t idx = mine + lanes_below(mk[0]) + lanes_below(mk[1]) + lanes_below(mk[2]) + lanes_below(mk[3]);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          if (pass[w]) {
+            if (idx < kHubRegion) region[idx] = draw_order_key(x[w], 4u * q + (uint32_t)w);
+            ++idx;
+          }
+        }
+        mine += (uint32_t)(__popcll(mk[0]) + __popcll(mk[1]) + __popcll(mk[2]) + __popcll(mk[3]));
+      }
+    }
+  }
+  if (lane == 0) counts[wave] = mine;
+  __syncthreads();
+  uint32_t offset = 0, total = 0;
+  bool overflow = false;
+  for (uint32_t w = 0; w < n_waves; ++w) {
+    const uint32_t c = counts[w];
+    offset += w < wave ? c : 0u;
+    total += c;
+    overflow |= c > kHubRegion;
+  }
+  overflow |= total > a.cap;
+  if (!overflow)
+    for (uint32_t j = lane; j < mine; j += kWave) joined[offset + j] = region[j];
+  __syncthreads();
+  // too few candidates, too many, or a forced exhaustive run: wavefront 0 takes the slow path
+  if (wave == 0)
+    sample_node_wave<IdxT, kWeighted>(a, i, n_dst, joined, rest, true, overflow ? a.cap + 1u : total);
+  __syncthreads();  // the regions are reused for the workgroup's next hub
+}
+
 template <typename IdxT, int G, bool kWeighted>
 __device__ __forceinline__ void run_group_role(const SampleArgs<IdxT>& a, int bin, uint32_t block_in_role,
                                                uint32_t blocks_in_role, int32_t n_dst) {
   const int64_t count = a.st->bin_count[bin];
-  const int64_t groups = (int64_t)blocks_in_role * (kTileThreads / G);
-  for (int64_t item = (int64_t)block_in_role * (kTileThreads / G) + threadIdx.x / G; item < count;
-       item += groups) {
+  const uint32_t per_block = blockDim.x / G;
+  const int64_t groups = (int64_t)blocks_in_role * per_block;
+  for (int64_t item = (int64_t)block_in_role * per_block + threadIdx.x / G; item < count; item += groups) {
     const int64_t i = a.bins[bin][item];
     if (i >= 0 && i < n_dst) sample_node_group<IdxT, G, kWeighted>(a, i, n_dst);
   }
 }
 
+constexpr int kSampleMaxThreads = 1024;
+
+// Workgroups take roles by index: role_blocks[0..2] serve the small-degree bins with lane groups,
+// role_blocks[3] the wide nodes (one wavefront each), role_blocks[4] the hubs (one workgroup each).
 template <typename IdxT, bool kWeighted>
-__global__ __launch_bounds__(kTileThreads) void k_sample(const SampleArgs<IdxT> a) {
+__global__ __launch_bounds__(kSampleMaxThreads) void k_sample(const SampleArgs<IdxT> a) {
   extern __shared__ uint64_t lds[];
   const int32_t n_dst = a.st->n_dst[a.hop];
   uint32_t b = blockIdx.x;
@@ -771,18 +888,26 @@ __global__ __launch_bounds__(kTileThreads) void k_sample(const SampleArgs<IdxT> 
   b -= a.role_blocks[1];
   if (b < a.role_blocks[2]) return run_group_role<IdxT, 16, kWeighted>(a, 2, b, a.role_blocks[2], n_dst);
   b -= a.role_blocks[2];
-  // wide nodes, one wavefront each: hubs first, then the rest, dealt round-robin over the
-  // wavefronts of this role so that the hubs land on different wavefronts
-  const int64_t n_hub = a.st->bin_count[4];
-  const int64_t n_wide = a.st->bin_count[3];
-  // the wavefront's index inside the workgroup, held in a scalar register so that the node loop
-  // below is uniform control flow for the whole wavefront
+  // the wavefront's index inside the workgroup, held in a scalar register so that the node loops
+  // below are uniform control flow for the whole wavefront
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(threadIdx.x >> 6));
-  uint64_t* my_lds = lds + (size_t)wave * a.lds_per_wave;
-  const int64_t waves = (int64_t)a.role_blocks[3] * (kTileThreads / kWave);
-  for (int64_t t = (int64_t)b * (kTileThreads / kWave) + wave; t < n_hub + n_wide; t += waves) {
-    const int64_t i = t < n_hub ? a.bins[4][t] : a.bins[3][t - n_hub];
-    if (i >= 0 && i < n_dst) sample_node_wave<IdxT, kWeighted>(a, i, n_dst, my_lds);
+  const uint32_t n_waves = blockDim.x >> 6;
+  if (b < a.role_blocks[3]) {
+    const int64_t n_wide = a.st->bin_count[3];
+    uint64_t* my_lds = lds + (size_t)wave * a.lds_per_wave;
+    const int64_t waves = (int64_t)a.role_blocks[3] * n_waves;
+    for (int64_t t = (int64_t)b * n_waves + wave; t < n_wide; t += waves) {
+      const int64_t i = a.bins[3][t];
+      if (i >= 0 && i < n_dst)
+        sample_node_wave<IdxT, kWeighted>(a, i, n_dst, my_lds, my_lds + a.cap, false, 0u);
+    }
+    return;
+  }
+  b -= a.role_blocks[3];
+  const int64_t n_hub = a.st->bin_count[4];
+  for (int64_t t = b; t < n_hub; t += a.role_blocks[4]) {
+    const int64_t i = a.bins[4][t];  // the same for every thread of the workgroup
+    if (i >= 0 && i < n_dst) sample_hub_block<IdxT, kWeighted>(a, i, n_dst, lds);
   }
 }
 

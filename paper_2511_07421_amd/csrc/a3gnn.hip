@@ -102,7 +102,9 @@ inline unsigned blocks_for(int64_t n, int per_block) {
 uint32_t lambda_for(int32_t m) { return (uint32_t)(m + 4.0 * std::sqrt((double)m) + 8.0); }
 uint32_t cap_for(uint32_t lambda) { return ((2 * lambda + 63) / 64) * 64; }
 constexpr uint32_t kChallengerCap = 192;
-constexpr int64_t kMaxRoleBlocks = 2048;
+constexpr int64_t kMaxRoleWaves = 8192;  // wavefronts serving one role of k_sample
+constexpr int64_t kMaxHubBlocks = 2048;
+constexpr int kSampleWaves = 4;           // wavefronts per k_sample workgroup (fewer if LDS is short)
 
 // uint64 entries of LDS one wavefront needs in the wavefront-per-node path
 uint32_t sample_lds_entries(int32_t fanout, bool weighted) {
@@ -118,6 +120,15 @@ void prof_mark(a3_ctx* ctx, int kind, int which) {
   const int slot = (int)(ctx->prof_written[kind] % A3_PROFILE_DEPTH);
   (void)hipEventRecord(ctx->prof_ev[kind][slot][which], ctx->stream);
   if (which == 1) ctx->prof_written[kind]++;
+}
+
+// LDS of one k_sample workgroup of n_waves wavefronts: the larger of "every wavefront works on
+// its own node" and "the workgroup works on one hub" (regions, joined candidates, counts, and the
+// finishing wavefront's buffers)
+size_t sample_block_lds_bytes(uint32_t lds_per_wave, uint32_t cap, int n_waves) {
+  const size_t own = (size_t)lds_per_wave * n_waves;
+  const size_t hub = (size_t)a3::kHubRegion * n_waves + cap + 8 + (lds_per_wave - cap);
+  return std::max(own, hub) * sizeof(uint64_t);
 }
 
 void free_all(a3_ctx* ctx) {
@@ -233,28 +244,37 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       for (int b = 0; b < a3::kNumBins; ++b) sa.bins[b] = ctx->bins[b];
       sa.num_nodes = num_nodes;
       sa.cap_edges = ctx->cap_edges[h];
-      // workgroups per role: enough to cover the frontier bound once, at most kMaxRoleBlocks
+      sa.lds_per_wave = sample_lds_entries(f, weighted);
+      sa.cap = cap_for(lambda_for(f));
+      // wavefronts per workgroup: as many as the LDS allows, at most kSampleWaves
+      const size_t kLdsLimit = 64 * 1024;
+      int n_waves = kSampleWaves;
+      while (n_waves > 1 && sample_block_lds_bytes(sa.lds_per_wave, sa.cap, n_waves) > kLdsLimit)
+        n_waves >>= 1;
+      // workgroups per role: enough to cover the frontier bound once, at most kMaxRoleWaves wavefronts
       const int64_t nb = std::max<int64_t>(bound_dst[h], 1);
-      sa.role_blocks[0] = (uint32_t)std::min<int64_t>((nb + 63) / 64, kMaxRoleBlocks);
-      sa.role_blocks[1] = (uint32_t)std::min<int64_t>((nb + 31) / 32, kMaxRoleBlocks);
-      sa.role_blocks[2] = (uint32_t)std::min<int64_t>((nb + 15) / 16, kMaxRoleBlocks);
-      sa.role_blocks[3] = (uint32_t)std::min<int64_t>((nb + 3) / 4, kMaxRoleBlocks);
+      const int64_t max_blocks = std::max<int64_t>(kMaxRoleWaves / n_waves, 1);
+      const int64_t threads = 64 * n_waves;
+      sa.role_blocks[0] = (uint32_t)std::min<int64_t>((nb * 4 + threads - 1) / threads, max_blocks);
+      sa.role_blocks[1] = (uint32_t)std::min<int64_t>((nb * 8 + threads - 1) / threads, max_blocks);
+      sa.role_blocks[2] = (uint32_t)std::min<int64_t>((nb * 16 + threads - 1) / threads, max_blocks);
+      sa.role_blocks[3] = (uint32_t)std::min<int64_t>((nb + n_waves - 1) / n_waves, max_blocks);
+      sa.role_blocks[4] = (uint32_t)std::min<int64_t>(nb, kMaxHubBlocks);
       sa.hop = h;
       sa.fanout = f;
       sa.lambda = lambda_for(f);
-      sa.cap = cap_for(sa.lambda);
       sa.xcap = kChallengerCap;
-      sa.lds_per_wave = sample_lds_entries(f, weighted);
       sa.bias_q16 = bias_q16;
       sa.seed_lo = (uint32_t)rng_seed;
       sa.seed_hi = (uint32_t)(rng_seed >> 32);
       sa.force_radix = (ctx->flags & A3_FORCE_RADIX) ? 1u : 0u;
-      const unsigned grid = sa.role_blocks[0] + sa.role_blocks[1] + sa.role_blocks[2] + sa.role_blocks[3];
-      const size_t lds_bytes = (size_t)sa.lds_per_wave * sizeof(uint64_t) * (a3::kTileThreads / a3::kWave);
+      const unsigned grid = sa.role_blocks[0] + sa.role_blocks[1] + sa.role_blocks[2] +
+                            sa.role_blocks[3] + sa.role_blocks[4];
+      const size_t lds_bytes = sample_block_lds_bytes(sa.lds_per_wave, sa.cap, n_waves);
       if (weighted)
-        hipLaunchKernelGGL((a3::k_sample<IdxT, true>), dim3(grid), dim3(a3::kTileThreads), lds_bytes, st, sa);
+        hipLaunchKernelGGL((a3::k_sample<IdxT, true>), dim3(grid), dim3((unsigned)threads), lds_bytes, st, sa);
       else
-        hipLaunchKernelGGL((a3::k_sample<IdxT, false>), dim3(grid), dim3(a3::kTileThreads), lds_bytes, st, sa);
+        hipLaunchKernelGGL((a3::k_sample<IdxT, false>), dim3(grid), dim3((unsigned)threads), lds_bytes, st, sa);
     }
     // a5: first occurrences -> numbering of new nodes -> local ids
     hipLaunchKernelGGL(a3::k_flag<IdxT>, dim3(edge_tiles), dim3(a3::kTileThreads), 0, st, gid,
