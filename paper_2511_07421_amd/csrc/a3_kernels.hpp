@@ -46,6 +46,18 @@ struct DevState {
   int32_t bin_count[kNumBins];
 };
 
+// What k_sample needs to know of a frontier node; k_frontier has it all in registers and writes
+// it into the node's degree bin, so that the sampler starts a node with one 32-byte load instead
+// of a chain of dependent loads (bin entry -> frontier -> indptr).
+struct NodeRec {
+  int64_t v;          // global id
+  int64_t row;        // indptr[v]
+  uint32_t deg;       // degree, clipped to 2^31 - 1
+  int32_t i;          // position in the frontier (destination id of the block)
+  int32_t local_off;  // edges of earlier nodes of the same scan tile
+  int32_t pad;
+};
+
 // ---------------------------------------------------------------------------
 // block-wide helpers (256 threads = 4 waves)
 // ---------------------------------------------------------------------------
@@ -90,6 +102,37 @@ __global__ __launch_bounds__(kTileThreads) void k_scan_tiles(const int32_t* tile
       st->n_dst[hop + 1] = n_src;
     }
   }
+}
+
+// When there are few tiles (kFuseTiles at most) the consumers of a tile scan do it themselves
+// instead of waiting for k_scan_tiles: every workgroup's first wavefront reads the tile sums and
+// leaves their exclusive prefix in LDS, 16 consecutive tiles per lane.  Returns the grand total
+// (valid in every thread after the barrier inside).
+constexpr int kFuseTiles = 1024;
+
+__device__ __forceinline__ uint32_t tile_prefix_to_lds(const int32_t* tile_sums, int64_t n_tiles,
+                                                       int32_t* lds_offs, uint32_t* lds_total) {
+  if (threadIdx.x < (unsigned)kWave) {
+    const uint32_t lane = threadIdx.x;
+    uint32_t v[kFuseTiles / kWave];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int k = 0; k < kFuseTiles / kWave; ++k) {
+      const int64_t t = (int64_t)lane * (kFuseTiles / kWave) + k;
+      v[k] = t < n_tiles ? (uint32_t)tile_sums[t] : 0u;
+      sum += v[k];
+    }
+    uint32_t run = wave_excl_scan_u32(sum);
+#pragma unroll
+    for (int k = 0; k < kFuseTiles / kWave; ++k) {
+      const int64_t t = (int64_t)lane * (kFuseTiles / kWave) + k;
+      if (t < n_tiles) lds_offs[t] = (int32_t)run;
+      run += v[k];
+    }
+    if (lane == kWave - 1) *lds_total = run;
+  }
+  __syncthreads();
+  return *lds_total;
 }
 
 // ---------------------------------------------------------------------------
@@ -159,10 +202,9 @@ struct FrontierArgs {
   DevState* st;
   int32_t hop;
   int32_t fanout;
-  int32_t* local_off;  // per node: edges of earlier nodes of the same tile
   int32_t* tile_sums;
   int64_t num_nodes;
-  int32_t* bins[kNumBins];   // node indices per degree bin
+  NodeRec* bins[kNumBins];   // node records per degree bin
 };
 
 __device__ __forceinline__ int degree_bin(uint32_t deg) {
@@ -184,6 +226,7 @@ __global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<Id
   uint32_t cnt[kTilePerThread];
   uint32_t rank_in_bin[kTilePerThread];
   int bin[kTilePerThread];
+  NodeRec rec[kTilePerThread];
   uint32_t sum = 0;
 #pragma unroll
   for (int k = 0; k < kTilePerThread; ++k) {
@@ -201,27 +244,37 @@ __global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<Id
       } else {
         v = (int64_t)a.S[i];
       }
-      int64_t deg = 0;
-      if (v >= 0 && v < a.num_nodes)
-        deg = a.indptr[v + 1] - a.indptr[v];
-      else
+      int64_t row = 0, deg = 0;
+      if (v >= 0 && v < a.num_nodes) {
+        row = a.indptr[v];
+        deg = a.indptr[v + 1] - row;
+      } else {
         atomicOr(&a.st->error, kErrFrontierId);
+      }
       if (deg < 0) deg = 0;
-      if (deg > 0x7FFFFFFF) deg = 0x7FFFFFFF;
+      if (deg > 0x7FFFFFFF) {
+        atomicOr(&a.st->error, kErrHugeRow);
+        deg = 0x7FFFFFFF;
+      }
       cnt[k] = deg < (int64_t)a.fanout ? (uint32_t)deg : (uint32_t)a.fanout;
       bin[k] = degree_bin((uint32_t)deg);
       rank_in_bin[k] = atomicAdd(&bin_n[bin[k]], 1u);
       sum += cnt[k];
+      rec[k].v = v;
+      rec[k].row = row;
+      rec[k].deg = (uint32_t)deg;
+      rec[k].i = (int32_t)i;
+      rec[k].pad = 0;
     }
   }
   uint32_t total;
   uint32_t run = block_excl_scan_256(sum, lds4, &total);
 #pragma unroll
   for (int k = 0; k < kTilePerThread; ++k) {
-    if (base_i + k < n) a.local_off[base_i + k] = (int32_t)run;
+    rec[k].local_off = (int32_t)run;
     run += cnt[k];
   }
-  // one global reservation per bin and block, then scatter the node indices
+  // one global reservation per bin and block, then scatter the node records
   if (threadIdx.x < kNumBins)
     bin_base[threadIdx.x] = bin_n[threadIdx.x]
                                 ? (uint32_t)atomicAdd(&a.st->bin_count[threadIdx.x], (int32_t)bin_n[threadIdx.x])
@@ -229,7 +282,7 @@ __global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<Id
   __syncthreads();
 #pragma unroll
   for (int k = 0; k < kTilePerThread; ++k)
-    if (bin[k] >= 0) a.bins[bin[k]][bin_base[bin[k]] + rank_in_bin[k]] = (int32_t)(base_i + k);
+    if (bin[k] >= 0) a.bins[bin[k]][bin_base[bin[k]] + rank_in_bin[k]] = rec[k];
   if (threadIdx.x == 0) a.tile_sums[blockIdx.x] = (int32_t)total;
 }
 
@@ -242,14 +295,14 @@ struct SampleArgs {
   const IdxT* indices;
   const int32_t* cache_map;  // read only when weighted
   const IdxT* S;             // frontier: local id -> global id
-  const int32_t* local_off;
-  const int32_t* tile_offs;
+  const int32_t* tile_offs;  // scanned tile offsets in global memory, or null: scan tile_sums here
+  const int32_t* tile_sums;
   int32_t* blk_indptr;       // out: edge offsets of this hop
   IdxT* gid;                 // out: global id of each sampled neighbour
   int64_t* eids;             // out: CSR position of each sampled edge (may be null)
   int32_t* node_map;         // global id -> first position / local id
   DevState* st;
-  const int32_t* bins[kNumBins];
+  const NodeRec* bins[kNumBins];
   int64_t num_nodes;
   int64_t cap_edges;         // entries in gid / eids (arena capacity of this hop)
   uint32_t role_blocks[5];   // workgroups serving bins 0, 1, 2 (lane groups), 3 (wide), 4 (hubs)
@@ -487,21 +540,16 @@ __device__ __noinline__ void radix_select(const PhiloxKey pk, uint32_t deg, uint
 // prefiltered set, cand already holds pre_cnt candidates in slot order (a workgroup scanned the
 // row together) and the scan is skipped.
 template <typename IdxT, bool kWeighted>
-__device__ void sample_node_wave(const SampleArgs<IdxT>& a, int64_t i, int32_t n_dst, uint64_t* cand,
-                                 uint64_t* rest, bool prefiltered, uint32_t pre_cnt) {
+__device__ void sample_node_wave(const SampleArgs<IdxT>& a, const int32_t* tile_offs,
+                                 const NodeRec& r, int32_t n_dst, uint64_t* cand, uint64_t* rest,
+                                 bool prefiltered, uint32_t pre_cnt) {
   const uint32_t lane = lane_id();
-  const int64_t v = (int64_t)a.S[i];
-  if (v < 0 || v >= a.num_nodes) return;  // flagged by k_frontier, which gave it zero edges
-  const int64_t row = a.indptr[v];
-  int64_t deg64 = a.indptr[v + 1] - row;
-  if (deg64 < 0) deg64 = 0;
-  if (deg64 > 0x7FFFFFFF) {
-    if (lane == 0) atomicOr(&a.st->error, kErrHugeRow);
-    deg64 = 0x7FFFFFFF;
-  }
-  const uint32_t deg = (uint32_t)deg64;
+  const int64_t v = r.v;
+  const int64_t row = r.row;
+  const int64_t i = r.i;
+  const uint32_t deg = r.deg;
   const uint32_t f = (uint32_t)a.fanout;
-  const int32_t base = a.tile_offs[i >> kTileShift] + a.local_off[i];
+  const int32_t base = tile_offs[i >> kTileShift] + r.local_off;
   if (lane == 0) a.blk_indptr[i] = base;
   const Emitter<IdxT> emit{a.indices, a.gid, a.eids, a.node_map, row, base, n_dst, a.num_nodes, a.cap_edges, &a.st->error};
 
@@ -676,18 +724,17 @@ __device__ void sample_node_wave(const SampleArgs<IdxT>& a, int64_t i, int32_t n
 // the group" (lane-local best, butterfly reduction, lowest lane among equals), which costs
 // O(m log G) instead of ranking every slot against every other.
 template <typename IdxT, int G, bool kWeighted>
-__device__ void sample_node_group(const SampleArgs<IdxT>& a, int64_t i, int32_t n_dst) {
+__device__ void sample_node_group(const SampleArgs<IdxT>& a, const int32_t* tile_offs,
+                                  const NodeRec& r, int32_t n_dst) {
   const uint32_t lane = lane_id();
   const uint32_t gl = lane & (G - 1);       // lane inside the group
   const uint32_t gshift = lane & ~(G - 1);  // first lane of the group inside the wavefront
-  const int64_t v = (int64_t)a.S[i];
-  if (v < 0 || v >= a.num_nodes) return;  // flagged by k_frontier, which gave it zero edges
-  const int64_t row = a.indptr[v];
-  int64_t deg64 = a.indptr[v + 1] - row;
-  if (deg64 < 0) deg64 = 0;
-  const uint32_t deg = (uint32_t)deg64;  // <= 4 G by construction of the bins
+  const int64_t v = r.v;
+  const int64_t row = r.row;
+  const int64_t i = r.i;
+  const uint32_t deg = r.deg;  // <= 4 G by construction of the bins
   const uint32_t f = (uint32_t)a.fanout;
-  const int32_t base = a.tile_offs[i >> kTileShift] + a.local_off[i];
+  const int32_t base = tile_offs[i >> kTileShift] + r.local_off;
   if (gl == 0) a.blk_indptr[i] = base;
   const Emitter<IdxT> emit{a.indices, a.gid, a.eids, a.node_map, row, base, n_dst, a.num_nodes, a.cap_edges, &a.st->error};
   if (deg <= f) {
@@ -787,7 +834,8 @@ __device__ void sample_node_group(const SampleArgs<IdxT>& a, int64_t i, int32_t 
 constexpr uint32_t kHubRegion = 64;  // candidates one wavefront may contribute
 
 template <typename IdxT, bool kWeighted>
-__device__ void sample_hub_block(const SampleArgs<IdxT>& a, int64_t i, int32_t n_dst, uint64_t* lds) {
+__device__ void sample_hub_block(const SampleArgs<IdxT>& a, const int32_t* tile_offs,
+                                 const NodeRec& r, int32_t n_dst, uint64_t* lds) {
   const uint32_t lane = lane_id();
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(threadIdx.x >> 6));
   const uint32_t n_waves = blockDim.x >> 6;
@@ -795,14 +843,8 @@ __device__ void sample_hub_block(const SampleArgs<IdxT>& a, int64_t i, int32_t n
   uint64_t* joined = lds + (size_t)n_waves * kHubRegion;      // [cap]
   uint32_t* counts = (uint32_t*)(joined + a.cap);             // [n_waves] (<= 16 -> 8 entries)
   uint64_t* rest = joined + a.cap + 8;
-  const int64_t v = (int64_t)a.S[i];
-  uint32_t deg = 0;
-  if (v >= 0 && v < a.num_nodes) {
-    int64_t deg64 = a.indptr[v + 1] - a.indptr[v];
-    if (deg64 < 0) deg64 = 0;
-    if (deg64 > 0x7FFFFFFF) deg64 = 0x7FFFFFFF;
-    deg = (uint32_t)deg64;
-  }
+  const int64_t v = r.v;
+  const uint32_t deg = r.deg;
   uint32_t mine = 0;
   if (deg > (uint32_t)a.fanout && !a.force_radix) {
     const PhiloxKey pk{(uint32_t)(uint64_t)v, (uint32_t)((uint64_t)v >> 32), (uint32_t)a.hop,
@@ -857,19 +899,26 @@ __device__ void sample_hub_block(const SampleArgs<IdxT>& a, int64_t i, int32_t n
   __syncthreads();
   // too few candidates, too many, or a forced exhaustive run: wavefront 0 takes the slow path
   if (wave == 0)
-    sample_node_wave<IdxT, kWeighted>(a, i, n_dst, joined, rest, true, overflow ? a.cap + 1u : total);
+    sample_node_wave<IdxT, kWeighted>(a, tile_offs, r, n_dst, joined, rest, true,
+                                      overflow ? a.cap + 1u : total);
   __syncthreads();  // the regions are reused for the workgroup's next hub
 }
 
 template <typename IdxT, int G, bool kWeighted>
-__device__ __forceinline__ void run_group_role(const SampleArgs<IdxT>& a, int bin, uint32_t block_in_role,
+__device__ __forceinline__ void run_group_role(const SampleArgs<IdxT>& a, const int32_t* tile_offs,
+                                               int bin, uint32_t block_in_role,
                                                uint32_t blocks_in_role, int32_t n_dst) {
   const int64_t count = a.st->bin_count[bin];
   const uint32_t per_block = blockDim.x / G;
   const int64_t groups = (int64_t)blocks_in_role * per_block;
-  for (int64_t item = (int64_t)block_in_role * per_block + threadIdx.x / G; item < count; item += groups) {
-    const int64_t i = a.bins[bin][item];
-    if (i >= 0 && i < n_dst) sample_node_group<IdxT, G, kWeighted>(a, i, n_dst);
+  int64_t item = (int64_t)block_in_role * per_block + threadIdx.x / G;
+  NodeRec cur = {};
+  if (item < count) cur = a.bins[bin][item];
+  for (; item < count; item += groups) {
+    NodeRec nxt = {};
+    if (item + groups < count) nxt = a.bins[bin][item + groups];  // in flight while cur is sampled
+    if (cur.i >= 0 && cur.i < n_dst) sample_node_group<IdxT, G, kWeighted>(a, tile_offs, cur, n_dst);
+    cur = nxt;
   }
 }
 
@@ -880,13 +929,25 @@ constexpr int kSampleMaxThreads = 1024;
 template <typename IdxT, bool kWeighted>
 __global__ __launch_bounds__(kSampleMaxThreads) void k_sample(const SampleArgs<IdxT> a) {
   extern __shared__ uint64_t lds[];
+  __shared__ int32_t fused_offs[kFuseTiles];
+  __shared__ uint32_t fused_total;
   const int32_t n_dst = a.st->n_dst[a.hop];
+  const int32_t* tile_offs = a.tile_offs;
+  if (tile_offs == nullptr) {  // few tiles: scan the tile sums here, publish the hop's edge count
+    const uint32_t total = tile_prefix_to_lds(a.tile_sums, ((int64_t)n_dst + kTile - 1) >> kTileShift,
+                                              fused_offs, &fused_total);
+    tile_offs = fused_offs;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      a.st->n_edges[a.hop] = (int32_t)total;
+      a.blk_indptr[n_dst] = (int32_t)total;
+    }
+  }
   uint32_t b = blockIdx.x;
-  if (b < a.role_blocks[0]) return run_group_role<IdxT, 4, kWeighted>(a, 0, b, a.role_blocks[0], n_dst);
+  if (b < a.role_blocks[0]) return run_group_role<IdxT, 4, kWeighted>(a, tile_offs, 0, b, a.role_blocks[0], n_dst);
   b -= a.role_blocks[0];
-  if (b < a.role_blocks[1]) return run_group_role<IdxT, 8, kWeighted>(a, 1, b, a.role_blocks[1], n_dst);
+  if (b < a.role_blocks[1]) return run_group_role<IdxT, 8, kWeighted>(a, tile_offs, 1, b, a.role_blocks[1], n_dst);
   b -= a.role_blocks[1];
-  if (b < a.role_blocks[2]) return run_group_role<IdxT, 16, kWeighted>(a, 2, b, a.role_blocks[2], n_dst);
+  if (b < a.role_blocks[2]) return run_group_role<IdxT, 16, kWeighted>(a, tile_offs, 2, b, a.role_blocks[2], n_dst);
   b -= a.role_blocks[2];
   // the wavefront's index inside the workgroup, held in a scalar register so that the node loops
   // below are uniform control flow for the whole wavefront
@@ -896,18 +957,28 @@ __global__ __launch_bounds__(kSampleMaxThreads) void k_sample(const SampleArgs<I
     const int64_t n_wide = a.st->bin_count[3];
     uint64_t* my_lds = lds + (size_t)wave * a.lds_per_wave;
     const int64_t waves = (int64_t)a.role_blocks[3] * n_waves;
-    for (int64_t t = (int64_t)b * n_waves + wave; t < n_wide; t += waves) {
-      const int64_t i = a.bins[3][t];
-      if (i >= 0 && i < n_dst)
-        sample_node_wave<IdxT, kWeighted>(a, i, n_dst, my_lds, my_lds + a.cap, false, 0u);
+    int64_t t = (int64_t)b * n_waves + wave;
+    NodeRec cur = {};
+    if (t < n_wide) cur = a.bins[3][t];
+    for (; t < n_wide; t += waves) {
+      NodeRec nxt = {};
+      if (t + waves < n_wide) nxt = a.bins[3][t + waves];  // in flight while cur is sampled
+      if (cur.i >= 0 && cur.i < n_dst)
+        sample_node_wave<IdxT, kWeighted>(a, tile_offs, cur, n_dst, my_lds, my_lds + a.cap, false, 0u);
+      cur = nxt;
     }
     return;
   }
   b -= a.role_blocks[3];
   const int64_t n_hub = a.st->bin_count[4];
-  for (int64_t t = b; t < n_hub; t += a.role_blocks[4]) {
-    const int64_t i = a.bins[4][t];  // the same for every thread of the workgroup
-    if (i >= 0 && i < n_dst) sample_hub_block<IdxT, kWeighted>(a, i, n_dst, lds);
+  int64_t t = b;
+  NodeRec cur = {};
+  if (t < n_hub) cur = a.bins[4][t];
+  for (; t < n_hub; t += a.role_blocks[4]) {  // the same node for every thread of the workgroup
+    NodeRec nxt = {};
+    if (t + a.role_blocks[4] < n_hub) nxt = a.bins[4][t + a.role_blocks[4]];
+    if (cur.i >= 0 && cur.i < n_dst) sample_hub_block<IdxT, kWeighted>(a, tile_offs, cur, n_dst, lds);
+    cur = nxt;
   }
 }
 
@@ -954,44 +1025,66 @@ __global__ __launch_bounds__(kTileThreads) void k_flag(const IdxT* gid, const in
 }
 
 // A first occurrence at edge q gets local id n_dst + (first occurrences before q); every edge
-// reads its id through its first occurrence.  Also clears the hop's scratch counters.
+// reads its id through its first occurrence.  Also clears the hop's scratch counters.  With
+// tile_offs null the workgroup scans k_flag's tile sums itself (few tiles) and workgroup 0
+// publishes the hop's source count.
+constexpr int kRelabelPerThread = 4;
+
 template <typename IdxT>
-__global__ void k_relabel(const IdxT* gid, const int32_t* first_pos, const int32_t* local_rank,
-                          const int32_t* tile_offs, DevState* st, int hop, int64_t num_nodes,
-                          int64_t cap_src, IdxT* S, int32_t* node_map, int32_t* blk_indices) {
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e == 0) {
-    for (int b = 0; b < kNumBins; ++b) st->bin_count[b] = 0;
-  }
+__global__ __launch_bounds__(kTileThreads) void k_relabel(const IdxT* gid, const int32_t* first_pos,
+                                                          const int32_t* local_rank,
+                                                          const int32_t* tile_offs,
+                                                          const int32_t* tile_sums, DevState* st,
+                                                          int hop, int64_t num_nodes, int64_t cap_src,
+                                                          IdxT* S, int32_t* node_map,
+                                                          int32_t* blk_indices) {
+  __shared__ int32_t fused_offs[kFuseTiles];
+  __shared__ uint32_t fused_total;
   const int64_t n = st->n_edges[hop];
-  if (e >= n) return;
   const int32_t n_dst = st->n_dst[hop];
-  const int32_t p = first_pos[e];
-  int32_t local;
-  if (p < 0) {
-    atomicOr(&st->error, kErrFirstPosNeg);
-    local = 0;
-  } else if (p < n_dst) {
-    local = p;
-  } else {
-    const int32_t q = p - n_dst;
-    if ((int64_t)q > e) {  // a first occurrence cannot lie after the edge itself
-      atomicOr(&st->error, kErrFirstPosLate);
-      blk_indices[e] = 0;
-      return;
+  if (blockIdx.x == 0 && threadIdx.x == 0)
+    for (int b = 0; b < kNumBins; ++b) st->bin_count[b] = 0;
+  if (tile_offs == nullptr) {
+    const uint32_t total = tile_prefix_to_lds(tile_sums, (n + kTile - 1) >> kTileShift, fused_offs,
+                                              &fused_total);
+    tile_offs = fused_offs;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      const int32_t n_src = n_dst + (int32_t)total;
+      st->n_src[hop] = n_src;
+      st->n_dst[hop + 1] = n_src;
     }
-    local = n_dst + tile_offs[q >> kTileShift] + local_rank[q];
-    if ((int64_t)q == e) {
-      const IdxT g = gid[e];
-      if (local >= 0 && (int64_t)local < cap_src && (int64_t)g >= 0 && (int64_t)g < num_nodes) {
-        S[local] = g;
-        node_map[(int64_t)g] = local;
-      } else {
-        atomicOr(&st->error, kErrNewNode);
+  }
+#pragma unroll
+  for (int k = 0; k < kRelabelPerThread; ++k) {
+    const int64_t e = ((int64_t)blockIdx.x * kRelabelPerThread + k) * kTileThreads + threadIdx.x;
+    if (e >= n) continue;
+    const int32_t p = first_pos[e];
+    int32_t local;
+    if (p < 0) {
+      atomicOr(&st->error, kErrFirstPosNeg);
+      local = 0;
+    } else if (p < n_dst) {
+      local = p;
+    } else {
+      const int32_t q = p - n_dst;
+      if ((int64_t)q > e) {  // a first occurrence cannot lie after the edge itself
+        atomicOr(&st->error, kErrFirstPosLate);
+        blk_indices[e] = 0;
+        continue;
+      }
+      local = n_dst + tile_offs[q >> kTileShift] + local_rank[q];
+      if ((int64_t)q == e) {
+        const IdxT g = gid[e];
+        if (local >= 0 && (int64_t)local < cap_src && (int64_t)g >= 0 && (int64_t)g < num_nodes) {
+          S[local] = g;
+          node_map[(int64_t)g] = local;
+        } else {
+          atomicOr(&st->error, kErrNewNode);
+        }
       }
     }
+    blk_indices[e] = local;
   }
-  blk_indices[e] = local;
 }
 
 // ---------------------------------------------------------------------------

@@ -33,13 +33,13 @@ struct a3_ctx {
   int32_t* blk_indices[A3_MAX_HOPS] = {nullptr};
   int64_t* blk_eids[A3_MAX_HOPS] = {nullptr};
   void* gid = nullptr;            // sampled global ids of the running hop, 8 bytes per entry
-  int32_t* local_off = nullptr;   // per frontier node: edge offset inside its scan tile
   int32_t* first_pos = nullptr;   // per edge: relabel-map value
   int32_t* local_rank = nullptr;  // per edge: first occurrences before it inside its scan tile
-  int32_t* tile_sums = nullptr;
+  int32_t* tile_sums = nullptr;   // per node tile: edges
+  int32_t* tile_sums2 = nullptr;  // per edge tile: first occurrences
   int32_t* tile_offs = nullptr;   // edge offsets of the node tiles (read by k_sample)
   int32_t* tile_offs2 = nullptr;  // new-node offsets of the edge tiles (read by k_relabel)
-  int32_t* bins[a3::kNumBins] = {nullptr};  // frontier node indices by degree bin
+  a3::NodeRec* bins[a3::kNumBins] = {nullptr};  // frontier node records by degree bin
   int32_t* node_map = nullptr;  // global id -> position, grown on demand
   int64_t node_map_cap = 0;
   bool node_map_dirty = false;
@@ -220,13 +220,16 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
     fa.st = ds;
     fa.hop = h;
     fa.fanout = f;
-    fa.local_off = ctx->local_off;
     fa.tile_sums = ctx->tile_sums;
     fa.num_nodes = num_nodes;
     for (int b = 0; b < a3::kNumBins; ++b) fa.bins[b] = ctx->bins[b];
     hipLaunchKernelGGL(a3::k_frontier<IdxT>, dim3(dst_tiles), dim3(a3::kTileThreads), 0, st, fa);
-    hipLaunchKernelGGL(a3::k_scan_tiles, dim3(1), dim3(a3::kTileThreads), 0, st, ctx->tile_sums,
-                       ctx->tile_offs, ds, h, 0, ctx->blk_indptr[h]);
+    // few tiles: the consumer scans the tile sums itself and the launch is saved
+    const bool fuse_dst = dst_tiles <= (unsigned)a3::kFuseTiles;
+    const bool fuse_edges = edge_tiles <= (unsigned)a3::kFuseTiles;
+    if (!fuse_dst)
+      hipLaunchKernelGGL(a3::k_scan_tiles, dim3(1), dim3(a3::kTileThreads), 0, st, ctx->tile_sums,
+                         ctx->tile_offs, ds, h, 0, ctx->blk_indptr[h]);
     // a2-a4: selection
     {
       a3::SampleArgs<IdxT> sa;
@@ -234,8 +237,8 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       sa.indices = indices;
       sa.cache_map = cache_map;
       sa.S = S;
-      sa.local_off = ctx->local_off;
-      sa.tile_offs = ctx->tile_offs;
+      sa.tile_offs = fuse_dst ? nullptr : ctx->tile_offs;
+      sa.tile_sums = ctx->tile_sums;
       sa.blk_indptr = ctx->blk_indptr[h];
       sa.gid = gid;
       sa.eids = ctx->blk_eids[h];
@@ -279,11 +282,14 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
     // a5: first occurrences -> numbering of new nodes -> local ids
     hipLaunchKernelGGL(a3::k_flag<IdxT>, dim3(edge_tiles), dim3(a3::kTileThreads), 0, st, gid,
                        ctx->node_map, ds, h, num_nodes, ctx->first_pos, ctx->local_rank,
-                       ctx->tile_sums);
-    hipLaunchKernelGGL(a3::k_scan_tiles, dim3(1), dim3(a3::kTileThreads), 0, st, ctx->tile_sums,
-                       ctx->tile_offs2, ds, h, 1, (int32_t*)nullptr);
-    hipLaunchKernelGGL(a3::k_relabel<IdxT>, dim3(blocks_for(bound_edges[h], 256)), dim3(256), 0, st,
-                       gid, ctx->first_pos, ctx->local_rank, ctx->tile_offs2, ds, h, num_nodes,
+                       ctx->tile_sums2);
+    if (!fuse_edges)
+      hipLaunchKernelGGL(a3::k_scan_tiles, dim3(1), dim3(a3::kTileThreads), 0, st, ctx->tile_sums2,
+                         ctx->tile_offs2, ds, h, 1, (int32_t*)nullptr);
+    hipLaunchKernelGGL(a3::k_relabel<IdxT>,
+                       dim3(blocks_for(bound_edges[h], a3::kTileThreads * a3::kRelabelPerThread)),
+                       dim3(a3::kTileThreads), 0, st, gid, ctx->first_pos, ctx->local_rank,
+                       fuse_edges ? (const int32_t*)nullptr : ctx->tile_offs2, ctx->tile_sums2, ds, h, num_nodes,
                        ctx->cap_dst[ctx->max_hops], S, ctx->node_map, ctx->blk_indices[h]);
   }
   // leave the relabel map empty for the next call; the same kernel publishes the counts
@@ -470,10 +476,10 @@ extern "C" int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t
   auto chk = [&](int r) { if (rc == A3_OK) rc = r; };
   chk(dev_alloc(ctx, (int64_t**)&ctx->S, ctx->cap_dst[max_hops]));
   chk(dev_alloc(ctx, (int64_t**)&ctx->gid, max_edges));
-  chk(dev_alloc(ctx, &ctx->local_off, ctx->cap_dst[max_hops - 1]));
   chk(dev_alloc(ctx, &ctx->first_pos, max_edges));
   chk(dev_alloc(ctx, &ctx->local_rank, max_edges));
   chk(dev_alloc(ctx, &ctx->tile_sums, ctx->cap_tiles));
+  chk(dev_alloc(ctx, &ctx->tile_sums2, ctx->cap_tiles));
   chk(dev_alloc(ctx, &ctx->tile_offs, ctx->cap_tiles));
   chk(dev_alloc(ctx, &ctx->tile_offs2, ctx->cap_tiles));
   for (int b = 0; b < a3::kNumBins; ++b) chk(dev_alloc(ctx, &ctx->bins[b], ctx->cap_dst[max_hops - 1]));
