@@ -192,6 +192,28 @@ __global__ void k_finish_call(const IdxT* S, DevState* st, int last_hop, int64_t
 // ---------------------------------------------------------------------------
 // step a1: frontier degrees -> edge offsets, degree bins
 // ---------------------------------------------------------------------------
+// One bit per node from the device map: bit u of the bitmap = (cache_map[u] >= 0).  A wavefront
+// turns 64 consecutive entries into one 64-bit word with a ballot.
+__global__ __launch_bounds__(kTileThreads) void k_cached_bits(const int32_t* __restrict__ cache_map,
+                                                             int64_t num_nodes, uint64_t* __restrict__ bits) {
+  const int64_t n_words = (num_nodes + 63) >> 6;
+  const int64_t n_waves = (int64_t)gridDim.x * (kTileThreads / kWave);
+  const uint32_t lane = lane_id();
+  for (int64_t w0 = ((int64_t)blockIdx.x * kTileThreads + threadIdx.x) >> 6; w0 < n_words; w0 += 4 * n_waves) {
+    int32_t c[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int64_t u = ((w0 + k * n_waves) << 6) + lane;
+      c[k] = u < num_nodes ? cache_map[u] : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint64_t word = __ballot(c[k] >= 0);
+      if (lane == 0 && w0 + k * n_waves < n_words) bits[w0 + k * n_waves] = word;
+    }
+  }
+}
+
 template <typename IdxT>
 struct FrontierArgs {
   const IdxT* seeds;  // non-null at hop 0 without validation: the frontier is read from here
@@ -293,7 +315,7 @@ template <typename IdxT>
 struct SampleArgs {
   const int64_t* indptr;
   const IdxT* indices;
-  const int32_t* cache_map;  // read only when weighted
+  const uint32_t* cached_bits;  // bit u set: node u's row is in the device cache (weighted only)
   const IdxT* S;             // frontier: local id -> global id
   const int32_t* tile_offs;  // scanned tile offsets in global memory, or null: scan tile_sums here
   const int32_t* tile_sums;
@@ -311,6 +333,7 @@ struct SampleArgs {
   uint32_t lambda;    // expected number of candidates kept by the draw threshold
   uint32_t cap;       // candidate buffer entries per wavefront (>= lambda)
   uint32_t xcap;      // challenger buffer entries (weighted only, multiple of 64, >= 128)
+  uint32_t capb;      // second candidate list (weighted only; 0: rescan the row instead)
   uint32_t lds_per_wave;  // uint64 entries of LDS per wavefront
   uint32_t bias_q16;
   uint32_t seed_lo, seed_hi;
@@ -318,6 +341,14 @@ struct SampleArgs {
 };
 
 // what a lane needs to write one sampled edge
+// Is node u's feature row in the device cache?  One bit per node (k_cached_bits): the lookups of
+// a neighbourhood are random, and a bitmap of N / 8 bytes stays in the L2 where the 4 N bytes of
+// the device map do not.  Ids outside the graph count as not cached (the emitter reports them).
+template <typename IdxT>
+__device__ __forceinline__ bool is_cached(const SampleArgs<IdxT>& a, int64_t u) {
+  return u >= 0 && u < a.num_nodes && ((a.cached_bits[u >> 5] >> (u & 31)) & 1u);
+}
+
 template <typename IdxT>
 struct Emitter {
   const IdxT* indices;
@@ -536,13 +567,177 @@ __device__ __noinline__ void radix_select(const PhiloxKey pk, uint32_t deg, uint
 }
 
 // ---- one wavefront, one node of any degree ------------------------------------------------------
-// cand [cap] and rest [m (+ 3 m + 2 xcap when weighted)] are this wavefront's LDS buffers.  With
-// prefiltered set, cand already holds pre_cnt candidates in slot order (a workgroup scanned the
-// row together) and the scan is skipped.
+// The m smallest of up to 64*NK (K, k) pairs held NK per lane in registers (pair j in lane j % 64,
+// register j / 64; the k are distinct), by the same quickselect on wave-wide masks as
+// select_in_registers, here on two-word keys.  The pairs come in no particular slot order, so a
+// chosen pair's output position is counted: the number of chosen pairs with a smaller slot.
+// Calls on_selected(position, k) for each of the m chosen pairs.
+template <int NK, typename OnSelected>
+__device__ __forceinline__ void select_pairs_in_registers(const uint64_t (&K)[NK], const uint64_t (&k)[NK],
+                                                          uint32_t cnt, uint32_t m, OnSelected on_selected) {
+  const uint32_t lane = lane_id();
+  uint64_t active[NK], chosen[NK];
+#pragma unroll
+  for (int r = 0; r < NK; ++r) {
+    const uint32_t n_r = cnt > (uint32_t)r * kWave ? min(cnt - (uint32_t)r * kWave, (uint32_t)kWave) : 0u;
+    active[r] = n_r >= (uint32_t)kWave ? ~0ull : ((1ull << n_r) - 1ull);
+    chosen[r] = 0;
+  }
+  uint32_t need = m, n_active = cnt;
+  while (need > 0) {
+    if (n_active == need) {
+#pragma unroll
+      for (int r = 0; r < NK; ++r) chosen[r] |= active[r];
+      break;
+    }
+    uint64_t pK = 0, pk = 0, pivot_bit = 0;
+    int pivot_reg = -1;
+#pragma unroll
+    for (int r = 0; r < NK; ++r) {
+      if (pivot_reg < 0 && active[r] != 0) {
+        const uint32_t pl = (uint32_t)__ffsll((long long)active[r]) - 1u;
+        pK = readlane_u64(K[r], pl);
+        pk = readlane_u64(k[r], pl);
+        pivot_reg = r;
+        pivot_bit = 1ull << pl;
+      }
+    }
+    uint64_t less[NK];
+    uint32_t n_less = 0;
+#pragma unroll
+    for (int r = 0; r < NK; ++r) {
+      less[r] = __ballot(tuple_less(K[r], k[r], pK, pk)) & active[r];
+      n_less += (uint32_t)__popcll(less[r]);
+    }
+    if (n_less >= need) {
+#pragma unroll
+      for (int r = 0; r < NK; ++r) active[r] = less[r];
+      n_active = n_less;
+    } else {
+#pragma unroll
+      for (int r = 0; r < NK; ++r) {
+        const uint64_t taken = less[r] | (r == pivot_reg ? pivot_bit : 0ull);
+        chosen[r] |= taken;
+        active[r] &= ~taken;
+      }
+      need -= n_less + 1;
+      n_active -= n_less + 1;
+    }
+  }
+  uint32_t pos[NK];
+#pragma unroll
+  for (int r = 0; r < NK; ++r) pos[r] = 0;
+#pragma unroll
+  for (int r2 = 0; r2 < NK; ++r2) {
+    uint64_t pending = chosen[r2];
+    while (pending) {
+      const uint32_t t = (uint32_t)__ffsll((long long)pending) - 1u;
+      pending &= pending - 1;
+      const uint32_t other_slot = (uint32_t)__builtin_amdgcn_readlane((int32_t)(uint32_t)k[r2], (int32_t)t);
+#pragma unroll
+      for (int r = 0; r < NK; ++r) pos[r] += other_slot < (uint32_t)k[r] ? 1u : 0u;
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < NK; ++r)
+    if ((chosen[r] >> lane) & 1ull) on_selected(pos[r], k[r]);
+}
+
+// Weighted selection from the two candidate lists (A: draws above the threshold, B: draws below it
+// that could still matter as cached slots).  The answer is the m best (K, k) among all of A and
+// the cached members of B: an uncached slot outside the m largest draws loses to all of those,
+// and a cached slot below B's floor has a key above that of the threshold draw taken as
+// uncached, which every one of the m largest draws beats.  All lookups are issued together (one
+// memory round trip per node), the survivors are packed into E (bit 31 of the slot word marks
+// a cached one; slots stay below 2^31), keyed densely, and chosen in registers.
+// Returns false (nothing written) if the survivors do not fit; the caller then rescans the row.
+constexpr int kListPerLane = 8;  // list entries one lane looks up
+constexpr uint64_t kCachedMark = 1ull << 31;
+
+template <int NK, typename IdxT, typename Emit>
+__device__ __forceinline__ void key_and_select(const SampleArgs<IdxT>& a, const uint64_t* E, uint32_t n_s,
+                                               uint32_t m, const Emit& emit) {
+  const uint32_t lane = lane_id();
+  uint64_t K[NK], k[NK];
+#pragma unroll
+  for (int r = 0; r < NK; ++r) {
+    K[r] = ~0ull;
+    k[r] = ~0ull;
+    if ((uint32_t)r * kWave < n_s) {  // uniform: a dense round of keys
+      const uint32_t j = (uint32_t)r * kWave + lane;
+      if (j < n_s) {
+        const uint64_t e = E[j];
+        k[r] = e & ~kCachedMark;
+        K[r] = sample_key(~(uint32_t)(e >> 32), (e & kCachedMark) ? a.bias_q16 : 65536u);
+      }
+    }
+  }
+  select_pairs_in_registers<NK>(K, k, n_s, m, [&](uint32_t pos, uint64_t kk) { emit(pos, (uint32_t)kk); });
+}
+
+template <typename IdxT, typename Emit>
+__device__ __forceinline__ bool weighted_from_lists(const SampleArgs<IdxT>& a, int64_t row, const uint64_t* list_a,
+                                    uint32_t cnt_a, const uint64_t* list_b, uint32_t cnt_b, uint32_t m,
+                                    uint64_t* E, uint32_t ecap, const Emit& emit) {
+  const uint32_t lane = lane_id();
+  const uint32_t total = cnt_a + cnt_b;
+  if (total > (uint32_t)kListPerLane * kWave) return false;
+  uint64_t key[kListPerLane];
+  int64_t u[kListPerLane];
+#pragma unroll
+  for (int c = 0; c < kListPerLane; ++c) {
+    const uint32_t j = (uint32_t)c * kWave + lane;
+    key[c] = j < total ? (j < cnt_a ? list_a[j] : list_b[j - cnt_a]) : 0ull;
+    u[c] = j < total ? (int64_t)a.indices[row + (uint32_t)key[c]] : -1;
+  }
+  uint32_t n_s = 0;  // same value in every lane
+#pragma unroll
+  for (int c = 0; c < kListPerLane; ++c) {
+    if ((uint32_t)c * kWave < total) {
+      const uint32_t j = (uint32_t)c * kWave + lane;
+      const bool cached = j < total && is_cached(a, u[c]);
+      const bool keep = j < cnt_a || cached;
+      const uint64_t mask = __ballot(keep);
+      if (keep) {
+        const uint32_t idx = n_s + lanes_below(mask);
+        if (idx < ecap) E[idx] = key[c] | (cached ? kCachedMark : 0ull);
+      }
+      n_s += (uint32_t)__popcll(mask);
+    }
+  }
+  if (n_s > ecap || n_s > 8u * kWave) return false;
+  wave_sync();
+  if (n_s <= kWave)
+    key_and_select<1>(a, E, n_s, m, emit);
+  else if (n_s <= 2 * kWave)
+    key_and_select<2>(a, E, n_s, m, emit);
+  else if (n_s <= 4 * kWave)
+    key_and_select<4>(a, E, n_s, m, emit);
+  else
+    key_and_select<8>(a, E, n_s, m, emit);
+  return true;
+}
+
+// Floor of the second list, known before anything is looked up.  With p = lambda / deg the
+// threshold keeps draws with 1 - u <= p, and the worst key of the final reservoir is at most the
+// key of the threshold draw taken as uncached.  A cached slot reaches that key only if
+// u >= (1 - p)^gamma, and (1 - p)^gamma >= 1 - gamma p, so every such slot has 1 - u <= gamma p.
+// keep = p * 2^32 as computed for the threshold; the relative and absolute margins (2^-10, and
+// gamma * 2^-20 of the draw range) cover the float rounding here and the few units by which
+// the fixed-point logarithm and the floor in the key differ from the exact values, all scaled
+// by gamma.  A lower floor only lengthens the list.
+__device__ __forceinline__ uint32_t second_list_floor(float keep, uint32_t bias_q16) {
+  const float kb = (float)bias_q16 * (1.0f / 65536.0f) * (keep * (1.0f + 1.0f / 1024.0f) + 4096.0f);
+  return kb >= 4294967040.0f ? 0u : 0u - (uint32_t)kb;
+}
+
+// cand [cap] and rest [m (+ 3 m + 2 xcap + capb when weighted)] are this wavefront's LDS buffers.
+// With prefiltered set, cand already holds pre_cnt candidates in slot order (a workgroup scanned
+// the row together; pre_cnt_b entries of the second list too) and the scan is skipped.
 template <typename IdxT, bool kWeighted>
-__device__ void sample_node_wave(const SampleArgs<IdxT>& a, const int32_t* tile_offs,
+__device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, const int32_t* tile_offs,
                                  const NodeRec& r, int32_t n_dst, uint64_t* cand, uint64_t* rest,
-                                 bool prefiltered, uint32_t pre_cnt) {
+                                 bool prefiltered, uint32_t pre_cnt, uint32_t pre_cnt_b) {
   const uint32_t lane = lane_id();
   const int64_t v = r.v;
   const int64_t row = r.row;
@@ -568,11 +763,18 @@ __device__ void sample_node_wave(const SampleArgs<IdxT>& a, const int32_t* tile_
   // keep slots whose draw clears a threshold set so that about lambda survive, rank those
   // (any threshold gives the same result; this one only sets how many candidates survive)
   uint32_t X0 = 0;
+  float keep = 4294967296.0f;
   if (deg > a.lambda) {
-    const float keep = __fdividef((float)a.lambda, (float)deg) * 4294967296.0f;  // < 2^32
+    keep = __fdividef((float)a.lambda, (float)deg) * 4294967296.0f;  // < 2^32
     X0 = 0u - (uint32_t)keep;
   }
   uint32_t cnt = pre_cnt;  // same value in every lane
+  // weighted: a second list takes the slots below the threshold whose draw could still matter as
+  // a cached slot, so that the row need not be scanned again
+  uint64_t* list_b = rest + 4 * (size_t)m + 2 * (size_t)a.xcap;  // [capb]
+  uint32_t cnt_b = pre_cnt_b;
+  const bool want_b = kWeighted && a.capb > 0;
+  const uint32_t X1 = want_b ? second_list_floor(keep, a.bias_q16) : 0u;
   if (!a.force_radix && !prefiltered) {
     for (uint32_t q0 = 0; q0 < n_quads; q0 += kWave) {
       const uint32_t q = q0 + lane;
@@ -597,8 +799,37 @@ __device__ void sample_node_wave(const SampleArgs<IdxT>& a, const int32_t* tile_
         }
         cnt += (uint32_t)(__popcll(mk[0]) + __popcll(mk[1]) + __popcll(mk[2]) + __popcll(mk[3]));
       }
+      if (want_b) {
+        bool pb[4];
+        uint64_t mb[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          pb[w] = (4u * q + (uint32_t)w < deg) && (x[w] >= X1) && (x[w] < X0);
+          mb[w] = __ballot(pb[w]);
+        }
+        if (mb[0] | mb[1] | mb[2] | mb[3]) {
+          uint32_t idx = cnt_b + lanes_below(mb[0]) + lanes_below(mb[1]) + lanes_below(mb[2]) + lanes_below(mb[3]);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            if (pb[w]) {
+              if (idx < a.capb) list_b[idx] = draw_order_key(x[w], 4u * q + (uint32_t)w);
+              ++idx;
+            }
+          }
+          cnt_b += (uint32_t)(__popcll(mb[0]) + __popcll(mb[1]) + __popcll(mb[2]) + __popcll(mb[3]));
+        }
+      }
     }
     wave_sync();
+  }
+  // the lists can replace the second scan if both are complete
+  const bool lists_ok = want_b && !a.force_radix && cnt >= m && cnt <= a.cap && cnt_b <= a.capb;
+  if (kWeighted && lists_ok) {
+    uint64_t* E = rest + 4 * (size_t)m;  // [2 xcap], the challenger buffers of the rescanning path
+    if (weighted_from_lists<IdxT>(a, row, cand, cnt, list_b, cnt_b, m, E, 2 * a.xcap, emit)) {
+      wave_sync();
+      return;
+    }
   }
   if (!a.force_radix && cnt >= m && cnt <= a.cap && cnt <= 4 * kWave) {
     // the usual case: few candidates, selected in registers.  With equal weights the winners
@@ -662,7 +893,7 @@ __device__ void sample_node_wave(const SampleArgs<IdxT>& a, const int32_t* tile_
     const uint32_t s = (uint32_t)k;
     const uint32_t x = ~(uint32_t)(k >> 32);
     const int64_t u = (int64_t)a.indices[row + s];
-    const uint32_t w = a.cache_map[u] >= 0 ? a.bias_q16 : 65536u;
+    const uint32_t w = is_cached(a, u) ? a.bias_q16 : 65536u;
     RK[j] = sample_key(x, w);
     kT = k > kT ? k : kT;
   }
@@ -672,6 +903,38 @@ __device__ void sample_node_wave(const SampleArgs<IdxT>& a, const int32_t* tile_
   uint64_t BK = RK[m - 1], Bk = Rk[m - 1];
   uint32_t x_lo = draw_floor_for_key(BK, a.bias_q16);
   uint32_t nX = 0;  // same value in every lane
+  // one slot per lane goes through lookup, key and comparison with the bar; challengers are
+  // appended, and the buffer is folded into the reservoir when the next ballot might not fit
+  auto challenge = [&](bool live, uint64_t k) {
+    const uint32_t s = (uint32_t)k;
+    const uint32_t x = ~(uint32_t)(k >> 32);
+    bool challenger = false;
+    uint64_t K = 0;
+    if (live && x >= x_lo && k > kT) {
+      const int64_t u = (int64_t)a.indices[row + s];
+      if (is_cached(a, u)) {
+        K = sample_key(x, a.bias_q16);
+        challenger = tuple_less(K, k, BK, Bk);
+      }
+    }
+    const uint64_t mask = __ballot(challenger);
+    if (mask) {
+      if (challenger) {
+        const uint32_t idx = nX + lanes_below(mask);
+        XK[idx] = K;
+        Xk[idx] = k;
+      }
+      nX += (uint32_t)__popcll(mask);
+      if (nX + kWave > a.xcap) {
+        wave_sync();
+        merge_best(m, m, nX, RK, Rk, XK, Xk, NK, Nk);
+        nX = 0;
+        BK = RK[m - 1];
+        Bk = Rk[m - 1];
+        x_lo = draw_floor_for_key(BK, a.bias_q16);
+      }
+    }
+  };
   for (uint32_t q0 = 0; q0 < n_quads; q0 += kWave) {
     const uint32_t q = q0 + lane;
     uint32_t x[4];
@@ -679,33 +942,7 @@ __device__ void sample_node_wave(const SampleArgs<IdxT>& a, const int32_t* tile_
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       const uint32_t s = 4u * q + (uint32_t)w;
-      const uint64_t k = draw_order_key(x[w], s);
-      bool challenger = false;
-      uint64_t K = 0;
-      if (s < deg && x[w] >= x_lo && k > kT) {
-        const int64_t u = (int64_t)a.indices[row + s];
-        if (a.cache_map[u] >= 0) {
-          K = sample_key(x[w], a.bias_q16);
-          challenger = tuple_less(K, k, BK, Bk);
-        }
-      }
-      const uint64_t mask = __ballot(challenger);
-      if (mask) {
-        if (challenger) {
-          const uint32_t idx = nX + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-          XK[idx] = K;
-          Xk[idx] = k;
-        }
-        nX += (uint32_t)__popcll(mask);
-        if (nX + kWave > a.xcap) {  // the next ballot might not fit: fold the buffer in
-          wave_sync();
-          merge_best(m, m, nX, RK, Rk, XK, Xk, NK, Nk);
-          nX = 0;
-          BK = RK[m - 1];
-          Bk = Rk[m - 1];
-          x_lo = draw_floor_for_key(BK, a.bias_q16);
-        }
-      }
+      challenge(s < deg, draw_order_key(x[w], s));
     }
   }
   wave_sync();
@@ -758,7 +995,7 @@ __device__ void sample_node_group(const SampleArgs<IdxT>& a, const int32_t* tile
       cached[w] = false;
       if (alive & (1u << w)) {
         const int64_t u = (int64_t)a.indices[row + 4u * gl + w];
-        cached[w] = a.cache_map[u] >= 0;
+        cached[w] = is_cached(a, u);
         any_c |= cached[w];
         any_u |= !cached[w];
       }
@@ -834,27 +1071,39 @@ __device__ void sample_node_group(const SampleArgs<IdxT>& a, const int32_t* tile
 constexpr uint32_t kHubRegion = 64;  // candidates one wavefront may contribute
 
 template <typename IdxT, bool kWeighted>
-__device__ void sample_hub_block(const SampleArgs<IdxT>& a, const int32_t* tile_offs,
-                                 const NodeRec& r, int32_t n_dst, uint64_t* lds) {
+__device__ __forceinline__ void hub_scan(const SampleArgs<IdxT>& a, const NodeRec& r, uint64_t* lds,
+                                         uint64_t*& joined_out, uint64_t*& rest_out, uint32_t& pre_cnt,
+                                         uint32_t& pre_cnt_b) {
   const uint32_t lane = lane_id();
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(threadIdx.x >> 6));
   const uint32_t n_waves = blockDim.x >> 6;
   uint64_t* region = lds + (size_t)wave * kHubRegion;         // [kHubRegion]
   uint64_t* joined = lds + (size_t)n_waves * kHubRegion;      // [cap]
   uint32_t* counts = (uint32_t*)(joined + a.cap);             // [n_waves] (<= 16 -> 8 entries)
-  uint64_t* rest = joined + a.cap + 8;
+  uint32_t* shared_cnt_b = (uint32_t*)(joined + a.cap + 8);   // one more entry
+  uint64_t* rest = joined + a.cap + 9;
   const int64_t v = r.v;
   const uint32_t deg = r.deg;
+  // the second candidate list of the weighted case is shared: wavefronts reserve space in it
+  // with one LDS atomic per append (its order does not matter)
+  uint64_t* list_b = rest + 4 * (size_t)a.fanout + 2 * (size_t)a.xcap;
+  const bool want_b = kWeighted && a.capb > 0;
+  if (want_b) {
+    if (threadIdx.x == 0) *shared_cnt_b = 0;
+    __syncthreads();
+  }
   uint32_t mine = 0;
   if (deg > (uint32_t)a.fanout && !a.force_radix) {
     const PhiloxKey pk{(uint32_t)(uint64_t)v, (uint32_t)((uint64_t)v >> 32), (uint32_t)a.hop,
                        a.seed_lo, a.seed_hi};
     const uint32_t n_quads = (deg + 3) >> 2;
     uint32_t X0 = 0;
+    float keep = 4294967296.0f;
     if (deg > a.lambda) {
-      const float keep = __fdividef((float)a.lambda, (float)deg) * 4294967296.0f;
+      keep = __fdividef((float)a.lambda, (float)deg) * 4294967296.0f;
       X0 = 0u - (uint32_t)keep;
     }
+    const uint32_t X1 = want_b ? second_list_floor(keep, a.bias_q16) : 0u;
     // contiguous share of the row per wavefront, a whole number of 64-quad steps
     const uint32_t share = (((n_quads + n_waves - 1) / n_waves) + kWave - 1) & ~(uint32_t)(kWave - 1);
     const uint32_t q_begin = wave * share;
@@ -881,6 +1130,29 @@ __device__ void sample_hub_block(const SampleArgs<IdxT>& a, const int32_t* tile_
         }
         mine += (uint32_t)(__popcll(mk[0]) + __popcll(mk[1]) + __popcll(mk[2]) + __popcll(mk[3]));
       }
+      if (want_b) {
+        bool pb[4];
+        uint64_t mb[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          pb[w] = (4u * q + (uint32_t)w < deg) && (x[w] >= X1) && (x[w] < X0);
+          mb[w] = __ballot(pb[w]);
+        }
+        if (mb[0] | mb[1] | mb[2] | mb[3]) {
+          const uint32_t n_new = (uint32_t)(__popcll(mb[0]) + __popcll(mb[1]) + __popcll(mb[2]) + __popcll(mb[3]));
+          uint32_t start = 0;
+          if (lane == 0) start = atomicAdd(shared_cnt_b, n_new);
+          start = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)start);
+          uint32_t idx = start + lanes_below(mb[0]) + lanes_below(mb[1]) + lanes_below(mb[2]) + lanes_below(mb[3]);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            if (pb[w]) {
+              if (idx < a.capb) list_b[idx] = draw_order_key(x[w], 4u * q + (uint32_t)w);
+              ++idx;
+            }
+          }
+        }
+      }
     }
   }
   if (lane == 0) counts[wave] = mine;
@@ -897,11 +1169,12 @@ __device__ void sample_hub_block(const SampleArgs<IdxT>& a, const int32_t* tile_
   if (!overflow)
     for (uint32_t j = lane; j < mine; j += kWave) joined[offset + j] = region[j];
   __syncthreads();
-  // too few candidates, too many, or a forced exhaustive run: wavefront 0 takes the slow path
-  if (wave == 0)
-    sample_node_wave<IdxT, kWeighted>(a, tile_offs, r, n_dst, joined, rest, true,
-                                      overflow ? a.cap + 1u : total);
-  __syncthreads();  // the regions are reused for the workgroup's next hub
+  // too few candidates, too many, or a forced exhaustive run: the finishing wavefront takes the
+  // slow path
+  joined_out = joined;
+  rest_out = rest;
+  pre_cnt = overflow ? a.cap + 1u : total;
+  pre_cnt_b = want_b ? *shared_cnt_b : 0u;
 }
 
 template <typename IdxT, int G, bool kWeighted>
@@ -922,7 +1195,7 @@ __device__ __forceinline__ void run_group_role(const SampleArgs<IdxT>& a, const 
   }
 }
 
-constexpr int kSampleMaxThreads = 1024;
+constexpr int kSampleMaxThreads = 256;
 
 // Workgroups take roles by index: role_blocks[0..2] serve the small-degree bins with lane groups,
 // role_blocks[3] the wide nodes (one wavefront each), role_blocks[4] the hubs (one workgroup each).
@@ -953,31 +1226,30 @@ __global__ __launch_bounds__(kSampleMaxThreads) void k_sample(const SampleArgs<I
   // below are uniform control flow for the whole wavefront
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(threadIdx.x >> 6));
   const uint32_t n_waves = blockDim.x >> 6;
-  if (b < a.role_blocks[3]) {
-    const int64_t n_wide = a.st->bin_count[3];
-    uint64_t* my_lds = lds + (size_t)wave * a.lds_per_wave;
-    const int64_t waves = (int64_t)a.role_blocks[3] * n_waves;
-    int64_t t = (int64_t)b * n_waves + wave;
-    NodeRec cur = {};
-    if (t < n_wide) cur = a.bins[3][t];
-    for (; t < n_wide; t += waves) {
-      NodeRec nxt = {};
-      if (t + waves < n_wide) nxt = a.bins[3][t + waves];  // in flight while cur is sampled
-      if (cur.i >= 0 && cur.i < n_dst)
-        sample_node_wave<IdxT, kWeighted>(a, tile_offs, cur, n_dst, my_lds, my_lds + a.cap, false, 0u);
-      cur = nxt;
-    }
-    return;
-  }
-  b -= a.role_blocks[3];
-  const int64_t n_hub = a.st->bin_count[4];
-  int64_t t = b;
+  // wide nodes and hubs share one loop (and one copy of the selection code): a wavefront takes a
+  // wide node by itself; a hub is scanned by the whole workgroup and finished by wavefront 0
+  const bool hub_role = b >= a.role_blocks[3];  // the same for the whole workgroup
+  if (hub_role) b -= a.role_blocks[3];
+  const int bin = hub_role ? 4 : 3;
+  const int64_t n_nodes = a.st->bin_count[bin];
+  const NodeRec* recs = a.bins[bin];
+  const int64_t stride = hub_role ? (int64_t)a.role_blocks[4] : (int64_t)a.role_blocks[3] * n_waves;
+  int64_t t = hub_role ? (int64_t)b : (int64_t)b * n_waves + wave;
+  uint64_t* my_lds = lds + (size_t)wave * a.lds_per_wave;
   NodeRec cur = {};
-  if (t < n_hub) cur = a.bins[4][t];
-  for (; t < n_hub; t += a.role_blocks[4]) {  // the same node for every thread of the workgroup
+  if (t < n_nodes) cur = recs[t];
+  for (; t < n_nodes; t += stride) {
     NodeRec nxt = {};
-    if (t + a.role_blocks[4] < n_hub) nxt = a.bins[4][t + a.role_blocks[4]];
-    if (cur.i >= 0 && cur.i < n_dst) sample_hub_block<IdxT, kWeighted>(a, tile_offs, cur, n_dst, lds);
+    if (t + stride < n_nodes) nxt = recs[t + stride];  // in flight while cur is sampled
+    if (cur.i >= 0 && cur.i < n_dst) {
+      uint64_t* cand = my_lds;
+      uint64_t* rest = my_lds + a.cap;
+      uint32_t pre_cnt = 0, pre_cnt_b = 0;
+      if (hub_role) hub_scan<IdxT, kWeighted>(a, cur, lds, cand, rest, pre_cnt, pre_cnt_b);
+      if (!hub_role || wave == 0)
+        sample_node_wave<IdxT, kWeighted>(a, tile_offs, cur, n_dst, cand, rest, hub_role, pre_cnt, pre_cnt_b);
+      if (hub_role) __syncthreads();  // the regions are reused for the workgroup's next hub
+    }
     cur = nxt;
   }
 }

@@ -42,6 +42,8 @@ struct a3_ctx {
   a3::NodeRec* bins[a3::kNumBins] = {nullptr};  // frontier node records by degree bin
   int32_t* node_map = nullptr;  // global id -> position, grown on demand
   int64_t node_map_cap = 0;
+  uint64_t* cached_bits = nullptr;  // one bit per node, rebuilt from the device map by every weighted call
+  int64_t cached_bits_words = 0;
   bool node_map_dirty = false;
   DevState* d_state = nullptr;
   DevState* h_state = nullptr;      // pinned host copy of the counts, written by the last kernel
@@ -101,16 +103,33 @@ inline unsigned blocks_for(int64_t n, int per_block) {
 // negligible probability (then the exhaustive path takes over)
 uint32_t lambda_for(int32_t m) { return (uint32_t)(m + 4.0 * std::sqrt((double)m) + 8.0); }
 uint32_t cap_for(uint32_t lambda) { return ((2 * lambda + 63) / 64) * 64; }
-constexpr uint32_t kChallengerCap = 192;
 constexpr int64_t kMaxRoleWaves = 8192;  // wavefronts serving one role of k_sample
 constexpr int64_t kMaxHubBlocks = 2048;
 constexpr int kSampleWaves = 4;           // wavefronts per k_sample workgroup (fewer if LDS is short)
 
+// Second candidate list of the weighted case: slots below the threshold whose draw could still
+// matter as a cached slot; about (gamma - 1) * lambda of them, sized four standard deviations
+// above that.  The two lists together must fit the 512 entries one wavefront looks up at once;
+// beyond that the list is not used (0) and the row is scanned a second time instead.
+constexpr uint32_t kMaxListEntries = 512;
+uint32_t second_list_cap(int32_t fanout, uint32_t bias_q16) {
+  const double mean = (bias_q16 / 65536.0 - 1.0) * lambda_for(fanout);
+  const double want = mean + 4.0 * std::sqrt(mean) + 16.0;
+  const uint32_t capb = ((uint32_t)want + 63u) / 64u * 64u;
+  return cap_for(lambda_for(fanout)) + capb > kMaxListEntries ? 0u : capb;
+}
+// Challenger buffers of the rescanning path (two of xcap entries); the list path packs its
+// survivors, at most both lists, into the same memory.
+uint32_t challenger_cap(int32_t fanout, uint32_t capb) {
+  const uint32_t both = cap_for(lambda_for(fanout)) + capb;
+  return std::max<uint32_t>(64u, (both + 1u) / 2u);
+}
+
 // uint64 entries of LDS one wavefront needs in the wavefront-per-node path
-uint32_t sample_lds_entries(int32_t fanout, bool weighted) {
+uint32_t sample_lds_entries(int32_t fanout, bool weighted, uint32_t capb) {
   const uint32_t cap = cap_for(lambda_for(fanout));
   uint32_t entries = cap + (uint32_t)fanout;
-  if (weighted) entries += 3 * (uint32_t)fanout + 2 * kChallengerCap;
+  if (weighted) entries += 3 * (uint32_t)fanout + 2 * challenger_cap(fanout, capb) + capb;
   return entries;
 }
 
@@ -123,11 +142,11 @@ void prof_mark(a3_ctx* ctx, int kind, int which) {
 }
 
 // LDS of one k_sample workgroup of n_waves wavefronts: the larger of "every wavefront works on
-// its own node" and "the workgroup works on one hub" (regions, joined candidates, counts, and the
-// finishing wavefront's buffers)
+// its own node" and "the workgroup works on one hub" (regions, joined candidates, counts, the shared
+// counter of the second list, and the finishing wavefront's buffers)
 size_t sample_block_lds_bytes(uint32_t lds_per_wave, uint32_t cap, int n_waves) {
   const size_t own = (size_t)lds_per_wave * n_waves;
-  const size_t hub = (size_t)a3::kHubRegion * n_waves + cap + 8 + (lds_per_wave - cap);
+  const size_t hub = (size_t)a3::kHubRegion * n_waves + cap + 9 + (lds_per_wave - cap);
   return std::max(own, hub) * sizeof(uint64_t);
 }
 
@@ -142,6 +161,7 @@ void free_all(a3_ctx* ctx) {
   for (void* p : ctx->allocs) (void)hipFree(p);
   ctx->allocs.clear();
   if (ctx->node_map) (void)hipFree(ctx->node_map);
+  if (ctx->cached_bits) (void)hipFree(ctx->cached_bits);
   ctx->node_map = nullptr;
   if (ctx->h_state) (void)hipHostFree(ctx->h_state);
   ctx->h_state = nullptr;
@@ -172,6 +192,31 @@ int ensure_node_map(a3_ctx* ctx, int64_t num_nodes) {
   return A3_OK;
 }
 
+// The bitmap of cached nodes that the weighted kernels look up, rebuilt from the caller's device
+// map on every call (one streaming pass over 4 bytes per node; the map may have changed).
+int build_cached_bits(a3_ctx* ctx, const int32_t* cache_map, int64_t num_nodes) {
+  const int64_t words = (num_nodes + 63) / 64;
+  if (words > ctx->cached_bits_words) {
+    if (ctx->cached_bits) {
+      A3_HIP(ctx, hipStreamSynchronize(ctx->stream));
+      A3_HIP(ctx, hipFree(ctx->cached_bits));
+      ctx->cached_bits = nullptr;
+      ctx->cached_bits_words = 0;
+    }
+    void* q = nullptr;
+    A3_HIP(ctx, hipMalloc(&q, (size_t)words * sizeof(uint64_t)));
+    ctx->cached_bits = (uint64_t*)q;
+    ctx->cached_bits_words = words;
+  }
+  if (words == 0) return A3_OK;
+  // a wavefront makes four words per round; 2048 workgroups at most
+  const unsigned blocks = (unsigned)std::min<int64_t>((words + 15) / 16, 2048);
+  hipLaunchKernelGGL(a3::k_cached_bits, dim3(blocks), dim3(a3::kTileThreads), 0, ctx->stream, cache_map,
+                     num_nodes, ctx->cached_bits);
+  A3_HIP(ctx, hipGetLastError());
+  return A3_OK;
+}
+
 template <typename IdxT>
 int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int64_t num_nodes,
                    const IdxT* seeds, int64_t num_seeds, const int32_t* fanouts, int32_t num_hops,
@@ -198,6 +243,10 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
   ctx->node_map_dirty = true;  // until the call has cleaned up after itself
 
   prof_mark(ctx, 0, 0);
+  if (weighted) {
+    rc = build_cached_bits(ctx, cache_map, num_nodes);
+    if (rc != A3_OK) return rc;
+  }
   if (validate) {
     hipLaunchKernelGGL(a3::k_init_seeds_checked<IdxT>, dim3(blocks_for(num_seeds, 256)), dim3(256),
                        0, st, seeds, num_seeds, num_nodes, S, ctx->node_map, ds);
@@ -235,7 +284,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       a3::SampleArgs<IdxT> sa;
       sa.indptr = indptr;
       sa.indices = indices;
-      sa.cache_map = cache_map;
+      sa.cached_bits = (const uint32_t*)ctx->cached_bits;
       sa.S = S;
       sa.tile_offs = fuse_dst ? nullptr : ctx->tile_offs;
       sa.tile_sums = ctx->tile_sums;
@@ -247,7 +296,8 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       for (int b = 0; b < a3::kNumBins; ++b) sa.bins[b] = ctx->bins[b];
       sa.num_nodes = num_nodes;
       sa.cap_edges = ctx->cap_edges[h];
-      sa.lds_per_wave = sample_lds_entries(f, weighted);
+      sa.capb = weighted ? second_list_cap(f, bias_q16) : 0u;
+      sa.lds_per_wave = sample_lds_entries(f, weighted, sa.capb);
       sa.cap = cap_for(lambda_for(f));
       // wavefronts per workgroup: as many as the LDS allows, at most kSampleWaves
       const size_t kLdsLimit = 64 * 1024;
@@ -266,7 +316,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       sa.hop = h;
       sa.fanout = f;
       sa.lambda = lambda_for(f);
-      sa.xcap = kChallengerCap;
+      sa.xcap = challenger_cap(f, sa.capb);
       sa.bias_q16 = bias_q16;
       sa.seed_lo = (uint32_t)rng_seed;
       sa.seed_hi = (uint32_t)(rng_seed >> 32);

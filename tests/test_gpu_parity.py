@@ -64,6 +64,26 @@ def test_weighted_selection_matches_oracle(gamma):
     ctx.close()
 
 
+def test_weighted_candidate_lists_of_every_size():
+    """Wide rows and hubs with many cached neighbours: the two candidate lists of the weighted
+    path hold from a few to several hundred slots (every register count of the selection, and
+    past its limit, where the row is scanned a second time instead)."""
+    g = make_graph(20_000, 700.0, 40, 12_000, 2.1, True, 5, torch.int32)
+    deg = (g.indptr[1:] - g.indptr[:-1]).numpy()
+    assert deg.max() > 4096 and (deg > 64).sum() > 1000
+    d_ip, d_ix = g.indptr.to(DEV), g.indices.to(DEV)
+    w = get_config("mini_social")
+    order = np.argsort(-deg, kind="stable")
+    seeds = np.concatenate([order[:24], order[2000:2040], order[-16:]]).astype(np.int32)
+    ctx = a3.Context(len(seeds), [15, 3])
+    for frac in [0.1, 0.5, 0.9]:
+        cm = degree_ranked_cache(g, None, frac).cache_map.numpy()
+        for gamma, fan in [(1.25, [15, 3]), (2.0, [15]), (3.0, [10, 3]), (4.0, [15, 2]), (6.0, [5, 3]),
+                           (8.0, [15]), (12.0, [10]), (20.0, [15])]:
+            _compare(ctx, w, g, d_ip, d_ix, seeds, fan, cm, gamma, 21, f"lists frac={frac}")
+    ctx.close()
+
+
 def test_exhaustive_selection_path_matches_oracle():
     for name in ["tiny", "mini_copurchase"]:
         w, g, d_ip, d_ix = _graph(name)
