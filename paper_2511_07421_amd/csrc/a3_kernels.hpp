@@ -644,44 +644,62 @@ __device__ __forceinline__ void select_pairs_in_registers(const uint64_t (&K)[NK
 }
 
 // Weighted selection from the two candidate lists (A: draws above the threshold, B: draws below it
-// that could still matter as cached slots).  The answer is the m best (K, k) among all of A and
-// the cached members of B: an uncached slot outside the m largest draws loses to all of those,
-// and a cached slot below B's floor has a key above that of the threshold draw taken as
-// uncached, which every one of the m largest draws beats.  All lookups are issued together (one
-// memory round trip per node), the survivors are packed into E (bit 31 of the slot word marks
-// a cached one; slots stay below 2^31), keyed densely, and chosen in registers.
-// Returns false (nothing written) if the survivors do not fit; the caller then rescans the row.
+// that could still matter as cached slots).  The answer lies among all of A and the cached
+// members of B: an uncached slot outside the m largest draws loses to all of those, and a cached
+// slot below B's floor has a key above that of the threshold draw taken as uncached, which every
+// one of the m largest draws beats.  Inside one weight class the key K is monotone in the draw,
+// so the answer also lies among the m largest draws of the uncached candidates and the m largest
+// draws of the cached ones: only those 2 m slots get a key (the logarithm costs as much as
+// scanning hundreds of slots), and with one class empty none does.
+// All lookups are issued together, one memory round trip per node.  E [ecap] takes the two
+// classes (uncached from the front, cached from the back; ecap >= both lists), T [2 m] their
+// best.  Returns false (nothing written, the lists untouched) if the sizes do not fit the
+// registers; the caller then rescans the row.
 constexpr int kListPerLane = 8;  // list entries one lane looks up
-constexpr uint64_t kCachedMark = 1ull << 31;
+
+// the m smallest of list [n] (all of them if n <= m), in any order, to out; n <= 256
+__device__ __forceinline__ void smallest_to(const uint64_t* list, uint32_t n, uint32_t m, uint64_t* out) {
+  auto put = [&](uint32_t pos, uint64_t key) { out[pos] = key; };
+  if (n <= m) {
+    for (uint32_t j = lane_id(); j < n; j += kWave) out[j] = list[j];
+  } else if (n <= kWave) {
+    select_in_registers<1>(list, n, m, put);
+  } else if (n <= 2 * kWave) {
+    select_in_registers<2>(list, n, m, put);
+  } else {
+    select_in_registers<4>(list, n, m, put);
+  }
+}
 
 template <int NK, typename IdxT, typename Emit>
-__device__ __forceinline__ void key_and_select(const SampleArgs<IdxT>& a, const uint64_t* E, uint32_t n_s,
-                                               uint32_t m, const Emit& emit) {
+__device__ __forceinline__ void key_and_select(const SampleArgs<IdxT>& a, const uint64_t* T, uint32_t t_u,
+                                               uint32_t t_c, uint32_t m, const Emit& emit) {
   const uint32_t lane = lane_id();
+  const uint32_t n = t_u + t_c;
   uint64_t K[NK], k[NK];
 #pragma unroll
   for (int r = 0; r < NK; ++r) {
     K[r] = ~0ull;
     k[r] = ~0ull;
-    if ((uint32_t)r * kWave < n_s) {  // uniform: a dense round of keys
+    if ((uint32_t)r * kWave < n) {  // uniform: a dense round of keys
       const uint32_t j = (uint32_t)r * kWave + lane;
-      if (j < n_s) {
-        const uint64_t e = E[j];
-        k[r] = e & ~kCachedMark;
-        K[r] = sample_key(~(uint32_t)(e >> 32), (e & kCachedMark) ? a.bias_q16 : 65536u);
+      if (j < n) {
+        k[r] = j < t_u ? T[j] : T[m + (j - t_u)];
+        K[r] = sample_key(~(uint32_t)(k[r] >> 32), j < t_u ? 65536u : a.bias_q16);
       }
     }
   }
-  select_pairs_in_registers<NK>(K, k, n_s, m, [&](uint32_t pos, uint64_t kk) { emit(pos, (uint32_t)kk); });
+  select_pairs_in_registers<NK>(K, k, n, m, [&](uint32_t pos, uint64_t kk) { emit(pos, (uint32_t)kk); });
 }
 
 template <typename IdxT, typename Emit>
 __device__ __forceinline__ bool weighted_from_lists(const SampleArgs<IdxT>& a, int64_t row, const uint64_t* list_a,
-                                    uint32_t cnt_a, const uint64_t* list_b, uint32_t cnt_b, uint32_t m,
-                                    uint64_t* E, uint32_t ecap, const Emit& emit) {
+                                                    uint32_t cnt_a, const uint64_t* list_b, uint32_t cnt_b,
+                                                    uint32_t m, uint64_t* E, uint32_t ecap, uint64_t* T,
+                                                    const Emit& emit) {
   const uint32_t lane = lane_id();
   const uint32_t total = cnt_a + cnt_b;
-  if (total > (uint32_t)kListPerLane * kWave) return false;
+  if (total > (uint32_t)kListPerLane * kWave || total > ecap || m > (uint32_t)kWave) return false;
   uint64_t key[kListPerLane];
   int64_t u[kListPerLane];
 #pragma unroll
@@ -690,31 +708,40 @@ __device__ __forceinline__ bool weighted_from_lists(const SampleArgs<IdxT>& a, i
     key[c] = j < total ? (j < cnt_a ? list_a[j] : list_b[j - cnt_a]) : 0ull;
     u[c] = j < total ? (int64_t)a.indices[row + (uint32_t)key[c]] : -1;
   }
-  uint32_t n_s = 0;  // same value in every lane
+  uint32_t n_u = 0, n_c = 0;  // same values in every lane
 #pragma unroll
   for (int c = 0; c < kListPerLane; ++c) {
     if ((uint32_t)c * kWave < total) {
       const uint32_t j = (uint32_t)c * kWave + lane;
       const bool cached = j < total && is_cached(a, u[c]);
-      const bool keep = j < cnt_a || cached;
-      const uint64_t mask = __ballot(keep);
-      if (keep) {
-        const uint32_t idx = n_s + lanes_below(mask);
-        if (idx < ecap) E[idx] = key[c] | (cached ? kCachedMark : 0ull);
-      }
-      n_s += (uint32_t)__popcll(mask);
+      const bool plain = j < cnt_a && !cached;
+      const uint64_t mask_c = __ballot(cached), mask_u = __ballot(plain);
+      if (cached) E[ecap - 1u - (n_c + lanes_below(mask_c))] = key[c];
+      if (plain) E[n_u + lanes_below(mask_u)] = key[c];
+      n_c += (uint32_t)__popcll(mask_c);
+      n_u += (uint32_t)__popcll(mask_u);
     }
   }
-  if (n_s > ecap || n_s > 8u * kWave) return false;
   wave_sync();
-  if (n_s <= kWave)
-    key_and_select<1>(a, E, n_s, m, emit);
-  else if (n_s <= 2 * kWave)
-    key_and_select<2>(a, E, n_s, m, emit);
-  else if (n_s <= 4 * kWave)
-    key_and_select<4>(a, E, n_s, m, emit);
-  else
-    key_and_select<8>(a, E, n_s, m, emit);
+  if (n_u > 4u * kWave || n_c > 4u * kWave) return false;
+  const uint32_t t_u = min(n_u, m), t_c = min(n_c, m);
+  smallest_to(E, n_u, m, T);
+  smallest_to(E + (ecap - n_c), n_c, m, T + m);
+  wave_sync();
+  if (t_u == 0 || t_c == 0) {
+    // one weight class: the m largest draws, in slot order
+    const uint64_t* best = t_u ? T : T + m;  // exactly m entries (the lists hold at least m slots)
+    for (uint32_t j = lane; j < m; j += kWave) {
+      const uint32_t s = (uint32_t)best[j];
+      uint32_t pos = 0;
+      for (uint32_t t = 0; t < m; ++t) pos += (uint32_t)best[t] < s ? 1u : 0u;
+      emit(pos, s);
+    }
+  } else if (t_u + t_c <= (uint32_t)kWave) {
+    key_and_select<1>(a, T, t_u, t_c, m, emit);
+  } else {
+    key_and_select<2>(a, T, t_u, t_c, m, emit);
+  }
   return true;
 }
 
@@ -826,7 +853,7 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
   const bool lists_ok = want_b && !a.force_radix && cnt >= m && cnt <= a.cap && cnt_b <= a.capb;
   if (kWeighted && lists_ok) {
     uint64_t* E = rest + 4 * (size_t)m;  // [2 xcap], the challenger buffers of the rescanning path
-    if (weighted_from_lists<IdxT>(a, row, cand, cnt, list_b, cnt_b, m, E, 2 * a.xcap, emit)) {
+    if (weighted_from_lists<IdxT>(a, row, cand, cnt, list_b, cnt_b, m, E, 2 * a.xcap, rest, emit)) {
       wave_sync();
       return;
     }
