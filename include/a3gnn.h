@@ -157,6 +157,56 @@ int a3_gather_input_features(a3_ctx* ctx, const void* feat_dev, const void* feat
  * per kind are remembered.  A3_ERR_INVALID_ARG without A3_PROFILE. */
 int a3_profile_read(a3_ctx* ctx, int kind, float* ms, int max, int* n);
 
+/* ---- Mini-batch pipelines on HIP streams (Sec. III-B, "Multi-Level Parallelism Scheduling") ----
+ * A pipeline owns n_workers contexts, each with a stream of its own, and keeps up to n_workers
+ * mini-batches in flight.  The three scheduling templates of the paper:
+ *   A3_PIPE_SEQUENTIAL  one worker; sampling and batch generation (feature retrieve) of a
+ *                       mini-batch run one after the other, nothing overlaps;
+ *   A3_PIPE_MODE1       every worker samples AND retrieves its mini-batch on its own stream, so
+ *                       whole mini-batches overlap (Eq. 2); needs an output buffer per worker (Eq. 3);
+ *   A3_PIPE_MODE2       workers sample concurrently, batch generation is serialised on one more
+ *                       stream in submission order (Eq. 4), which is where the paper finds the
+ *                       read/write contention.
+ * Mini-batches complete in submission order.  Results are those of a3_sample_blocks +
+ * a3_gather_input_features with the same arguments, bit for bit, in every mode.
+ * Not thread-safe.  Inputs must be complete on the device before a3_pipeline_submit (the
+ * pipeline's streams do not synchronise with any other stream); see a3_pipeline_stream. */
+#define A3_PIPE_SEQUENTIAL 0
+#define A3_PIPE_MODE1 1
+#define A3_PIPE_MODE2 2
+#define A3_PIPE_MAX_WORKERS 8
+
+typedef struct a3_pipeline a3_pipeline;
+
+/* n_workers in [1, A3_PIPE_MAX_WORKERS] (A3_PIPE_SEQUENTIAL uses one whatever is asked); the other
+ * arguments as a3_create, applied to every worker.  Errors as a3_create; text: a3_pipeline_last_error(NULL). */
+int a3_pipeline_create(a3_pipeline** out, int hip_device, int mode, int n_workers, int64_t max_seeds,
+                       int32_t max_hops, const int32_t* max_fanouts, uint32_t flags);
+int a3_pipeline_destroy(a3_pipeline* p);
+const char* a3_pipeline_last_error(const a3_pipeline* p);
+/* Workers actually created, and device bytes their arenas hold (relabel maps included); the
+ * caller's output buffers come on top (Eq. 3, Eq. 5). */
+int a3_pipeline_workers(const a3_pipeline* p);
+int64_t a3_pipeline_workspace_bytes(const a3_pipeline* p);
+/* hipStream_t of worker w (w == n_workers: the batch-generation stream of A3_PIPE_MODE2, NULL in
+ * the other modes), for callers that order other work against the pipeline with events. */
+void* a3_pipeline_stream(const a3_pipeline* p, int w);
+
+/* Queue one mini-batch: sampling + reindex (arguments as a3_sample_blocks_begin), then feature
+ * retrieve of its input nodes into out (arguments as a3_gather_input_features; row_bytes == 0
+ * skips the retrieve).  Returns at once.  A3_ERR_CAPACITY when n_workers mini-batches are already
+ * in flight (a3_pipeline_wait first).  `out` must not be in use by an earlier mini-batch that has
+ * not been waited for, nor by the caller's own work. */
+int a3_pipeline_submit(a3_pipeline* p, const int64_t* indptr, const void* indices, int32_t idx_bytes,
+                       int64_t num_nodes, const void* seeds, int64_t num_seeds,
+                       const int32_t* fanouts, int32_t num_hops, const int32_t* cache_map,
+                       uint32_t bias_q16, uint64_t rng_seed, const void* feat_dev,
+                       const void* feat_host, int64_t row_bytes, void* out, int64_t out_rows);
+/* Wait for the oldest mini-batch in flight: its blocks (valid until n_workers further submits) and
+ * its rows in `out` are complete on return.  Errors of that mini-batch as a3_sample_blocks_end;
+ * A3_ERR_INVALID_ARG when nothing is in flight. */
+int a3_pipeline_wait(a3_pipeline* p, a3_blocks* blocks);
+
 #ifdef __cplusplus
 }
 #endif

@@ -15,6 +15,8 @@ A3_MAX_FANOUT = 1024
 A3_OK, A3_ERR_INVALID_ARG, A3_ERR_CAPACITY, A3_ERR_HIP, A3_ERR_INPUT = 0, -1, -2, -3, -4
 A3_VALIDATE, A3_NO_EIDS, A3_HOST_ONLY, A3_FORCE_RADIX, A3_PROFILE = 1, 2, 4, 8, 16
 A3_PROFILE_DEPTH = 256
+A3_PIPE_SEQUENTIAL, A3_PIPE_MODE1, A3_PIPE_MODE2 = 0, 1, 2
+A3_PIPE_MAX_WORKERS = 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _lib = None
@@ -72,6 +74,24 @@ def lib():
         L.a3_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float), C.c_int,
                                       C.POINTER(C.c_int)]
         L.a3_profile_read.restype = C.c_int
+        L.a3_pipeline_create.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int, C.c_int64,
+                                         C.c_int32, C.POINTER(C.c_int32), C.c_uint32]
+        L.a3_pipeline_create.restype = C.c_int
+        L.a3_pipeline_destroy.argtypes = [C.c_void_p]
+        L.a3_pipeline_destroy.restype = C.c_int
+        L.a3_pipeline_last_error.argtypes = [C.c_void_p]
+        L.a3_pipeline_last_error.restype = C.c_char_p
+        L.a3_pipeline_workers.argtypes = [C.c_void_p]
+        L.a3_pipeline_workers.restype = C.c_int
+        L.a3_pipeline_workspace_bytes.argtypes = [C.c_void_p]
+        L.a3_pipeline_workspace_bytes.restype = C.c_int64
+        L.a3_pipeline_stream.argtypes = [C.c_void_p, C.c_int]
+        L.a3_pipeline_stream.restype = C.c_void_p
+        L.a3_pipeline_submit.argtypes = L.a3_sample_blocks_begin.argtypes + [
+            C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64]
+        L.a3_pipeline_submit.restype = C.c_int
+        L.a3_pipeline_wait.argtypes = [C.c_void_p, C.POINTER(_CBlocks)]
+        L.a3_pipeline_wait.restype = C.c_int
         _lib = L
     return _lib
 
@@ -275,3 +295,77 @@ class Context:
                                       _dptr(out))
         self._check(rc)
         return out
+
+
+class Pipeline:
+    """An a3_pipeline: n_workers mini-batches in flight on streams of their own, scheduled as the
+    paper's sequential / parallel mode 1 / parallel mode 2 templates.  submit() queues sampling and
+    feature retrieve of one mini-batch, wait() returns the oldest one's Blocks once both are done."""
+
+    def __init__(self, mode: int, n_workers: int, max_seeds: int, max_fanouts: Sequence[int],
+                 device: int = 0, flags: int = 0):
+        self._h = C.c_void_p()
+        self.device = torch.device("cuda", device) if not (flags & A3_HOST_ONLY) else torch.device("cpu")
+        fan = (C.c_int32 * len(max_fanouts))(*max_fanouts)
+        rc = lib().a3_pipeline_create(C.byref(self._h), device, mode, n_workers, max_seeds,
+                                      len(max_fanouts), fan, flags)
+        if rc != A3_OK:
+            raise A3Error(rc, (lib().a3_pipeline_last_error(None) or b"").decode())
+        self.mode = mode
+        self.n_workers = lib().a3_pipeline_workers(self._h)
+        self._begun = []
+
+    def close(self):
+        if self._h:
+            lib().a3_pipeline_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != A3_OK:
+            raise A3Error(rc, (lib().a3_pipeline_last_error(self._h) or b"").decode())
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(lib().a3_pipeline_workspace_bytes(self._h))
+
+    def stream(self, w: int) -> int:
+        return int(lib().a3_pipeline_stream(self._h, w) or 0)
+
+    def submit(self, indptr: torch.Tensor, indices: torch.Tensor, seeds: torch.Tensor,
+               fanouts: Sequence[int], cache_map: Optional[torch.Tensor], bias_q16: int,
+               rng_seed: int, feat_dev: Optional[torch.Tensor], feat_host: Optional[torch.Tensor],
+               out: Optional[torch.Tensor]) -> None:
+        """The tensors must be complete on the device (the pipeline's streams do not wait for
+        torch's); out = None queues sampling only."""
+        assert indptr.dtype == torch.int64 and indptr.is_contiguous()
+        assert indices.dtype in (torch.int32, torch.int64) and indices.is_contiguous()
+        assert seeds.dtype == indices.dtype and seeds.is_contiguous()
+        assert cache_map is None or (cache_map.dtype == torch.int32 and cache_map.is_contiguous())
+        row_bytes, out_rows = 0, 0
+        if out is not None:
+            ref = feat_dev if feat_dev is not None else feat_host
+            assert ref is not None and ref.dim() == 2
+            assert feat_host is None or feat_host.is_pinned(), "feat_host must be pinned host memory"
+            assert out.is_contiguous() and out.dim() == 2 and out.shape[1] == ref.shape[1] and out.dtype == ref.dtype
+            row_bytes, out_rows = ref.shape[1] * ref.element_size(), out.shape[0]
+        fan = (C.c_int32 * len(fanouts))(*fanouts)
+        rc = lib().a3_pipeline_submit(self._h, _dptr(indptr), _dptr(indices), indices.element_size(),
+                                      indptr.shape[0] - 1, _dptr(seeds), seeds.shape[0], fan,
+                                      len(fanouts), _dptr(cache_map), bias_q16, rng_seed,
+                                      _dptr(feat_dev), _dptr(feat_host), row_bytes, _dptr(out), out_rows)
+        self._check(rc)
+        self._begun.append((indices.dtype, indices.device))
+
+    def wait(self) -> Blocks:
+        cb = _CBlocks()
+        rc = lib().a3_pipeline_wait(self._h, C.byref(cb))
+        if self._begun and rc != A3_ERR_INVALID_ARG:
+            begun = self._begun.pop(0)
+        self._check(rc)
+        return Blocks(cb, *begun)

@@ -55,6 +55,7 @@ struct a3_ctx {
   int64_t last_bound_in = 0;        // launch bound on its number of input nodes
   int64_t last_num_nodes = 0;
   std::vector<void*> allocs;
+  int64_t alloc_bytes = 0;  // device bytes of the arena (the on-demand maps are counted separately)
   std::string err;
   // A3_PROFILE: rings of (start, stop) events per kind of call
   hipEvent_t prof_ev[2][A3_PROFILE_DEPTH][2] = {};
@@ -91,6 +92,7 @@ int dev_alloc(a3_ctx* ctx, T** p, int64_t count) {
   hipError_t e = hipMalloc(&q, bytes);
   if (e != hipSuccess) return hip_fail(ctx, e, "hipMalloc");
   ctx->allocs.push_back(q);
+  ctx->alloc_bytes += (int64_t)bytes;
   *p = (T*)q;
   return A3_OK;
 }
@@ -734,3 +736,188 @@ extern "C" int a3_profile_read(a3_ctx* ctx, int kind, float* ms, int max, int* n
   return A3_OK;
 }
 
+
+// ---------------------------------------------------------------------------
+// Pipelines: n workers (context + stream each), mini-batches in flight in a ring
+// ---------------------------------------------------------------------------
+struct a3_pipeline {
+  int device = 0;
+  int mode = A3_PIPE_SEQUENTIAL;
+  int n = 0;
+  a3_ctx* ctx[A3_PIPE_MAX_WORKERS] = {nullptr};
+  hipStream_t stream[A3_PIPE_MAX_WORKERS] = {nullptr};
+  hipStream_t batch_stream = nullptr;                      // A3_PIPE_MODE2 only
+  hipEvent_t gathered[A3_PIPE_MAX_WORKERS] = {nullptr};     // the worker's latest retrieve is done
+  bool has_gather[A3_PIPE_MAX_WORKERS] = {false};
+  int64_t submitted = 0, waited = 0;
+  std::string err;
+};
+
+namespace {
+thread_local std::string g_pipe_err;
+
+int pfail(a3_pipeline* p, int code, const std::string& msg) {
+  if (p)
+    p->err = msg;
+  else
+    g_pipe_err = msg;
+  return code;
+}
+
+void pipeline_free(a3_pipeline* p) {
+  for (int w = 0; w < A3_PIPE_MAX_WORKERS; ++w) {
+    if (p->ctx[w]) (void)a3_destroy(p->ctx[w]);
+    if (p->gathered[w]) (void)hipEventDestroy(p->gathered[w]);
+  }
+  if (p->batch_stream) {
+    (void)hipStreamSynchronize(p->batch_stream);
+    (void)hipStreamDestroy(p->batch_stream);
+  }
+  for (int w = 0; w < A3_PIPE_MAX_WORKERS; ++w)
+    if (p->stream[w]) (void)hipStreamDestroy(p->stream[w]);
+  delete p;
+}
+}  // namespace
+
+extern "C" const char* a3_pipeline_last_error(const a3_pipeline* p) {
+  return p ? p->err.c_str() : g_pipe_err.c_str();
+}
+
+extern "C" int a3_pipeline_create(a3_pipeline** out, int hip_device, int mode, int n_workers,
+                                  int64_t max_seeds, int32_t max_hops, const int32_t* max_fanouts,
+                                  uint32_t flags) {
+  if (!out) return pfail(nullptr, A3_ERR_INVALID_ARG, "a3_pipeline_create: out is null");
+  *out = nullptr;
+  if (mode != A3_PIPE_SEQUENTIAL && mode != A3_PIPE_MODE1 && mode != A3_PIPE_MODE2)
+    return pfail(nullptr, A3_ERR_INVALID_ARG, "a3_pipeline_create: unknown mode");
+  if (n_workers < 1 || n_workers > A3_PIPE_MAX_WORKERS)
+    return pfail(nullptr, A3_ERR_INVALID_ARG, "a3_pipeline_create: n_workers must be in [1, A3_PIPE_MAX_WORKERS]");
+  a3_pipeline* p = new (std::nothrow) a3_pipeline();
+  if (!p) return pfail(nullptr, A3_ERR_HIP, "a3_pipeline_create: out of host memory");
+  p->device = hip_device;
+  p->mode = mode;
+  p->n = mode == A3_PIPE_SEQUENTIAL ? 1 : n_workers;
+  const bool host_only = (flags & A3_HOST_ONLY) != 0;
+  int rc = A3_OK;
+  if (!host_only) {
+    hipError_t e = hipSetDevice(hip_device);
+    if (e != hipSuccess) rc = pfail(nullptr, A3_ERR_HIP, std::string("a3_pipeline_create: hipSetDevice: ") + hipGetErrorString(e));
+  }
+  for (int w = 0; w < p->n && rc == A3_OK; ++w) {
+    if (!host_only) {
+      // streams of the default priority that do not synchronise with the null stream
+      hipError_t e = hipStreamCreateWithFlags(&p->stream[w], hipStreamNonBlocking);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&p->gathered[w], hipEventDisableTiming);
+      if (e != hipSuccess) {
+        rc = pfail(nullptr, A3_ERR_HIP, std::string("a3_pipeline_create: stream or event: ") + hipGetErrorString(e));
+        break;
+      }
+    }
+    rc = a3_create(&p->ctx[w], hip_device, p->stream[w], max_seeds, max_hops, max_fanouts, flags);
+    if (rc != A3_OK) pfail(nullptr, rc, std::string("a3_pipeline_create: ") + a3_last_error(nullptr));
+  }
+  if (rc == A3_OK && mode == A3_PIPE_MODE2 && !host_only) {
+    hipError_t e = hipStreamCreateWithFlags(&p->batch_stream, hipStreamNonBlocking);
+    if (e != hipSuccess) rc = pfail(nullptr, A3_ERR_HIP, std::string("a3_pipeline_create: stream: ") + hipGetErrorString(e));
+  }
+  if (rc != A3_OK) {
+    pipeline_free(p);
+    return rc;
+  }
+  *out = p;
+  return A3_OK;
+}
+
+extern "C" int a3_pipeline_destroy(a3_pipeline* p) {
+  if (!p) return A3_OK;
+  if (p->n > 0 && p->ctx[0] && !(p->ctx[0]->flags & A3_HOST_ONLY)) (void)hipSetDevice(p->device);
+  pipeline_free(p);
+  return A3_OK;
+}
+
+extern "C" int a3_pipeline_workers(const a3_pipeline* p) { return p ? p->n : 0; }
+
+extern "C" int64_t a3_pipeline_workspace_bytes(const a3_pipeline* p) {
+  if (!p) return 0;
+  int64_t bytes = 0;
+  for (int w = 0; w < p->n; ++w) {
+    const a3_ctx* c = p->ctx[w];
+    bytes += c->alloc_bytes + c->node_map_cap * (int64_t)sizeof(int32_t) +
+             c->cached_bits_words * (int64_t)sizeof(uint64_t);
+  }
+  return bytes;
+}
+
+extern "C" void* a3_pipeline_stream(const a3_pipeline* p, int w) {
+  if (!p || w < 0 || w > p->n) return nullptr;
+  return w == p->n ? (void*)p->batch_stream : (void*)p->stream[w];
+}
+
+extern "C" int a3_pipeline_submit(a3_pipeline* p, const int64_t* indptr, const void* indices,
+                                  int32_t idx_bytes, int64_t num_nodes, const void* seeds,
+                                  int64_t num_seeds, const int32_t* fanouts, int32_t num_hops,
+                                  const int32_t* cache_map, uint32_t bias_q16, uint64_t rng_seed,
+                                  const void* feat_dev, const void* feat_host, int64_t row_bytes,
+                                  void* out, int64_t out_rows) {
+  if (!p) return pfail(nullptr, A3_ERR_INVALID_ARG, "a3_pipeline_submit: pipeline is null");
+  if (p->submitted - p->waited >= p->n)
+    return pfail(p, A3_ERR_CAPACITY, "a3_pipeline_submit: every worker has a mini-batch in flight; wait first");
+  if (row_bytes < 0) return pfail(p, A3_ERR_INVALID_ARG, "a3_pipeline_submit: row_bytes < 0");
+  const int w = (int)(p->submitted % p->n);
+  a3_ctx* c = p->ctx[w];
+  if (row_bytes > 0) {  // refuse a bad retrieve before anything is queued
+    if (out_rows < 0 || (out_rows > 0 && !out))
+      return pfail(p, A3_ERR_INVALID_ARG, "a3_pipeline_submit: bad output buffer");
+    const int rc = check_gather_args(c, feat_dev, feat_host, cache_map, row_bytes);
+    if (rc != A3_OK) return pfail(p, rc, c->err);
+  }
+  int rc = a3_sample_blocks_begin(c, indptr, indices, idx_bytes, num_nodes, seeds, num_seeds, fanouts,
+                                  num_hops, cache_map, bias_q16, rng_seed);
+  if (rc != A3_OK) return pfail(p, rc, c->err);
+  p->has_gather[w] = false;
+  if (row_bytes > 0 && out_rows > 0 && num_seeds > 0) {
+    hipStream_t own = c->stream;
+    if (p->mode == A3_PIPE_MODE2) {
+      // batch generation is serialised: one stream takes the retrieves in submission order,
+      // each after its own mini-batch's sampling
+      hipError_t e = hipStreamWaitEvent(p->batch_stream, c->sampled, 0);
+      if (e != hipSuccess) return pfail(p, A3_ERR_HIP, std::string("a3_pipeline_submit: hipStreamWaitEvent: ") + hipGetErrorString(e));
+      c->stream = p->batch_stream;
+    }
+    rc = a3_gather_input_features(c, feat_dev, feat_host, cache_map, row_bytes, out, out_rows);
+    hipStream_t used = c->stream;
+    c->stream = own;
+    if (rc != A3_OK) {
+      // the sampling part is queued: it stays in flight and is reported by a3_pipeline_wait
+      p->submitted++;
+      return pfail(p, rc, c->err);
+    }
+    hipError_t e = hipEventRecord(p->gathered[w], used);
+    if (e != hipSuccess) {
+      p->submitted++;
+      return pfail(p, A3_ERR_HIP, std::string("a3_pipeline_submit: hipEventRecord: ") + hipGetErrorString(e));
+    }
+    p->has_gather[w] = true;
+  }
+  p->submitted++;
+  return A3_OK;
+}
+
+extern "C" int a3_pipeline_wait(a3_pipeline* p, a3_blocks* blocks) {
+  if (!p) return pfail(nullptr, A3_ERR_INVALID_ARG, "a3_pipeline_wait: pipeline is null");
+  if (!blocks) return pfail(p, A3_ERR_INVALID_ARG, "a3_pipeline_wait: blocks is null");
+  if (p->submitted == p->waited)
+    return pfail(p, A3_ERR_INVALID_ARG, "a3_pipeline_wait: no mini-batch is in flight");
+  const int w = (int)(p->waited % p->n);
+  a3_ctx* c = p->ctx[w];
+  p->waited++;
+  int rc = a3_sample_blocks_end(c, blocks);
+  if (rc != A3_OK) pfail(p, rc, c->err);
+  if (p->has_gather[w]) {
+    hipError_t e = hipEventSynchronize(p->gathered[w]);
+    p->has_gather[w] = false;
+    if (e != hipSuccess && rc == A3_OK)
+      rc = pfail(p, A3_ERR_HIP, std::string("a3_pipeline_wait: hipEventSynchronize: ") + hipGetErrorString(e));
+  }
+  return rc;
+}

@@ -110,3 +110,44 @@ def test_python_wrapper_raises_with_message():
         ctx.sample_blocks(indptr, idx, idx[:2], [9, 2])
     assert ei.value.code == a3.A3_ERR_CAPACITY
     ctx.close()
+
+
+def test_pipeline_argument_errors(L):
+    fan = (C.c_int32 * 2)(3, 2)
+    h = C.c_void_p()
+    assert L.a3_pipeline_create(None, 0, 1, 2, 8, 2, fan, a3.A3_HOST_ONLY) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_pipeline_create(C.byref(h), 0, 3, 2, 8, 2, fan, a3.A3_HOST_ONLY) == a3.A3_ERR_INVALID_ARG
+    assert b"mode" in L.a3_pipeline_last_error(None)
+    assert L.a3_pipeline_create(C.byref(h), 0, 1, 0, 8, 2, fan, a3.A3_HOST_ONLY) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_pipeline_create(C.byref(h), 0, 1, a3.A3_PIPE_MAX_WORKERS + 1, 8, 2, fan,
+                                a3.A3_HOST_ONLY) == a3.A3_ERR_INVALID_ARG
+    # the workers' own limits are checked as in a3_create
+    assert L.a3_pipeline_create(C.byref(h), 0, 1, 2, -1, 2, fan, a3.A3_HOST_ONLY) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_pipeline_create(C.byref(h), 0, a3.A3_PIPE_SEQUENTIAL, 4, 8, 2, fan,
+                                a3.A3_HOST_ONLY) == a3.A3_OK
+    assert L.a3_pipeline_workers(h) == 1  # the sequential template has one worker
+    assert L.a3_pipeline_destroy(h) == a3.A3_OK
+    assert L.a3_pipeline_create(C.byref(h), 0, a3.A3_PIPE_MODE2, 3, 8, 2, fan, a3.A3_HOST_ONLY) == a3.A3_OK
+    assert L.a3_pipeline_workers(h) == 3
+    assert L.a3_pipeline_stream(h, 7) is None
+    blocks = a3.binding._CBlocks()
+    assert L.a3_pipeline_wait(h, C.byref(blocks)) == a3.A3_ERR_INVALID_ARG  # nothing in flight
+    dummy = C.create_string_buffer(64)
+    p = C.cast(dummy, C.c_void_p)
+
+    def submit(indptr=p, ns=4, bias=65536, row_bytes=0, out=None, out_rows=0, feat=None):
+        return L.a3_pipeline_submit(h, indptr, p, 4, 10, p, ns, fan, 2, None, bias, 0, feat, None,
+                                    row_bytes, out, out_rows)
+
+    assert submit(indptr=None) == a3.A3_ERR_INVALID_ARG
+    assert submit(bias=1) == a3.A3_ERR_INVALID_ARG
+    assert submit(ns=9) == a3.A3_ERR_CAPACITY
+    assert submit(row_bytes=-2) == a3.A3_ERR_INVALID_ARG
+    assert submit(row_bytes=3, out=p, out_rows=1, feat=p) == a3.A3_ERR_INVALID_ARG  # odd row
+    assert submit(row_bytes=8, out=None, out_rows=4, feat=p) == a3.A3_ERR_INVALID_ARG
+    assert submit(row_bytes=8, out=p, out_rows=4, feat=None) == a3.A3_ERR_INVALID_ARG  # no store
+    assert submit() == a3.A3_ERR_HIP  # valid arguments, but no device behind the pipeline
+    assert b"without a device" in L.a3_pipeline_last_error(h)
+    assert L.a3_pipeline_wait(h, C.byref(blocks)) == a3.A3_ERR_INVALID_ARG  # still nothing in flight
+    assert L.a3_pipeline_destroy(h) == a3.A3_OK
+    assert L.a3_pipeline_destroy(None) == a3.A3_OK

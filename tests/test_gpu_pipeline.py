@@ -1,0 +1,102 @@
+"""GPU parity of the stream pipelines (sequential, parallel mode 1, parallel mode 2): every
+mini-batch that comes out of a pipeline equals the oracle's, blocks and gathered rows, whatever
+the mode and the number of workers in flight."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2511_07421_amd as a3
+from helpers import blocks_equal
+from workloads import get_config, make_graph, make_features, degree_ranked_cache, seed_batch
+
+pytestmark = pytest.mark.gpu
+Q = 65536
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def setup():
+    w = get_config("mini_copurchase")
+    g = make_graph(w.num_nodes, w.mean_degree, w.d_min, w.d_max, w.a, w.symmetric, w.graph_seed,
+                   w.idx_dtype)
+    full = make_features(w.num_nodes, 24, torch.float32)
+    split = degree_ranked_cache(g, full, 0.3, pin_host=True)
+    n_batches = 7
+    seeds = [seed_batch(w.num_nodes, 200 - 13 * b, 0, b, dtype=np.int32) for b in range(n_batches)]
+    gamma_q = 4 * Q
+    want = []
+    for b in range(n_batches):
+        blk = oracle.sample_blocks(g.indptr.numpy(), g.indices.numpy(), seeds[b], w.fanouts,
+                                   split.cache_map.numpy(), gamma_q, 100 + b)
+        rows = oracle.gather_features(split.feat_dev.numpy(), split.feat_host.numpy(),
+                                      split.cache_map.numpy(), blk.input_nodes)
+        want.append((blk, rows))
+    dev = dict(indptr=g.indptr.to(DEV), indices=g.indices.to(DEV), cache_map=split.cache_map.to(DEV),
+               feat_dev=split.feat_dev.to(DEV), feat_host=split.feat_host,
+               seeds=[torch.from_numpy(s).to(DEV) for s in seeds])
+    torch.cuda.synchronize()
+    return w, dev, want, gamma_q
+
+
+@pytest.mark.parametrize("mode,n_workers", [(a3.A3_PIPE_SEQUENTIAL, 1), (a3.A3_PIPE_MODE1, 2),
+                                            (a3.A3_PIPE_MODE1, 3), (a3.A3_PIPE_MODE2, 2),
+                                            (a3.A3_PIPE_MODE2, 4)])
+def test_pipeline_batches_match_oracle(setup, mode, n_workers):
+    w, d, want, gamma_q = setup
+    print(f"[case] pipeline mode={mode} workers={n_workers}", flush=True)
+    pipe = a3.Pipeline(mode, n_workers, 256, w.fanouts)
+    n = pipe.n_workers
+    assert pipe.workspace_bytes > 0
+    cap_rows = 256
+    for f in w.fanouts:
+        cap_rows *= 1 + f
+    cap_rows = min(cap_rows, w.num_nodes)
+    outs = [torch.zeros((cap_rows, 24), dtype=torch.float32, device=DEV) for _ in range(n)]
+    torch.cuda.synchronize()
+
+    def submit(b):
+        pipe.submit(d["indptr"], d["indices"], d["seeds"][b], w.fanouts, d["cache_map"], gamma_q,
+                    100 + b, d["feat_dev"], d["feat_host"], outs[b % n])
+
+    def check(b):
+        blk = pipe.wait()
+        blocks_equal(blk.to_host(), want[b][0])
+        rows = outs[b % n][: blk.n_src[-1]].cpu().numpy()
+        assert rows.tobytes() == want[b][1].tobytes(), f"gathered rows of mini-batch {b}"
+
+    nb = len(want)
+    for b in range(min(n, nb)):
+        submit(b)
+    with pytest.raises(a3.A3Error) as ei:  # one more than the workers can hold
+        submit(0)
+    assert ei.value.code == a3.A3_ERR_CAPACITY
+    for b in range(nb):
+        check(b)
+        if b + n < nb:
+            submit(b + n)
+    with pytest.raises(a3.A3Error) as ei:
+        pipe.wait()
+    assert ei.value.code == a3.A3_ERR_INVALID_ARG
+    pipe.close()
+
+
+def test_pipeline_sampling_only_and_error_batch(setup):
+    w, d, want, gamma_q = setup
+    pipe = a3.Pipeline(a3.A3_PIPE_MODE1, 2, 256, w.fanouts, flags=a3.A3_VALIDATE)
+    bad = torch.tensor([3, 3], dtype=torch.int32, device=DEV)
+    torch.cuda.synchronize()
+    pipe.submit(d["indptr"], d["indices"], d["seeds"][0], w.fanouts, d["cache_map"], gamma_q, 100,
+                None, None, None)
+    pipe.submit(d["indptr"], d["indices"], bad, w.fanouts, d["cache_map"], gamma_q, 0, None, None, None)
+    blocks_equal(pipe.wait().to_host(), want[0][0])
+    with pytest.raises(a3.A3Error) as ei:  # the repeated seed is reported by that batch's wait
+        pipe.wait()
+    assert ei.value.code == a3.A3_ERR_INPUT
+    pipe.submit(d["indptr"], d["indices"], d["seeds"][1], w.fanouts, d["cache_map"], gamma_q, 101,
+                None, None, None)
+    pipe.submit(d["indptr"], d["indices"], d["seeds"][2], w.fanouts, d["cache_map"], gamma_q, 102,
+                None, None, None)  # the worker that reported the error works again
+    blocks_equal(pipe.wait().to_host(), want[1][0])
+    blocks_equal(pipe.wait().to_host(), want[2][0])
+    pipe.close()
