@@ -38,6 +38,8 @@ def parse():
     p.add_argument("--batch", type=int, default=None)
     p.add_argument("--cpu-seconds", type=float, default=20.0,
                    help="budget of the oracle (CPU baseline) leg; 0 disables it")
+    p.add_argument("--no-pipelines", action="store_true",
+                   help="skip the extra leg that runs the same steps through the stream pipelines")
     p.add_argument("--traffic-bytes", type=float, default=None,
                    help="measured HBM bytes per gather launch (from rocprofv3 --pmc), if known")
     p.add_argument("--pmc-calibration", action="store_true",
@@ -218,6 +220,46 @@ def main():
                      "algorithmic_bytes_per_launch": algo_bytes_per_launch,
                      "avg_launch_seconds": gather_avg_s},
     }
+
+    if not args.no_pipelines:
+        # the same K mini-batches through the scheduling templates of Sec. III-B: n mini-batches in
+        # flight on streams of their own (mode 1: whole mini-batches overlap; mode 2: sampling
+        # overlaps, the feature retrieve is serialised).  `value` above stays the sequential figure.
+        ctx.close()
+        pipes = []
+        names = {a3.A3_PIPE_SEQUENTIAL: "sequential", a3.A3_PIPE_MODE1: "mode1", a3.A3_PIPE_MODE2: "mode2"}
+        for mode, n_w in [(a3.A3_PIPE_SEQUENTIAL, 1), (a3.A3_PIPE_MODE1, 2), (a3.A3_PIPE_MODE1, 3),
+                          (a3.A3_PIPE_MODE2, 2), (a3.A3_PIPE_MODE2, 3)]:
+            pipe = a3.Pipeline(mode, n_w, batch, w.fanouts)
+            outs = [out] + [torch.empty_like(out) for _ in range(n_w - 1)]
+            torch.cuda.synchronize()
+            # n_w + W warm-up mini-batches, then the K timed ones of the main leg
+            order = [i % (W + K) for i in range(n_w + W)] + list(range(W, W + K))
+            first_timed = n_w + W
+            p_edges = 0
+            t_start = 0.0
+            for j in range(len(order) + n_w):
+                if j == first_timed:  # everything before is complete; the timed ones start here
+                    torch.cuda.synchronize()
+                    t_start = time.perf_counter()
+                if j >= n_w:
+                    blk = pipe.wait()
+                    if j - n_w >= first_timed:
+                        p_edges += sum(blk.n_edges)
+                if j < len(order):
+                    b = order[j]
+                    pipe.submit(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b,
+                                split.feat_dev, split.feat_host, outs[j % n_w])
+            torch.cuda.synchronize()
+            p_s = time.perf_counter() - t_start
+            assert p_edges == n_edges  # the same mini-batches, the same edges
+            pipes.append({"mode": names[mode], "workers": n_w, "ms_per_step": p_s * 1e3 / K,
+                          "edges_per_s": p_edges / p_s,
+                          "workspace_bytes": pipe.workspace_bytes,
+                          "output_bytes": sum(o.numel() * o.element_size() for o in outs)})
+            pipe.close()
+            del outs
+        result["pipelines"] = pipes
 
     if args.cpu_seconds > 0:
         import oracle
