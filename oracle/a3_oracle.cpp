@@ -7,7 +7,9 @@
 #include <algorithm>
 #include <chrono>
 #include <cstdlib>
+#include <cmath>
 #include <cstring>
+#include <limits>
 #include <unordered_map>
 #include <vector>
 
@@ -255,6 +257,45 @@ extern "C" int oracle_gather_features(const void* feat_dev, const void* feat_hos
       src = (const char*)feat_host + (-c - 1) * row_bytes;
     }
     std::memcpy((char*)out + i * row_bytes, src, (size_t)row_bytes);
+  }
+  return 0;
+}
+
+// IEEE 754 binary16 -> double, written out from the format: 1 sign, 5 exponent (bias 15), 10
+// fraction bits; exponent 0 is zero/subnormal (fraction * 2^-24), exponent 31 is inf/nan.
+static double half_to_double(uint16_t h) {
+  const int sign = (h >> 15) & 1;
+  const int expo = (h >> 10) & 0x1F;
+  const int frac = h & 0x3FF;
+  double v;
+  if (expo == 0)
+    v = std::ldexp((double)frac, -24);
+  else if (expo == 31)
+    v = frac ? std::numeric_limits<double>::quiet_NaN() : std::numeric_limits<double>::infinity();
+  else
+    v = std::ldexp((double)(frac | 0x400), expo - 25);
+  return sign ? -v : v;
+}
+
+extern "C" int oracle_block_mean(const int32_t* blk_indptr, const int32_t* blk_indices,
+                                 int64_t n_dst, int64_t n_src, const void* x, int32_t x_dtype,
+                                 int64_t dim, double* out) {
+  if (n_dst < 0 || n_src < 0 || dim <= 0) return -1;
+  if (x_dtype != 0 && x_dtype != 1) return -1;
+  if (n_dst > 0 && (!blk_indptr || !out)) return -1;
+  for (int64_t i = 0; i < n_dst; ++i) {
+    const int64_t e0 = blk_indptr[i], e1 = blk_indptr[i + 1];
+    if (e1 < e0) return -1;
+    for (int64_t c = 0; c < dim; ++c) {
+      double sum = 0.0;
+      for (int64_t e = e0; e < e1; ++e) {
+        const int64_t j = blk_indices[e];
+        if (j < 0 || j >= n_src || !x) return -1;
+        sum += x_dtype == 0 ? (double)((const float*)x)[j * dim + c]
+                            : half_to_double(((const uint16_t*)x)[j * dim + c]);
+      }
+      out[i * dim + c] = e1 > e0 ? sum / (double)(e1 - e0) : 0.0;
+    }
   }
   return 0;
 }

@@ -28,8 +28,9 @@
  * arithmetic; selection against Alg. 1 transcribed as a stream, against the
  * top-m of exact real keys u^(1/w), against the A-Res inclusion law by
  * chi-square and brute-force enumeration; relabel against brute force on
- * tiny graphs; gather against a library index_select.  No function here is
- * "parity unpinned".
+ * tiny graphs; gather against a library index_select; the block mean against
+ * a dense normalised-adjacency product by a library matmul and closed forms.
+ * No function here is "parity unpinned".
  */
 #ifndef A3_ORACLE_H
 #define A3_ORACLE_H
@@ -106,6 +107,16 @@ void oracle_free_blocks(oracle_blocks* b);
 int oracle_gather_features(const void* feat_dev, const void* feat_host, const int32_t* cache_map,
                            const void* ids, int32_t idx_bytes, int64_t n_ids, int64_t row_bytes,
                            void* out);
+
+/* Neighbour aggregation of one block (Alg. 0 "forward" with the GraphSAGE
+ * mean aggregator the evaluation uses, Sec. IV-A): for every destination i,
+ *   out[i][c] = (1 / d_i) * sum over e in [blk_indptr[i], blk_indptr[i+1]) of x[blk_indices[e]][c],
+ * d_i the number of sampled edges of i; a destination without edges gets zeros.
+ * x is [n_src][dim], float32 (x_dtype = 0) or IEEE binary16 (x_dtype = 1); the
+ * sum and the division are done in double and stored as double, [n_dst][dim].
+ * Returns 0, or -1 on a bad argument (an index outside [0, n_src) included). */
+int oracle_block_mean(const int32_t* blk_indptr, const int32_t* blk_indices, int64_t n_dst,
+                      int64_t n_src, const void* x, int32_t x_dtype, int64_t dim, double* out);
 
 #ifdef __cplusplus
 }

@@ -51,6 +51,9 @@ def lib():
         L.oracle_sample_blocks.restype = C.c_int
         L.oracle_free_blocks.argtypes = [C.POINTER(_Blocks)]
         L.oracle_free_blocks.restype = None
+        L.oracle_block_mean.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p,
+                                        C.c_int32, C.c_int64, C.c_void_p]
+        L.oracle_block_mean.restype = C.c_int
         L.oracle_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                              C.c_int32, C.c_int64, C.c_int64, C.c_void_p]
         L.oracle_gather_features.restype = C.c_int
@@ -155,4 +158,19 @@ def gather_features(feat_dev, feat_host, cache_map, ids):
                                       ids.shape[0], row_bytes, _ptr(out))
     if rc != 0:
         raise ValueError("oracle_gather_features: bad argument")
+    return out
+
+
+def block_mean(blk_indptr, blk_indices, x):
+    """mean of the source rows of every destination of one block, in double: [n_dst, dim]"""
+    ip = np.ascontiguousarray(blk_indptr, dtype=np.int32)
+    ix = np.ascontiguousarray(blk_indices, dtype=np.int32)
+    x = np.ascontiguousarray(x)
+    assert x.ndim == 2 and x.dtype in (np.float32, np.float16)
+    n_dst = ip.shape[0] - 1
+    out = np.zeros((n_dst, x.shape[1]), dtype=np.float64)
+    rc = lib().oracle_block_mean(_ptr(ip), _ptr(ix), n_dst, x.shape[0], _ptr(x),
+                                 0 if x.dtype == np.float32 else 1, x.shape[1], _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle_block_mean: bad argument")
     return out
