@@ -149,9 +149,31 @@ int a3_gather_input_features(a3_ctx* ctx, const void* feat_dev, const void* feat
                              const int32_t* cache_map, int64_t row_bytes, void* out,
                              int64_t out_rows);
 
+/* Neighbour aggregation of one block, the step that consumes the path's output (Alg. 0 "forward";
+ * the evaluation's GraphSAGE aggregates with the mean, Sec. IV-A):
+ *   out[i,:] = mean over e in [blk_indptr[i], blk_indptr[i+1]) of x[blk_indices[e],:],  i < n_dst;
+ * a destination without sampled edges gets zeros.
+ *   blk_indptr   device int32 [n_dst + 1], blk_indices device int32 [blk_indptr[n_dst]], values in
+ *                [0, n_src) (others are skipped, never dereferenced): one hop of a3_blocks.
+ *                blk_indices may be NULL when the block has no edges.
+ *   x            device [n_src, dim], row-major, float32 (A3_F32) or IEEE binary16 (A3_F16);
+ *                for the outermost hop these are the rows a3_gather_input_features wrote.
+ *   out          device [n_dst, dim], same type as x, caller-allocated.
+ * Sums are taken in fp32 in edge order, then divided by the edge count and rounded once to the
+ * output type.  Asynchronous on the context's stream.  Errors: A3_ERR_INVALID_ARG, A3_ERR_HIP. */
+#define A3_F32 0
+#define A3_F16 1
+int a3_block_mean(a3_ctx* ctx, const int32_t* blk_indptr, const int32_t* blk_indices, int64_t n_dst,
+                  int64_t n_src, const void* x, int32_t x_dtype, int64_t dim, void* out);
+/* The same for block `hop` of the context's most recent a3_sample_blocks(_begin), with the counts
+ * taken on the device: may be queued right after a3_sample_blocks_begin (and after the gather
+ * that fills x).  min(n_dst[hop], out_rows) rows are written. */
+int a3_block_mean_of_hop(a3_ctx* ctx, int32_t hop, const void* x, int32_t x_dtype, int64_t dim,
+                         void* out, int64_t out_rows);
+
 /* Measurement aid (Sec. IV-A reports averages over runs; this gives per-call device times).
- * With A3_PROFILE every a3_sample_blocks (kind 0) and a3_gather_features (kind 1) brackets its
- * kernels with HIP events on the context's stream.  a3_profile_read waits for the newest event
+ * With A3_PROFILE every a3_sample_blocks (kind 0), a3_gather_features (kind 1) and a3_block_mean
+ * (kind 2) brackets its kernels with HIP events on the context's stream.  a3_profile_read waits for the newest event
  * and returns the device durations in milliseconds of the calls made since the previous read of
  * that kind, oldest first: ms (host) receives min(*n, max) values; at most A3_PROFILE_DEPTH calls
  * per kind are remembered.  A3_ERR_INVALID_ARG without A3_PROFILE. */

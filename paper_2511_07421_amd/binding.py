@@ -17,6 +17,7 @@ A3_VALIDATE, A3_NO_EIDS, A3_HOST_ONLY, A3_FORCE_RADIX, A3_PROFILE = 1, 2, 4, 8, 
 A3_PROFILE_DEPTH = 256
 A3_PIPE_SEQUENTIAL, A3_PIPE_MODE1, A3_PIPE_MODE2 = 0, 1, 2
 A3_PIPE_MAX_WORKERS = 8
+A3_F32, A3_F16 = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _lib = None
@@ -74,6 +75,12 @@ def lib():
         L.a3_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float), C.c_int,
                                       C.POINTER(C.c_int)]
         L.a3_profile_read.restype = C.c_int
+        L.a3_block_mean.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p,
+                                    C.c_int32, C.c_int64, C.c_void_p]
+        L.a3_block_mean.restype = C.c_int
+        L.a3_block_mean_of_hop.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int64,
+                                           C.c_void_p, C.c_int64]
+        L.a3_block_mean_of_hop.restype = C.c_int
         L.a3_pipeline_create.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int, C.c_int64,
                                          C.c_int32, C.POINTER(C.c_int32), C.c_uint32]
         L.a3_pipeline_create.restype = C.c_int
@@ -293,6 +300,36 @@ class Context:
         rc = lib().a3_gather_features(self._h, _dptr(feat_dev), _dptr(feat_host), _dptr(cache_map),
                                       _dptr(ids), ids.element_size(), ids.shape[0], row_bytes,
                                       _dptr(out))
+        self._check(rc)
+        return out
+
+    @staticmethod
+    def _dtype_code(t: torch.Tensor) -> int:
+        assert t.dtype in (torch.float32, torch.float16), "features must be float32 or float16"
+        return A3_F32 if t.dtype == torch.float32 else A3_F16
+
+    def block_mean(self, blk_indptr: torch.Tensor, blk_indices: torch.Tensor, x: torch.Tensor,
+                   out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """mean of the source rows x[blk_indices[e]] of every destination of one block"""
+        assert blk_indptr.dtype == torch.int32 and blk_indptr.is_contiguous()
+        assert blk_indices.dtype == torch.int32 and blk_indices.is_contiguous()
+        assert x.dim() == 2 and x.is_contiguous()
+        n_dst = blk_indptr.shape[0] - 1
+        if out is None:
+            out = torch.empty((n_dst, x.shape[1]), dtype=x.dtype, device=x.device)
+        assert out.is_contiguous() and out.shape == (n_dst, x.shape[1]) and out.dtype == x.dtype
+        rc = lib().a3_block_mean(self._h, _dptr(blk_indptr), _dptr(blk_indices), n_dst, x.shape[0],
+                                 _dptr(x), self._dtype_code(x), x.shape[1], _dptr(out))
+        self._check(rc)
+        return out
+
+    def block_mean_of_hop(self, hop: int, x: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
+        """the same for block `hop` of the last sampled mini-batch, counts taken on the device;
+        may be queued before sample_blocks_end; writes out[:n_dst[hop]]"""
+        assert x.dim() == 2 and x.is_contiguous()
+        assert out.is_contiguous() and out.dim() == 2 and out.shape[1] == x.shape[1] and out.dtype == x.dtype
+        rc = lib().a3_block_mean_of_hop(self._h, hop, _dptr(x), self._dtype_code(x), x.shape[1],
+                                        _dptr(out), out.shape[0])
         self._check(rc)
         return out
 

@@ -53,14 +53,15 @@ struct a3_ctx {
   int32_t last_hops = 0;            // shape of the most recent begun call
   int32_t last_idx_bytes = 0;
   int64_t last_bound_in = 0;        // launch bound on its number of input nodes
+  int64_t last_bound_dst[A3_MAX_HOPS] = {0};  // launch bounds on its destinations per hop
   int64_t last_num_nodes = 0;
   std::vector<void*> allocs;
   int64_t alloc_bytes = 0;  // device bytes of the arena (the on-demand maps are counted separately)
   std::string err;
   // A3_PROFILE: rings of (start, stop) events per kind of call
-  hipEvent_t prof_ev[2][A3_PROFILE_DEPTH][2] = {};
-  int64_t prof_written[2] = {0, 0};
-  int64_t prof_read[2] = {0, 0};
+  hipEvent_t prof_ev[3][A3_PROFILE_DEPTH][2] = {};
+  int64_t prof_written[3] = {0, 0, 0};
+  int64_t prof_read[3] = {0, 0, 0};
 };
 
 namespace {
@@ -354,6 +355,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
   ctx->last_hops = num_hops;
   ctx->last_idx_bytes = (int32_t)sizeof(IdxT);
   ctx->last_bound_in = bound_dst[num_hops];
+  for (int h = 0; h < num_hops; ++h) ctx->last_bound_dst[h] = bound_dst[h];
   ctx->last_num_nodes = num_nodes;
   return A3_OK;
 }
@@ -457,6 +459,61 @@ int gather_enqueue(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
     gather_by_width<int64_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, out);
   prof_mark(ctx, 1, 1);
   A3_HIP(ctx, hipGetLastError());
+  return A3_OK;
+}
+
+template <typename T, int VW>
+void launch_block_mean(a3_ctx* ctx, const int32_t* indptr, const int32_t* indices, int64_t n_dst,
+                       const int32_t* n_dst_dev, int64_t n_src, const int32_t* n_src_dev,
+                       const void* x, int64_t dim, void* out) {
+  const uint32_t vecs = (uint32_t)(dim / VW);
+  int log2_g = 0;
+  while ((1u << log2_g) < vecs && log2_g < 6) ++log2_g;
+  const uint32_t per_lane = (vecs + (1u << log2_g) - 1) >> log2_g;
+  const unsigned blocks = blocks_for(n_dst << log2_g, a3::kMeanThreads);
+#define A3_MEAN(C)                                                                                   \
+  hipLaunchKernelGGL((a3::k_block_mean<T, VW, C>), dim3(blocks), dim3(a3::kMeanThreads), 0,         \
+                     ctx->stream, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, (const T*)x, \
+                     vecs, log2_g, (T*)out)
+  if (per_lane <= 1) A3_MEAN(1);
+  else if (per_lane <= 2) A3_MEAN(2);
+  else if (per_lane <= 4) A3_MEAN(4);
+  else A3_MEAN(8);
+#undef A3_MEAN
+}
+
+// shared by the two aggregation entry points; arguments already validated
+int block_mean_enqueue(a3_ctx* ctx, const int32_t* indptr, const int32_t* indices, int64_t n_dst,
+                       const int32_t* n_dst_dev, int64_t n_src, const int32_t* n_src_dev,
+                       const void* x, int32_t x_dtype, int64_t dim, void* out) {
+  // widest vector (16 bytes at most) that divides a row and keeps every row start aligned
+  const int64_t elem = x_dtype == A3_F32 ? 4 : 2;
+  const uintptr_t align_bits = (uintptr_t)x | (uintptr_t)out | (uintptr_t)(dim * elem);
+  if (align_bits & (uintptr_t)(elem - 1))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean: buffers must be aligned to their element type");
+  int64_t width = 16;
+  while (width > elem && (align_bits & (uintptr_t)(width - 1))) width >>= 1;
+  prof_mark(ctx, 2, 0);
+  if (x_dtype == A3_F32) {
+    if (width == 16) launch_block_mean<float, 4>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
+    else if (width == 8) launch_block_mean<float, 2>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
+    else launch_block_mean<float, 1>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
+  } else {
+    if (width == 16) launch_block_mean<_Float16, 8>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
+    else if (width == 8) launch_block_mean<_Float16, 4>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
+    else if (width == 4) launch_block_mean<_Float16, 2>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
+    else launch_block_mean<_Float16, 1>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
+  }
+  prof_mark(ctx, 2, 1);
+  A3_HIP(ctx, hipGetLastError());
+  return A3_OK;
+}
+
+int check_block_mean_args(a3_ctx* ctx, int32_t x_dtype, int64_t dim) {
+  if (x_dtype != A3_F32 && x_dtype != A3_F16)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean: x_dtype must be A3_F32 or A3_F16");
+  if (dim <= 0 || dim > (1ll << 28))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean: dim must be in [1, 2^28]");
   return A3_OK;
 }
 
@@ -716,11 +773,53 @@ extern "C" int a3_gather_input_features(a3_ctx* ctx, const void* feat_dev, const
                         out);
 }
 
+extern "C" int a3_block_mean(a3_ctx* ctx, const int32_t* blk_indptr, const int32_t* blk_indices,
+                             int64_t n_dst, int64_t n_src, const void* x, int32_t x_dtype,
+                             int64_t dim, void* out) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_block_mean: ctx is null");
+  if (n_dst < 0 || n_src < 0) return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean: negative size");
+  if (n_dst > 0x7FFFFFFFLL || n_src > 0x7FFFFFFFLL)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean: more than 2^31-1 rows");
+  const int rc = check_block_mean_args(ctx, x_dtype, dim);
+  if (rc != A3_OK) return rc;
+  // blk_indices may be null: a block without edges has none, and only the device knows
+  if (n_dst > 0 && (!blk_indptr || !x || !out))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean: blk_indptr, x or out is null");
+  if (ctx->flags & A3_HOST_ONLY)
+    return fail(ctx, A3_ERR_HIP, "a3_block_mean: context was created without a device");
+  if (n_dst == 0) return A3_OK;
+  A3_HIP(ctx, hipSetDevice(ctx->device));
+  return block_mean_enqueue(ctx, blk_indptr, blk_indices, n_dst, nullptr, n_src, nullptr, x, x_dtype,
+                            dim, out);
+}
+
+extern "C" int a3_block_mean_of_hop(a3_ctx* ctx, int32_t hop, const void* x, int32_t x_dtype,
+                                    int64_t dim, void* out, int64_t out_rows) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_block_mean_of_hop: ctx is null");
+  if (out_rows < 0 || (out_rows > 0 && !out))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean_of_hop: bad output buffer");
+  const int rc = check_block_mean_args(ctx, x_dtype, dim);
+  if (rc != A3_OK) return rc;
+  if (!x) return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean_of_hop: x is null");
+  if (ctx->flags & A3_HOST_ONLY)
+    return fail(ctx, A3_ERR_HIP, "a3_block_mean: context was created without a device");
+  if (ctx->last_hops == 0)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean_of_hop: nothing was sampled yet");
+  if (hop < 0 || hop >= ctx->last_hops)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean_of_hop: hop outside the last sampled blocks");
+  const int64_t bound = std::min(ctx->last_bound_dst[hop], out_rows);
+  if (bound == 0) return A3_OK;
+  A3_HIP(ctx, hipSetDevice(ctx->device));
+  return block_mean_enqueue(ctx, ctx->blk_indptr[hop], ctx->blk_indices[hop], bound,
+                            &ctx->d_state->n_dst[hop], 0, &ctx->d_state->n_src[hop], x, x_dtype, dim,
+                            out);
+}
+
 extern "C" int a3_profile_read(a3_ctx* ctx, int kind, float* ms, int max, int* n) {
   if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_profile_read: ctx is null");
   if (!(ctx->flags & A3_PROFILE) || (ctx->flags & A3_HOST_ONLY))
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_profile_read: context was created without A3_PROFILE");
-  if (kind < 0 || kind > 1 || !n || max < 0 || (max > 0 && !ms))
+  if (kind < 0 || kind > 2 || !n || max < 0 || (max > 0 && !ms))
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_profile_read: bad argument");
   A3_HIP(ctx, hipSetDevice(ctx->device));
   int64_t first = std::max(ctx->prof_read[kind], ctx->prof_written[kind] - A3_PROFILE_DEPTH);

@@ -151,3 +151,28 @@ def test_pipeline_argument_errors(L):
     assert L.a3_pipeline_wait(h, C.byref(blocks)) == a3.A3_ERR_INVALID_ARG  # still nothing in flight
     assert L.a3_pipeline_destroy(h) == a3.A3_OK
     assert L.a3_pipeline_destroy(None) == a3.A3_OK
+
+
+def test_block_mean_argument_errors(L):
+    rc, h = _create(L, 8, [3, 2], a3.A3_HOST_ONLY)
+    assert rc == a3.A3_OK
+    dummy = C.create_string_buffer(64)
+    p = C.cast(dummy, C.c_void_p)
+
+    def mean(ip=p, ix=p, n_dst=2, n_src=3, x=p, dt=a3.A3_F32, dim=4, out=p):
+        return L.a3_block_mean(h, ip, ix, n_dst, n_src, x, dt, dim, out)
+
+    assert L.a3_block_mean(None, p, p, 2, 3, p, 0, 4, p) == a3.A3_ERR_INVALID_ARG
+    assert mean(n_dst=-1) == a3.A3_ERR_INVALID_ARG
+    assert mean(n_src=1 << 31) == a3.A3_ERR_INVALID_ARG
+    assert mean(dt=2) == a3.A3_ERR_INVALID_ARG
+    assert b"x_dtype" in L.a3_last_error(h)
+    assert mean(dim=0) == a3.A3_ERR_INVALID_ARG
+    assert mean(ip=None) == a3.A3_ERR_INVALID_ARG
+    assert mean(x=None) == a3.A3_ERR_INVALID_ARG
+    assert mean(out=None) == a3.A3_ERR_INVALID_ARG
+    assert mean() == a3.A3_ERR_HIP  # valid arguments, no device
+    assert L.a3_block_mean_of_hop(h, 0, None, 0, 4, p, 2) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_block_mean_of_hop(h, 0, p, 0, 4, None, 2) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_block_mean_of_hop(h, 0, p, 0, 4, p, 2) == a3.A3_ERR_HIP
+    assert L.a3_destroy(h) == a3.A3_OK
