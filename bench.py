@@ -221,6 +221,39 @@ def main():
                      "avg_launch_seconds": gather_avg_s},
     }
 
+    # the step after the path: mean aggregation of the gathered rows over the outermost block
+    # (a3_block_mean_of_hop), timed by the library's events on a few of the same mini-batches
+    if w.feat_dtype in (torch.float32, torch.float16):
+        H = len(w.fanouts)
+        agg_rows = batch
+        for f in w.fanouts[:-1]:
+            agg_rows *= 1 + f
+        agg = torch.empty((min(agg_rows, w.num_nodes), w.feat_dim), dtype=w.feat_dtype, device=dev)
+        ctx.profile_read(2)
+        m_edges = m_dst = 0
+        n_mean = min(K, 10)
+        for b in range(W, W + n_mean):
+            ctx.sample_blocks_begin(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b)
+            ctx.gather_input_features(split.feat_dev, split.feat_host, d_cm, out)
+            ctx.block_mean_of_hop(H - 1, out, agg)
+            blk = ctx.sample_blocks_end()
+            m_edges += blk.n_edges[-1]
+            m_dst += blk.n_dst[-1]
+        torch.cuda.synchronize()
+        ms_m = ctx.profile_read(2)
+        mean_s = sum(ms_m) / len(ms_m) * 1e-3
+        # bytes the aggregation must move through the memory system per launch: one source row
+        # and one 4-byte local id per edge, one output row and one 4-byte offset per destination
+        mean_bytes = (m_edges * (row_bytes + 4) + m_dst * (row_bytes + 4)) / n_mean
+        result["block_mean"] = {"kernel": "k_block_mean (outermost block, rows of the gather)",
+                                "bound": "hbm", "achieved": mean_bytes / mean_s / 1e9,
+                                "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                "frac": mean_bytes / mean_s / 1e9 / HBM_PEAK_GBPS,
+                                "avg_launch_seconds": mean_s, "edges_per_launch": m_edges / n_mean,
+                                "dst_per_launch": m_dst / n_mean,
+                                "algorithmic_bytes_per_launch": mean_bytes}
+        del agg
+
     if not args.no_pipelines:
         # the same K mini-batches through the scheduling templates of Sec. III-B: n mini-batches in
         # flight on streams of their own (mode 1: whole mini-batches overlap; mode 2: sampling
