@@ -299,3 +299,65 @@ extern "C" int oracle_block_mean(const int32_t* blk_indptr, const int32_t* blk_i
   }
   return 0;
 }
+
+extern "C" int oracle_count_accesses(const void* ids, int32_t idx_bytes, int64_t n_ids,
+                                     int64_t num_nodes, uint32_t* counts) {
+  if (n_ids < 0 || num_nodes < 0 || (idx_bytes != 4 && idx_bytes != 8)) return -1;
+  if (n_ids > 0 && (!ids || !counts)) return -1;
+  for (int64_t i = 0; i < n_ids; ++i) {
+    const int64_t v = read_idx(ids, idx_bytes, i);
+    if (v < 0 || v >= num_nodes) return -1;
+    counts[v] += 1;
+  }
+  return 0;
+}
+
+extern "C" int oracle_rank_cache(const uint32_t* counts, int64_t num_nodes, int64_t n_cached,
+                                 int32_t* cache_map, int32_t* order) {
+  if (num_nodes < 0 || num_nodes > 0x7FFFFFFFLL || n_cached < 0 || n_cached > num_nodes) return -1;
+  if (num_nodes > 0 && (!counts || !cache_map)) return -1;
+  std::vector<int32_t> by_rank((size_t)num_nodes);
+  for (int64_t v = 0; v < num_nodes; ++v) by_rank[(size_t)v] = (int32_t)v;
+  std::sort(by_rank.begin(), by_rank.end(), [&](int32_t a, int32_t b) {
+    if (counts[a] != counts[b]) return counts[a] > counts[b];
+    return a < b;
+  });
+  for (int64_t r = 0; r < num_nodes; ++r) {
+    const int32_t v = by_rank[(size_t)r];
+    cache_map[v] = r < n_cached ? (int32_t)r : (int32_t)(-(r - n_cached) - 1);
+    if (order) order[r] = v;
+  }
+  return 0;
+}
+
+extern "C" int64_t oracle_cache_fifo_update(int32_t* cache_map, int64_t num_nodes,
+                                            int32_t* slot_owner, int32_t* head, int64_t n_slots,
+                                            void* feat_dev, int64_t row_bytes, const void* ids,
+                                            int32_t idx_bytes, int64_t n_ids, const void* rows) {
+  if (num_nodes < 0 || n_slots <= 0 || row_bytes <= 0 || n_ids < 0) return -1;
+  if (idx_bytes != 4 && idx_bytes != 8) return -1;
+  if (!cache_map || !slot_owner || !head || !feat_dev) return -1;
+  if (*head < 0 || *head >= n_slots) return -1;
+  if (n_ids > 0 && (!ids || !rows)) return -1;
+  // misses are judged against the cache as the mini-batch found it (the state its feature
+  // retrieve used): first list them, in order, then let them in one by one
+  std::vector<int64_t> missed;
+  for (int64_t i = 0; i < n_ids; ++i) {
+    const int64_t v = read_idx(ids, idx_bytes, i);
+    if (v < 0 || v >= num_nodes) return -1;
+    if (cache_map[v] < 0) missed.push_back(i);
+  }
+  const int64_t misses = (int64_t)missed.size();
+  for (const int64_t i : missed) {
+    const int64_t v = read_idx(ids, idx_bytes, i);
+    const int32_t s = *head;
+    const int32_t old = slot_owner[s];
+    if (old >= 0) cache_map[old] = -old - 1;  // back to its row of the host store
+    slot_owner[s] = (int32_t)v;
+    cache_map[v] = s;
+    std::memcpy((char*)feat_dev + (int64_t)s * row_bytes, (const char*)rows + i * row_bytes,
+                (size_t)row_bytes);
+    *head = (int32_t)((s + 1) % n_slots);
+  }
+  return misses;
+}

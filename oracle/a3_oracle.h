@@ -29,7 +29,10 @@
  * top-m of exact real keys u^(1/w), against the A-Res inclusion law by
  * chi-square and brute-force enumeration; relabel against brute force on
  * tiny graphs; gather against a library index_select; the block mean against
- * a dense normalised-adjacency product by a library matmul and closed forms.
+ * a dense normalised-adjacency product by a library matmul and closed forms;
+ * the access-count ranking against a library lexsort and the degree-ranked
+ * split of the input generators; the FIFO cache against a queue simulation
+ * written separately and a hand-followed example.
  * No function here is "parity unpinned".
  */
 #ifndef A3_ORACLE_H
@@ -117,6 +120,36 @@ int oracle_gather_features(const void* feat_dev, const void* feat_host, const in
  * Returns 0, or -1 on a bad argument (an index outside [0, n_src) included). */
 int oracle_block_mean(const int32_t* blk_indptr, const int32_t* blk_indices, int64_t n_dst,
                       int64_t n_src, const void* x, int32_t x_dtype, int64_t dim, double* out);
+
+/* Cache policies (Sec. III feature cache module; Sec. IV-C caches "the most
+ * frequently accessed nodes"; Sec. II-B names static and FIFO policies).
+ *
+ * oracle_count_accesses: counts[id] += 1 for every id (one mini-batch's input
+ * nodes); pre-sampling some mini-batches and counting gives the access
+ * frequencies.  Returns 0, or -1 on a bad argument or an id outside [0, num_nodes). */
+int oracle_count_accesses(const void* ids, int32_t idx_bytes, int64_t n_ids, int64_t num_nodes,
+                          uint32_t* counts);
+
+/* oracle_rank_cache: static fill.  Nodes are ranked by (count descending, id
+ * ascending); order[r] = the node of rank r; the first n_cached ranks get a
+ * device slot, the others a host row, in the device-map encoding:
+ * cache_map[v] = r if r < n_cached, else -(r - n_cached) - 1.
+ * order may be NULL.  Returns 0 or -1. */
+int oracle_rank_cache(const uint32_t* counts, int64_t num_nodes, int64_t n_cached,
+                      int32_t* cache_map, int32_t* order);
+
+/* oracle_cache_fifo_update: dynamic FIFO cache of n_slots rows.  The host
+ * store holds every row (an uncached node v has cache_map[v] = -v - 1).  The
+ * ids are one mini-batch's input nodes (distinct).  Those that were not cached
+ * when the mini-batch arrived (the state its feature retrieve used) enter in
+ * order: each takes the slot at the head of the ring, the slot's previous
+ * owner (slot_owner[s], -1 = none) leaves the cache, the id's row (rows[i],
+ * row_bytes wide) is copied into feat_dev[s], and the head moves on.  *head
+ * stays in [0, n_slots).  Returns the number of misses, or -1 on a bad
+ * argument. */
+int64_t oracle_cache_fifo_update(int32_t* cache_map, int64_t num_nodes, int32_t* slot_owner,
+                                 int32_t* head, int64_t n_slots, void* feat_dev, int64_t row_bytes,
+                                 const void* ids, int32_t idx_bytes, int64_t n_ids, const void* rows);
 
 #ifdef __cplusplus
 }

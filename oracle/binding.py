@@ -54,6 +54,14 @@ def lib():
         L.oracle_block_mean.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p,
                                         C.c_int32, C.c_int64, C.c_void_p]
         L.oracle_block_mean.restype = C.c_int
+        L.oracle_count_accesses.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p]
+        L.oracle_count_accesses.restype = C.c_int
+        L.oracle_rank_cache.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
+        L.oracle_rank_cache.restype = C.c_int
+        L.oracle_cache_fifo_update.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
+                                               C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_int64,
+                                               C.c_void_p]
+        L.oracle_cache_fifo_update.restype = C.c_int64
         L.oracle_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                              C.c_int32, C.c_int64, C.c_int64, C.c_void_p]
         L.oracle_gather_features.restype = C.c_int
@@ -174,3 +182,43 @@ def block_mean(blk_indptr, blk_indices, x):
     if rc != 0:
         raise ValueError("oracle_block_mean: bad argument")
     return out
+
+
+def count_accesses(ids, counts):
+    """counts[id] += 1 for every id, in place (counts: uint32 [num_nodes])"""
+    ids = np.ascontiguousarray(ids)
+    assert ids.dtype in (np.int32, np.int64)
+    assert counts.dtype == np.uint32 and counts.flags.c_contiguous
+    rc = lib().oracle_count_accesses(_ptr(ids), ids.dtype.itemsize, ids.shape[0], counts.shape[0],
+                                     _ptr(counts))
+    if rc != 0:
+        raise ValueError("oracle_count_accesses: bad argument")
+
+
+def rank_cache(counts, n_cached):
+    """(cache_map, order) of the static fill by access count"""
+    counts = np.ascontiguousarray(counts, dtype=np.uint32)
+    n = counts.shape[0]
+    cache_map = np.zeros(n, dtype=np.int32)
+    order = np.zeros(n, dtype=np.int32)
+    rc = lib().oracle_rank_cache(_ptr(counts), n, n_cached, _ptr(cache_map), _ptr(order))
+    if rc != 0:
+        raise ValueError("oracle_rank_cache: bad argument")
+    return cache_map, order
+
+
+def cache_fifo_update(cache_map, slot_owner, head, feat_dev, ids, rows):
+    """one mini-batch through the FIFO cache, in place; head is an int32 array of one element.
+    Returns the number of misses."""
+    ids = np.ascontiguousarray(ids)
+    rows = np.ascontiguousarray(rows)
+    assert cache_map.dtype == np.int32 and slot_owner.dtype == np.int32 and head.dtype == np.int32
+    assert feat_dev.flags.c_contiguous and feat_dev.ndim == 2
+    row_bytes = feat_dev.shape[1] * feat_dev.dtype.itemsize
+    assert rows.size == 0 or rows.shape[1] * rows.dtype.itemsize == row_bytes
+    m = lib().oracle_cache_fifo_update(_ptr(cache_map), cache_map.shape[0], _ptr(slot_owner),
+                                       _ptr(head), slot_owner.shape[0], _ptr(feat_dev), row_bytes,
+                                       _ptr(ids), ids.dtype.itemsize, ids.shape[0], _ptr(rows))
+    if m < 0:
+        raise ValueError("oracle_cache_fifo_update: bad argument")
+    return int(m)
