@@ -171,6 +171,45 @@ int a3_block_mean(a3_ctx* ctx, const int32_t* blk_indptr, const int32_t* blk_ind
 int a3_block_mean_of_hop(a3_ctx* ctx, int32_t hop, const void* x, int32_t x_dtype, int64_t dim,
                          void* out, int64_t out_rows);
 
+/* ---- Cache policies (Sec. III feature cache module; Sec. IV-C caches "the most frequently
+ * accessed nodes"; Sec. II-B names static and FIFO caches).  In all three calls ids == NULL means
+ * the input nodes of the context's most recent a3_sample_blocks(_begin), with their count taken on
+ * the device (idx_bytes and n_ids are then ignored), so the call can be queued without a host wait.
+ *
+ * a3_cache_count_accesses: counts[id] += 1 for every id.  Pre-sampling some mini-batches and
+ * counting their input nodes gives the access frequencies.
+ *   ids      device, idx_bytes wide, [n_ids], or NULL;  counts  device uint32 [num_nodes].
+ * Asynchronous on the context's stream. */
+int a3_cache_count_accesses(a3_ctx* ctx, const void* ids, int32_t idx_bytes, int64_t n_ids,
+                            int64_t num_nodes, uint32_t* counts);
+
+/* a3_cache_rank: the static fill.  Nodes are ranked by (count descending, id ascending); the
+ * first n_cached ranks get the device slot = rank, the others the host row = rank - n_cached:
+ *   cache_map[v] = r            if the rank r of v is below n_cached,
+ *                = -(r - n_cached) - 1 otherwise;      order[r] = v (order may be NULL).
+ *   counts   device uint32 [num_nodes] (any hotness: access counts, degrees);
+ *   cache_map, order   device int32 [num_nodes], written.
+ * The stores themselves are then two a3_gather_features calls on `order`.  Set-up work: allocates
+ * and frees temporaries (24 bytes per node) and returns after the stream has finished. */
+int a3_cache_rank(a3_ctx* ctx, const uint32_t* counts, int64_t num_nodes, int64_t n_cached,
+                  int32_t* cache_map, int32_t* order);
+
+/* a3_cache_fifo_update: one mini-batch through a FIFO cache of n_slots rows.  The host store holds
+ * every row, so an uncached node v has cache_map[v] = -v - 1.  The ids (distinct: a mini-batch's
+ * input nodes) that were not cached when the call starts enter in order: each takes the slot at the
+ * head of the ring, the slot's previous owner leaves the cache (its map entry returns to -v - 1),
+ * the id's row is copied from rows[i] into feat_dev[slot], and the head moves on.
+ *   cache_map    device int32 [num_nodes], updated;  slot_owner  device int32 [n_slots], node in
+ *                each slot or -1, updated;  fifo_state  device int32 [4], zero before first use:
+ *                [0] head, [1] misses of this update, [2] head before it;
+ *   feat_dev     device [n_slots, row_bytes], updated;  rows  device [n_ids, row_bytes], the
+ *                rows of the ids in the same order (what a3_gather_input_features wrote).
+ * Queue it after the mini-batch's gather; the next mini-batch's sampling then sees the new map.
+ * Asynchronous on the context's stream (the first call, or a larger n_ids, allocates scratch). */
+int a3_cache_fifo_update(a3_ctx* ctx, int32_t* cache_map, int64_t num_nodes, int32_t* slot_owner,
+                         int32_t* fifo_state, int64_t n_slots, void* feat_dev, int64_t row_bytes,
+                         const void* ids, int32_t idx_bytes, int64_t n_ids, const void* rows);
+
 /* Measurement aid (Sec. IV-A reports averages over runs; this gives per-call device times).
  * With A3_PROFILE every a3_sample_blocks (kind 0), a3_gather_features (kind 1) and a3_block_mean
  * (kind 2) brackets its kernels with HIP events on the context's stream.  a3_profile_read waits for the newest event

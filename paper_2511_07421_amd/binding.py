@@ -81,6 +81,15 @@ def lib():
         L.a3_block_mean_of_hop.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int64,
                                            C.c_void_p, C.c_int64]
         L.a3_block_mean_of_hop.restype = C.c_int
+        L.a3_cache_count_accesses.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64,
+                                              C.c_void_p]
+        L.a3_cache_count_accesses.restype = C.c_int
+        L.a3_cache_rank.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
+        L.a3_cache_rank.restype = C.c_int
+        L.a3_cache_fifo_update.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                           C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
+                                           C.c_int64, C.c_void_p]
+        L.a3_cache_fifo_update.restype = C.c_int
         L.a3_pipeline_create.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int, C.c_int64,
                                          C.c_int32, C.POINTER(C.c_int32), C.c_uint32]
         L.a3_pipeline_create.restype = C.c_int
@@ -332,6 +341,49 @@ class Context:
                                         _dptr(out), out.shape[0])
         self._check(rc)
         return out
+
+    def cache_count_accesses(self, counts: torch.Tensor, ids: Optional[torch.Tensor] = None) -> None:
+        """counts[id] += 1 for every id; ids = None: the input nodes of the last sampled mini-batch
+        (count taken on the device, may be queued before sample_blocks_end)"""
+        assert counts.dtype == torch.int32 and counts.is_contiguous(), "counts: int32 tensor (read as uint32)"
+        assert ids is None or (ids.dtype in (torch.int32, torch.int64) and ids.is_contiguous())
+        if ids is not None and ids.shape[0] == 0:
+            return  # an empty tensor has no address; a null `ids` would mean "the last input nodes"
+        rc = lib().a3_cache_count_accesses(self._h, _dptr(ids), 0 if ids is None else ids.element_size(),
+                                           0 if ids is None else ids.shape[0], counts.shape[0],
+                                           _dptr(counts))
+        self._check(rc)
+
+    def cache_rank(self, counts: torch.Tensor, n_cached: int):
+        """(cache_map, order) of the static fill ranked by (count descending, id ascending)"""
+        assert counts.dtype == torch.int32 and counts.is_contiguous()
+        n = counts.shape[0]
+        cache_map = torch.empty(n, dtype=torch.int32, device=counts.device)
+        order = torch.empty(n, dtype=torch.int32, device=counts.device)
+        self._check(lib().a3_cache_rank(self._h, _dptr(counts), n, n_cached, _dptr(cache_map),
+                                        _dptr(order)))
+        return cache_map, order
+
+    def cache_fifo_update(self, cache_map: torch.Tensor, slot_owner: torch.Tensor,
+                          fifo_state: torch.Tensor, feat_dev: torch.Tensor, rows: torch.Tensor,
+                          ids: Optional[torch.Tensor] = None) -> None:
+        """one mini-batch through the FIFO cache, in place; ids = None: the input nodes of the last
+        sampled mini-batch, rows then being what gather_input_features wrote"""
+        for t in (cache_map, slot_owner, fifo_state):
+            assert t.dtype == torch.int32 and t.is_contiguous()
+        assert fifo_state.shape[0] >= 4
+        assert feat_dev.dim() == 2 and feat_dev.is_contiguous() and rows.is_contiguous()
+        assert rows.dim() == 2 and rows.shape[1] == feat_dev.shape[1] and rows.dtype == feat_dev.dtype
+        assert ids is None or (ids.dtype in (torch.int32, torch.int64) and ids.is_contiguous()
+                               and ids.shape[0] <= rows.shape[0])
+        row_bytes = feat_dev.shape[1] * feat_dev.element_size()
+        if ids is not None and ids.shape[0] == 0:
+            return  # an empty tensor has no address; a null `ids` would mean "the last input nodes"
+        rc = lib().a3_cache_fifo_update(self._h, _dptr(cache_map), cache_map.shape[0], _dptr(slot_owner),
+                                        _dptr(fifo_state), slot_owner.shape[0], _dptr(feat_dev),
+                                        row_bytes, _dptr(ids), 0 if ids is None else ids.element_size(),
+                                        0 if ids is None else ids.shape[0], _dptr(rows))
+        self._check(rc)
 
 
 class Pipeline:

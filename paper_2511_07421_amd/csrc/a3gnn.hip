@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "a3_kernels.hpp"
+#include <rocprim/device/device_radix_sort.hpp>
 
 using a3::DevState;
 
@@ -45,6 +46,10 @@ struct a3_ctx {
   uint64_t* cached_bits = nullptr;  // one bit per node, rebuilt from the device map by every weighted call
   int64_t cached_bits_words = 0;
   bool node_map_dirty = false;
+  int32_t* fifo_rank = nullptr;   // FIFO update: per id, rank among its tile's misses (grown on demand)
+  int64_t fifo_rank_cap = 0;
+  int32_t* fifo_tiles = nullptr;  // FIFO update: tile sums, then tile offsets
+  int64_t fifo_tiles_cap = 0;
   DevState* d_state = nullptr;
   DevState* h_state = nullptr;      // pinned host copy of the counts, written by the last kernel
   DevState* h_state_dev = nullptr;  // the same memory as the device addresses it
@@ -165,6 +170,8 @@ void free_all(a3_ctx* ctx) {
   ctx->allocs.clear();
   if (ctx->node_map) (void)hipFree(ctx->node_map);
   if (ctx->cached_bits) (void)hipFree(ctx->cached_bits);
+  if (ctx->fifo_rank) (void)hipFree(ctx->fifo_rank);
+  if (ctx->fifo_tiles) (void)hipFree(ctx->fifo_tiles);
   ctx->node_map = nullptr;
   if (ctx->h_state) (void)hipHostFree(ctx->h_state);
   ctx->h_state = nullptr;
@@ -813,6 +820,190 @@ extern "C" int a3_block_mean_of_hop(a3_ctx* ctx, int32_t hop, const void* x, int
   return block_mean_enqueue(ctx, ctx->blk_indptr[hop], ctx->blk_indices[hop], bound,
                             &ctx->d_state->n_dst[hop], 0, &ctx->d_state->n_src[hop], x, x_dtype, dim,
                             out);
+}
+
+namespace {
+// grows a context-owned device buffer to at least `count` elements (contents are not kept)
+template <typename T>
+int ensure_buffer(a3_ctx* ctx, T** buf, int64_t* cap, int64_t count) {
+  if (count <= *cap) return A3_OK;
+  if (*buf) {
+    A3_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    A3_HIP(ctx, hipFree(*buf));
+    *buf = nullptr;
+    *cap = 0;
+  }
+  void* q = nullptr;
+  A3_HIP(ctx, hipMalloc(&q, (size_t)count * sizeof(T)));
+  *buf = (T*)q;
+  *cap = count;
+  return A3_OK;
+}
+
+// ids == NULL: the input nodes of the context's last sampled mini-batch, count on the device
+int resolve_ids(a3_ctx* ctx, const char* who, const void** ids, int32_t* idx_bytes, int64_t* n_ids,
+                const int32_t** n_ids_dev) {
+  *n_ids_dev = nullptr;
+  if (*ids) {
+    if (*idx_bytes != 4 && *idx_bytes != 8)
+      return fail(ctx, A3_ERR_INVALID_ARG, std::string(who) + ": idx_bytes must be 4 or 8");
+    if (*n_ids < 0) return fail(ctx, A3_ERR_INVALID_ARG, std::string(who) + ": n_ids < 0");
+    return A3_OK;
+  }
+  if (ctx->flags & A3_HOST_ONLY) return A3_OK;  // the caller reports the missing device
+  if (ctx->last_hops == 0)
+    return fail(ctx, A3_ERR_INVALID_ARG, std::string(who) + ": ids is null and nothing was sampled yet");
+  *ids = ctx->S;
+  *idx_bytes = ctx->last_idx_bytes;
+  *n_ids = ctx->last_bound_in;
+  *n_ids_dev = &ctx->d_state->n_src[ctx->last_hops - 1];
+  return A3_OK;
+}
+}  // namespace
+
+extern "C" int a3_cache_count_accesses(a3_ctx* ctx, const void* ids, int32_t idx_bytes, int64_t n_ids,
+                                       int64_t num_nodes, uint32_t* counts) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_cache_count_accesses: ctx is null");
+  if (num_nodes < 0) return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_count_accesses: num_nodes < 0");
+  if (!counts) return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_count_accesses: counts is null");
+  const int32_t* n_dev = nullptr;
+  const int rc = resolve_ids(ctx, "a3_cache_count_accesses", &ids, &idx_bytes, &n_ids, &n_dev);
+  if (rc != A3_OK) return rc;
+  if (ctx->flags & A3_HOST_ONLY)
+    return fail(ctx, A3_ERR_HIP, "a3_cache_count_accesses: context was created without a device");
+  if (n_ids == 0) return A3_OK;
+  A3_HIP(ctx, hipSetDevice(ctx->device));
+  const unsigned blocks = blocks_for(n_ids, a3::kTileThreads);
+  if (idx_bytes == 4)
+    hipLaunchKernelGGL(a3::k_count_accesses<int32_t>, dim3(blocks), dim3(a3::kTileThreads), 0, ctx->stream,
+                       (const int32_t*)ids, n_ids, n_dev, num_nodes, counts);
+  else
+    hipLaunchKernelGGL(a3::k_count_accesses<int64_t>, dim3(blocks), dim3(a3::kTileThreads), 0, ctx->stream,
+                       (const int64_t*)ids, n_ids, n_dev, num_nodes, counts);
+  A3_HIP(ctx, hipGetLastError());
+  return A3_OK;
+}
+
+extern "C" int a3_cache_rank(a3_ctx* ctx, const uint32_t* counts, int64_t num_nodes, int64_t n_cached,
+                             int32_t* cache_map, int32_t* order) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_cache_rank: ctx is null");
+  if (num_nodes < 0 || num_nodes > 0x7FFFFFFFLL)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_rank: num_nodes must be in [0, 2^31-1]");
+  if (n_cached < 0 || n_cached > num_nodes)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_rank: n_cached must be in [0, num_nodes]");
+  if (num_nodes > 0 && (!counts || !cache_map))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_rank: counts or cache_map is null");
+  if (ctx->flags & A3_HOST_ONLY)
+    return fail(ctx, A3_ERR_HIP, "a3_cache_rank: context was created without a device");
+  if (num_nodes == 0) return A3_OK;
+  A3_HIP(ctx, hipSetDevice(ctx->device));
+  // set-up work, once per training run: temporary buffers are allocated and freed here
+  uint64_t *keys = nullptr, *sorted = nullptr;
+  void* temp = nullptr;
+  size_t temp_bytes = 0;
+  int rc = A3_OK;
+  auto hip_ok = [&](hipError_t e, const char* what) {
+    if (e != hipSuccess && rc == A3_OK) rc = hip_fail(ctx, e, what);
+    return e == hipSuccess;
+  };
+  const unsigned blocks = blocks_for(num_nodes, a3::kTileThreads);
+  if (hip_ok(hipMalloc((void**)&keys, (size_t)num_nodes * sizeof(uint64_t)), "a3_cache_rank: hipMalloc") &&
+      hip_ok(hipMalloc((void**)&sorted, (size_t)num_nodes * sizeof(uint64_t)), "a3_cache_rank: hipMalloc") &&
+      hip_ok(rocprim::radix_sort_keys(nullptr, temp_bytes, keys, sorted, (size_t)num_nodes, 0, 64, ctx->stream),
+             "a3_cache_rank: radix sort (size query)") &&
+      hip_ok(hipMalloc(&temp, std::max<size_t>(temp_bytes, 1)), "a3_cache_rank: hipMalloc")) {
+    hipLaunchKernelGGL(a3::k_rank_keys, dim3(blocks), dim3(a3::kTileThreads), 0, ctx->stream, counts,
+                       num_nodes, keys);
+    if (hip_ok(hipGetLastError(), "a3_cache_rank: k_rank_keys") &&
+        hip_ok(rocprim::radix_sort_keys(temp, temp_bytes, keys, sorted, (size_t)num_nodes, 0, 64, ctx->stream),
+               "a3_cache_rank: radix sort")) {
+      hipLaunchKernelGGL(a3::k_rank_apply, dim3(blocks), dim3(a3::kTileThreads), 0, ctx->stream, sorted,
+                         num_nodes, n_cached, cache_map, order);
+      hip_ok(hipGetLastError(), "a3_cache_rank: k_rank_apply");
+    }
+  }
+  hip_ok(hipStreamSynchronize(ctx->stream), "a3_cache_rank: hipStreamSynchronize");
+  if (temp) (void)hipFree(temp);
+  if (sorted) (void)hipFree(sorted);
+  if (keys) (void)hipFree(keys);
+  return rc;
+}
+
+namespace {
+template <typename VecT, typename IdxT>
+void launch_fifo_apply(a3_ctx* ctx, const void* ids, int64_t n_ids, const int32_t* n_dev,
+                       const int32_t* tile_offs, const int32_t* state, int64_t n_slots,
+                       int64_t num_nodes, int32_t* cache_map, int32_t* slot_owner, const void* rows,
+                       void* feat_dev, int64_t row_bytes) {
+  const uint32_t vecs = (uint32_t)(row_bytes / (int64_t)sizeof(VecT));
+  int log2_g = 0;
+  while ((1u << log2_g) < vecs && log2_g < 6) ++log2_g;
+  const unsigned blocks = blocks_for(n_ids << log2_g, a3::kGatherThreads);
+  hipLaunchKernelGGL((a3::k_fifo_apply<VecT, IdxT>), dim3(blocks), dim3(a3::kGatherThreads), 0, ctx->stream,
+                     (const IdxT*)ids, n_ids, n_dev, ctx->fifo_rank, tile_offs, state, n_slots, num_nodes,
+                     cache_map, slot_owner, (const VecT*)rows, (VecT*)feat_dev, vecs, log2_g);
+}
+template <typename IdxT>
+void fifo_apply_by_width(a3_ctx* ctx, int width, const void* ids, int64_t n_ids, const int32_t* n_dev,
+                         const int32_t* tile_offs, const int32_t* state, int64_t n_slots,
+                         int64_t num_nodes, int32_t* cache_map, int32_t* slot_owner, const void* rows,
+                         void* feat_dev, int64_t row_bytes) {
+  switch (width) {
+    case 16: launch_fifo_apply<a3::vec16_t, IdxT>(ctx, ids, n_ids, n_dev, tile_offs, state, n_slots, num_nodes, cache_map, slot_owner, rows, feat_dev, row_bytes); break;
+    case 8: launch_fifo_apply<a3::vec8_t, IdxT>(ctx, ids, n_ids, n_dev, tile_offs, state, n_slots, num_nodes, cache_map, slot_owner, rows, feat_dev, row_bytes); break;
+    case 4: launch_fifo_apply<a3::vec4_t, IdxT>(ctx, ids, n_ids, n_dev, tile_offs, state, n_slots, num_nodes, cache_map, slot_owner, rows, feat_dev, row_bytes); break;
+    default: launch_fifo_apply<a3::vec2_t, IdxT>(ctx, ids, n_ids, n_dev, tile_offs, state, n_slots, num_nodes, cache_map, slot_owner, rows, feat_dev, row_bytes); break;
+  }
+}
+}  // namespace
+
+extern "C" int a3_cache_fifo_update(a3_ctx* ctx, int32_t* cache_map, int64_t num_nodes,
+                                    int32_t* slot_owner, int32_t* fifo_state, int64_t n_slots,
+                                    void* feat_dev, int64_t row_bytes, const void* ids,
+                                    int32_t idx_bytes, int64_t n_ids, const void* rows) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_cache_fifo_update: ctx is null");
+  if (num_nodes < 0 || num_nodes > 0x7FFFFFFFLL)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_fifo_update: num_nodes must be in [0, 2^31-1]");
+  if (n_slots < 1 || n_slots > 0x7FFFFFFFLL)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_fifo_update: n_slots must be in [1, 2^31-1]");
+  if (row_bytes <= 0 || (row_bytes & 1) || row_bytes > (1ll << 30))
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_fifo_update: row_bytes must be positive, even, at most 2^30");
+  if (!cache_map || !slot_owner || !fifo_state || !feat_dev || !rows)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_fifo_update: a required pointer is null");
+  const int32_t* n_dev = nullptr;
+  int rc = resolve_ids(ctx, "a3_cache_fifo_update", &ids, &idx_bytes, &n_ids, &n_dev);
+  if (rc != A3_OK) return rc;
+  if (ctx->flags & A3_HOST_ONLY)
+    return fail(ctx, A3_ERR_HIP, "a3_cache_fifo_update: context was created without a device");
+  const uintptr_t align_bits = (uintptr_t)feat_dev | (uintptr_t)rows | (uintptr_t)row_bytes;
+  if (align_bits & 1)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_fifo_update: buffers must be 2-byte aligned");
+  if (n_ids == 0) return A3_OK;
+  A3_HIP(ctx, hipSetDevice(ctx->device));
+  const int64_t n_tiles = (n_ids + a3::kTile - 1) / a3::kTile;
+  rc = ensure_buffer(ctx, &ctx->fifo_rank, &ctx->fifo_rank_cap, n_ids);
+  if (rc == A3_OK) rc = ensure_buffer(ctx, &ctx->fifo_tiles, &ctx->fifo_tiles_cap, 2 * n_tiles);
+  if (rc != A3_OK) return rc;
+  int32_t* tile_sums = ctx->fifo_tiles;
+  int32_t* tile_offs = ctx->fifo_tiles + n_tiles;
+  if (idx_bytes == 4)
+    hipLaunchKernelGGL(a3::k_fifo_flag<int32_t>, dim3((unsigned)n_tiles), dim3(a3::kTileThreads), 0, ctx->stream,
+                       (const int32_t*)ids, n_ids, n_dev, cache_map, num_nodes, ctx->fifo_rank, tile_sums);
+  else
+    hipLaunchKernelGGL(a3::k_fifo_flag<int64_t>, dim3((unsigned)n_tiles), dim3(a3::kTileThreads), 0, ctx->stream,
+                       (const int64_t*)ids, n_ids, n_dev, cache_map, num_nodes, ctx->fifo_rank, tile_sums);
+  hipLaunchKernelGGL(a3::k_fifo_scan, dim3(1), dim3(a3::kTileThreads), 0, ctx->stream, tile_sums, tile_offs,
+                     n_tiles, fifo_state, n_slots);
+  int width = 16;
+  while (width > 2 && (align_bits & (uintptr_t)(width - 1))) width >>= 1;
+  if (idx_bytes == 4)
+    fifo_apply_by_width<int32_t>(ctx, width, ids, n_ids, n_dev, tile_offs, fifo_state, n_slots, num_nodes,
+                                 cache_map, slot_owner, rows, feat_dev, row_bytes);
+  else
+    fifo_apply_by_width<int64_t>(ctx, width, ids, n_ids, n_dev, tile_offs, fifo_state, n_slots, num_nodes,
+                                 cache_map, slot_owner, rows, feat_dev, row_bytes);
+  A3_HIP(ctx, hipGetLastError());
+  return A3_OK;
 }
 
 extern "C" int a3_profile_read(a3_ctx* ctx, int kind, float* ms, int max, int* n) {

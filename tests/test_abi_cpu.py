@@ -176,3 +176,31 @@ def test_block_mean_argument_errors(L):
     assert L.a3_block_mean_of_hop(h, 0, p, 0, 4, None, 2) == a3.A3_ERR_INVALID_ARG
     assert L.a3_block_mean_of_hop(h, 0, p, 0, 4, p, 2) == a3.A3_ERR_HIP
     assert L.a3_destroy(h) == a3.A3_OK
+
+
+def test_cache_policy_argument_errors(L):
+    rc, h = _create(L, 8, [3, 2], a3.A3_HOST_ONLY)
+    assert rc == a3.A3_OK
+    dummy = C.create_string_buffer(64)
+    p = C.cast(dummy, C.c_void_p)
+    assert L.a3_cache_count_accesses(None, p, 4, 3, 10, p) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_cache_count_accesses(h, p, 4, 3, -1, p) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_cache_count_accesses(h, p, 4, 3, 10, None) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_cache_count_accesses(h, p, 2, 3, 10, p) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_cache_count_accesses(h, p, 4, -3, 10, p) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_cache_count_accesses(h, p, 4, 3, 10, p) == a3.A3_ERR_HIP
+    assert L.a3_cache_rank(h, p, 10, 11, p, None) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_cache_rank(h, p, -1, 0, p, None) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_cache_rank(h, None, 10, 2, p, None) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_cache_rank(h, p, 10, 2, p, None) == a3.A3_ERR_HIP
+
+    def fifo(cm=p, n=10, owner=p, st=p, slots=4, feat=p, rb=8, ids=p, ib=4, n_ids=2, rows=p):
+        return L.a3_cache_fifo_update(h, cm, n, owner, st, slots, feat, rb, ids, ib, n_ids, rows)
+
+    assert fifo(cm=None) == a3.A3_ERR_INVALID_ARG
+    assert fifo(slots=0) == a3.A3_ERR_INVALID_ARG
+    assert fifo(rb=7) == a3.A3_ERR_INVALID_ARG
+    assert fifo(rows=None) == a3.A3_ERR_INVALID_ARG
+    assert fifo(ib=3) == a3.A3_ERR_INVALID_ARG
+    assert fifo() == a3.A3_ERR_HIP
+    assert L.a3_destroy(h) == a3.A3_OK
