@@ -321,6 +321,25 @@ def main():
             "gather_GBps": o_rows * row_bytes / max(o_gather, 1e-9) / 1e9,
             "ms_sample": o_sample * 1e3 / done, "ms_gather": o_gather * 1e3 / done,
         }
+        # the same mini-batches on the library's own multi-threaded host sampler (the paper's
+        # "Sampling Device = CPU, Workers = n"): sampling + reindex only, bit-identical blocks
+        n_workers = min(16, os.cpu_count() or 1)
+        cpu = a3.CpuSampler(n_workers)
+        c_edges, c_s, c_done = 0, 0.0, 0
+        while c_s < args.cpu_seconds / 4 and c_done < K:
+            s_h = seeds[W + c_done].cpu().numpy()
+            c0 = time.perf_counter()
+            cb = cpu.sample_blocks(ip_h, ix_h, s_h, w.fanouts, cm_h, bias_q16, W + c_done)
+            c_s += time.perf_counter() - c0
+            c_edges += sum(cb.n_edges)
+            c_done += 1
+        cpu.close()
+        result["cpu_sampler"] = {
+            "value": c_edges / c_s, "unit": "sampled edges/s (sampling + reindex, no gather)",
+            "cores": n_workers, "kind": "a3cpu_sample_blocks, the library's multi-threaded host sampler",
+            "sample": "%d of the timed mini-batches, %.1f s" % (c_done, c_s),
+            "ms_sample": c_s * 1e3 / c_done,
+        }
     ctx.close()
     print(json.dumps(result))
 

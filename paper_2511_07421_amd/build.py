@@ -1,13 +1,14 @@
-"""Compile the HIP library (paper_2511_07421_amd/liba3gnn.so) for gfx950 with hipcc."""
+"""Compile the library (paper_2511_07421_amd/liba3gnn.so) with hipcc: the HIP kernels for gfx950 and
+the host-side CPU sampler."""
 import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "liba3gnn.so")
-SOURCES = [os.path.join(HERE, "csrc", "a3gnn.hip")]
+SOURCES = [os.path.join(HERE, "csrc", "a3gnn.hip"), os.path.join(HERE, "csrc", "a3cpu.cpp")]
 HEADERS = [os.path.join(HERE, "csrc", "a3_kernels.hpp"), os.path.join(HERE, "csrc", "a3_device.hpp"),
-           os.path.join(ROOT, "include", "a3gnn.h")]
+           os.path.join(ROOT, "include", "a3gnn.h"), os.path.join(ROOT, "include", "a3gnn_cpu.h")]
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
@@ -18,7 +19,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-command-line-argument",
+           "-Wall", "-Wno-unused-command-line-argument", "-pthread",
            "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
            "-o", LIB] + SOURCES
     if verbose:

@@ -25,9 +25,10 @@ def test_every_declared_symbol_is_exported(L):
         if fn.endswith(".h"):
             text = open(os.path.join(ROOT, "include", fn)).read()
             text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-            names |= set(re.findall(r"\b(a3_[a-z_]+)\s*\(", text))
+            names |= set(re.findall(r"\b(a3(?:cpu)?_[a-z_]+)\s*\(", text))
     assert {"a3_create", "a3_destroy", "a3_set_stream", "a3_last_error", "a3_sample_blocks",
-            "a3_gather_features"} <= names
+            "a3_gather_features", "a3_pipeline_submit", "a3_block_mean", "a3_cache_fifo_update",
+            "a3cpu_sample_blocks"} <= names
     for n in names:
         assert hasattr(L, n), n
 
