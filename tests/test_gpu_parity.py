@@ -150,7 +150,13 @@ def test_repeated_calls_are_byte_identical_and_seed_sensitive():
 
 @pytest.mark.parametrize("dim,dtype", [(64, torch.float32), (602, torch.float32), (100, torch.float32),
                                        (128, torch.float16), (3, torch.float16), (1, torch.float16),
-                                       (5, torch.float32)])
+                                       (5, torch.float32),
+                                       # rows that are 4- or 8-byte aligned and >= 64 bytes: 16-byte
+                                       # accesses plus a tail of 1-3 dwords, 1..8 vectors per lane,
+                                       # and more than one column step (n16 > 512)
+                                       (602, torch.float16), (17, torch.float32), (23, torch.float32),
+                                       (34, torch.float16), (2050, torch.float32), (4102, torch.float32),
+                                       (1538, torch.float16)])
 def test_gather_matches_oracle(dim, dtype):
     w, g, _, _ = _graph("tiny")
     full = make_features(g.num_nodes, dim, dtype, feat_seed=2)
