@@ -38,6 +38,9 @@ def parse():
     p.add_argument("--batch", type=int, default=None)
     p.add_argument("--cpu-seconds", type=float, default=20.0,
                    help="budget of the oracle (CPU baseline) leg; 0 disables it")
+    p.add_argument("--row-align", type=int, default=128,
+                   help="bytes between row starts of the feature stores and of the output are a "
+                        "multiple of this (0: packed rows)")
     p.add_argument("--no-pipelines", action="store_true",
                    help="skip the extra leg that runs the same steps through the stream pipelines")
     p.add_argument("--traffic-bytes", type=float, default=None,
@@ -69,7 +72,8 @@ def main():
     import numpy as np
     import torch
     import paper_2511_07421_amd as a3
-    from workloads import get_config, make_graph, make_features, degree_ranked_cache, seed_batch
+    from workloads import (get_config, make_graph, make_features, degree_ranked_cache, padded_rows,
+                           seed_batch)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -88,7 +92,7 @@ def main():
     g = make_graph(w.num_nodes, w.mean_degree, w.d_min, w.d_max, w.a, w.symmetric, w.graph_seed,
                    w.idx_dtype, device=dev)
     full = make_features(w.num_nodes, w.feat_dim, w.feat_dtype, device=dev)
-    split = degree_ranked_cache(g, full, cache_frac, pin_host=True)
+    split = degree_ranked_cache(g, full, cache_frac, pin_host=True, row_align=args.row_align)
     del full
     d_cm = split.cache_map
     idx_np = np.int32 if w.idx_dtype == torch.int32 else np.int64
@@ -107,7 +111,8 @@ def main():
     for f in w.fanouts:
         cap_rows = cap_rows * (1 + f)
     cap_rows = min(cap_rows, w.num_nodes)
-    out = torch.empty((cap_rows, w.feat_dim), dtype=w.feat_dtype, device=dev)
+    out = padded_rows(cap_rows, w.feat_dim, w.feat_dtype, dev, args.row_align)
+    row_stride = (out.stride(0) if cap_rows > 1 else w.feat_dim) * out.element_size()
 
     n_edges = n_in = 0
     last_ids = None
@@ -175,7 +180,8 @@ def main():
     # counters cannot be read from inside this process: the figure comes from the committed
     # rocprofv3 --pmc summary of this same command, and only for the configuration it was taken on
     traffic = args.traffic_bytes
-    if traffic is None and args.batch is None and args.cache_frac is None and args.bias_rate is None:
+    if (traffic is None and args.batch is None and args.cache_frac is None and args.bias_rate is None
+            and args.row_align == 128):
         traffic = recorded_traffic(w.name)
 
     gather_payload_gbps = n_in * row_bytes / (ms_gather * 1e-3) / 1e9
@@ -198,7 +204,7 @@ def main():
         "config": {"workload": w.name, "num_nodes": stats["num_nodes"], "nnz": stats["nnz"],
                    "mean_degree": round(stats["mean_degree"], 2), "max_degree": stats["max_degree"],
                    "idx_bytes": ib, "row_bytes": row_bytes, "batch": batch, "fanouts": w.fanouts,
-                   "bias_rate": gamma, "cache_frac": cache_frac,
+                   "bias_rate": gamma, "cache_frac": cache_frac, "row_stride_bytes": row_stride,
                    "generate_seconds": round(t_gen, 2)},
         "gather_GBps": gather_payload_gbps,
         "gather_frac_of_hbm_peak": achieved / HBM_PEAK_GBPS,
@@ -228,7 +234,7 @@ def main():
         agg_rows = batch
         for f in w.fanouts[:-1]:
             agg_rows *= 1 + f
-        agg = torch.empty((min(agg_rows, w.num_nodes), w.feat_dim), dtype=w.feat_dtype, device=dev)
+        agg = padded_rows(min(agg_rows, w.num_nodes), w.feat_dim, w.feat_dtype, dev, args.row_align)
         ctx.profile_read(2)
         m_edges = m_dst = 0
         n_mean = min(K, 10)
@@ -264,7 +270,8 @@ def main():
         for mode, n_w in [(a3.A3_PIPE_SEQUENTIAL, 1), (a3.A3_PIPE_MODE1, 2), (a3.A3_PIPE_MODE1, 3),
                           (a3.A3_PIPE_MODE2, 2), (a3.A3_PIPE_MODE2, 3)]:
             pipe = a3.Pipeline(mode, n_w, batch, w.fanouts)
-            outs = [out] + [torch.empty_like(out) for _ in range(n_w - 1)]
+            outs = [out] + [padded_rows(cap_rows, w.feat_dim, w.feat_dtype, dev, args.row_align)
+                            for _ in range(n_w - 1)]
             torch.cuda.synchronize()
             # n_w + W warm-up mini-batches, then the K timed ones of the main leg
             order = [i % (W + K) for i in range(n_w + W)] + list(range(W, W + K))
@@ -289,7 +296,7 @@ def main():
             pipes.append({"mode": names[mode], "workers": n_w, "ms_per_step": p_s * 1e3 / K,
                           "edges_per_s": p_edges / p_s,
                           "workspace_bytes": pipe.workspace_bytes,
-                          "output_bytes": sum(o.numel() * o.element_size() for o in outs)})
+                          "output_bytes": n_w * cap_rows * row_stride})
             pipe.close()
             del outs
         result["pipelines"] = pipes

@@ -149,6 +149,22 @@ int a3_gather_input_features(a3_ctx* ctx, const void* feat_dev, const void* feat
                              const int32_t* cache_map, int64_t row_bytes, void* out,
                              int64_t out_rows);
 
+/* The two retrieves for padded rows: row r of a store starts at r * stride bytes and holds
+ * row_bytes of payload.  dev_stride, host_stride, out_stride: 0 (packed, = row_bytes) or even and
+ * >= row_bytes.  Strides that are multiples of 16 (128: whole cache lines) let every row be moved
+ * with aligned 16-byte accesses whatever row_bytes is (2 408-byte rows: about 10 % faster than
+ * packed).  Where every stride in use leaves the room, a row is copied up to the next multiple of
+ * the access width: the padding of `out` rows then receives padding bytes of the source rows, and
+ * each store must be readable up to rows * stride.  Otherwise as the calls above. */
+int a3_gather_features_strided(a3_ctx* ctx, const void* feat_dev, int64_t dev_stride,
+                               const void* feat_host, int64_t host_stride, const int32_t* cache_map,
+                               const void* ids, int32_t idx_bytes, int64_t n_ids, int64_t row_bytes,
+                               void* out, int64_t out_stride);
+int a3_gather_input_features_strided(a3_ctx* ctx, const void* feat_dev, int64_t dev_stride,
+                                     const void* feat_host, int64_t host_stride,
+                                     const int32_t* cache_map, int64_t row_bytes, void* out,
+                                     int64_t out_stride, int64_t out_rows);
+
 /* Neighbour aggregation of one block, the step that consumes the path's output (Alg. 0 "forward";
  * the evaluation's GraphSAGE aggregates with the mean, Sec. IV-A):
  *   out[i,:] = mean over e in [blk_indptr[i], blk_indptr[i+1]) of x[blk_indices[e],:],  i < n_dst;
@@ -170,6 +186,14 @@ int a3_block_mean(a3_ctx* ctx, const int32_t* blk_indptr, const int32_t* blk_ind
  * that fills x).  min(n_dst[hop], out_rows) rows are written. */
 int a3_block_mean_of_hop(a3_ctx* ctx, int32_t hop, const void* x, int32_t x_dtype, int64_t dim,
                          void* out, int64_t out_rows);
+/* The same two for padded rows (x_stride, out_stride in bytes: 0 = packed, else a multiple of the
+ * element size and >= dim elements); the padding of `out` rows may be overwritten. */
+int a3_block_mean_strided(a3_ctx* ctx, const int32_t* blk_indptr, const int32_t* blk_indices,
+                          int64_t n_dst, int64_t n_src, const void* x, int64_t x_stride,
+                          int32_t x_dtype, int64_t dim, void* out, int64_t out_stride);
+int a3_block_mean_of_hop_strided(a3_ctx* ctx, int32_t hop, const void* x, int64_t x_stride,
+                                 int32_t x_dtype, int64_t dim, void* out, int64_t out_stride,
+                                 int64_t out_rows);
 
 /* ---- Cache policies (Sec. III feature cache module; Sec. IV-C caches "the most frequently
  * accessed nodes"; Sec. II-B names static and FIFO caches).  In all three calls ids == NULL means
@@ -254,15 +278,16 @@ int64_t a3_pipeline_workspace_bytes(const a3_pipeline* p);
 void* a3_pipeline_stream(const a3_pipeline* p, int w);
 
 /* Queue one mini-batch: sampling + reindex (arguments as a3_sample_blocks_begin), then feature
- * retrieve of its input nodes into out (arguments as a3_gather_input_features; row_bytes == 0
- * skips the retrieve).  Returns at once.  A3_ERR_CAPACITY when n_workers mini-batches are already
+ * retrieve of its input nodes into out (arguments as a3_gather_input_features_strided; strides of
+ * 0 = packed rows; row_bytes == 0 skips the retrieve).  Returns at once.  A3_ERR_CAPACITY when n_workers mini-batches are already
  * in flight (a3_pipeline_wait first).  `out` must not be in use by an earlier mini-batch that has
  * not been waited for, nor by the caller's own work. */
 int a3_pipeline_submit(a3_pipeline* p, const int64_t* indptr, const void* indices, int32_t idx_bytes,
                        int64_t num_nodes, const void* seeds, int64_t num_seeds,
                        const int32_t* fanouts, int32_t num_hops, const int32_t* cache_map,
-                       uint32_t bias_q16, uint64_t rng_seed, const void* feat_dev,
-                       const void* feat_host, int64_t row_bytes, void* out, int64_t out_rows);
+                       uint32_t bias_q16, uint64_t rng_seed, const void* feat_dev, int64_t dev_stride,
+                       const void* feat_host, int64_t host_stride, int64_t row_bytes, void* out,
+                       int64_t out_stride, int64_t out_rows);
 /* Wait for the oldest mini-batch in flight: its blocks (valid until n_workers further submits) and
  * its rows in `out` are complete on return.  Errors of that mini-batch as a3_sample_blocks_end;
  * A3_ERR_INVALID_ARG when nothing is in flight. */

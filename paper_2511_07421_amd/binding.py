@@ -72,6 +72,14 @@ def lib():
         L.a3_gather_input_features.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                C.c_int64, C.c_void_p, C.c_int64]
         L.a3_gather_input_features.restype = C.c_int
+        L.a3_gather_features_strided.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                                 C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64,
+                                                 C.c_void_p, C.c_int64]
+        L.a3_gather_features_strided.restype = C.c_int
+        L.a3_gather_input_features_strided.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                                       C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
+                                                       C.c_int64, C.c_int64]
+        L.a3_gather_input_features_strided.restype = C.c_int
         L.a3_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float), C.c_int,
                                       C.POINTER(C.c_int)]
         L.a3_profile_read.restype = C.c_int
@@ -90,6 +98,12 @@ def lib():
                                            C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                                            C.c_int64, C.c_void_p]
         L.a3_cache_fifo_update.restype = C.c_int
+        L.a3_block_mean_strided.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                            C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_int64]
+        L.a3_block_mean_strided.restype = C.c_int
+        L.a3_block_mean_of_hop_strided.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_int32,
+                                                   C.c_int64, C.c_void_p, C.c_int64, C.c_int64]
+        L.a3_block_mean_of_hop_strided.restype = C.c_int
         L.a3_pipeline_create.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int, C.c_int64,
                                          C.c_int32, C.POINTER(C.c_int32), C.c_uint32]
         L.a3_pipeline_create.restype = C.c_int
@@ -104,7 +118,7 @@ def lib():
         L.a3_pipeline_stream.argtypes = [C.c_void_p, C.c_int]
         L.a3_pipeline_stream.restype = C.c_void_p
         L.a3_pipeline_submit.argtypes = L.a3_sample_blocks_begin.argtypes + [
-            C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64]
+            C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_int64]
         L.a3_pipeline_submit.restype = C.c_int
         L.a3_pipeline_wait.argtypes = [C.c_void_p, C.POINTER(_CBlocks)]
         L.a3_pipeline_wait.restype = C.c_int
@@ -202,6 +216,16 @@ def _dptr(t: Optional[torch.Tensor]):
     return None if t is None else C.c_void_p(t.data_ptr())
 
 
+def _row_stride(t: Optional[torch.Tensor]) -> int:
+    """Bytes from one row of a 2-D tensor to the next.  Rows must be dense (unit stride inside a
+    row) but may be padded: a column slice of a wider buffer, t = buf[:, :dim], is accepted."""
+    if t is None:
+        return 0
+    assert t.dim() == 2 and (t.shape[1] == 1 or t.stride(1) == 1), "rows must be dense"
+    assert t.shape[0] <= 1 or t.stride(0) >= t.shape[1], "rows overlap"
+    return (t.stride(0) if t.shape[0] > 1 else t.shape[1]) * t.element_size()
+
+
 class Context:
     """An a3_ctx bound to a device and to torch's current stream on it."""
 
@@ -286,10 +310,12 @@ class Context:
         ref = feat_dev if feat_dev is not None else feat_host
         assert ref is not None and ref.dim() == 2
         assert feat_host is None or feat_host.is_pinned(), "feat_host must be pinned host memory"
-        assert out.is_contiguous() and out.dim() == 2 and out.shape[1] == ref.shape[1] and out.dtype == ref.dtype
+        assert out.dim() == 2 and out.shape[1] == ref.shape[1] and out.dtype == ref.dtype
         row_bytes = ref.shape[1] * ref.element_size()
-        rc = lib().a3_gather_input_features(self._h, _dptr(feat_dev), _dptr(feat_host),
-                                            _dptr(cache_map), row_bytes, _dptr(out), out.shape[0])
+        rc = lib().a3_gather_input_features_strided(self._h, _dptr(feat_dev), _row_stride(feat_dev),
+                                                    _dptr(feat_host), _row_stride(feat_host),
+                                                    _dptr(cache_map), row_bytes, _dptr(out),
+                                                    _row_stride(out), out.shape[0])
         self._check(rc)
         return out
 
@@ -299,16 +325,17 @@ class Context:
         ref = feat_dev if feat_dev is not None else feat_host
         assert ref is not None and ref.dim() == 2
         for t in (feat_dev, feat_host):
-            assert t is None or (t.is_contiguous() and t.dtype == ref.dtype and t.shape[1] == ref.shape[1])
+            assert t is None or (t.dtype == ref.dtype and t.shape[1] == ref.shape[1])
         assert feat_host is None or feat_host.is_pinned(), "feat_host must be pinned host memory"
         assert ids.dtype in (torch.int32, torch.int64) and ids.is_contiguous()
         row_bytes = ref.shape[1] * ref.element_size()
         if out is None:
             out = torch.empty((ids.shape[0], ref.shape[1]), dtype=ref.dtype, device=ids.device)
-        assert out.is_contiguous() and out.shape == (ids.shape[0], ref.shape[1]) and out.dtype == ref.dtype
-        rc = lib().a3_gather_features(self._h, _dptr(feat_dev), _dptr(feat_host), _dptr(cache_map),
-                                      _dptr(ids), ids.element_size(), ids.shape[0], row_bytes,
-                                      _dptr(out))
+        assert out.shape == (ids.shape[0], ref.shape[1]) and out.dtype == ref.dtype
+        rc = lib().a3_gather_features_strided(self._h, _dptr(feat_dev), _row_stride(feat_dev),
+                                              _dptr(feat_host), _row_stride(feat_host), _dptr(cache_map),
+                                              _dptr(ids), ids.element_size(), ids.shape[0], row_bytes,
+                                              _dptr(out), _row_stride(out))
         self._check(rc)
         return out
 
@@ -322,23 +349,23 @@ class Context:
         """mean of the source rows x[blk_indices[e]] of every destination of one block"""
         assert blk_indptr.dtype == torch.int32 and blk_indptr.is_contiguous()
         assert blk_indices.dtype == torch.int32 and blk_indices.is_contiguous()
-        assert x.dim() == 2 and x.is_contiguous()
         n_dst = blk_indptr.shape[0] - 1
         if out is None:
             out = torch.empty((n_dst, x.shape[1]), dtype=x.dtype, device=x.device)
-        assert out.is_contiguous() and out.shape == (n_dst, x.shape[1]) and out.dtype == x.dtype
-        rc = lib().a3_block_mean(self._h, _dptr(blk_indptr), _dptr(blk_indices), n_dst, x.shape[0],
-                                 _dptr(x), self._dtype_code(x), x.shape[1], _dptr(out))
+        assert out.shape == (n_dst, x.shape[1]) and out.dtype == x.dtype
+        rc = lib().a3_block_mean_strided(self._h, _dptr(blk_indptr), _dptr(blk_indices), n_dst,
+                                         x.shape[0], _dptr(x), _row_stride(x), self._dtype_code(x),
+                                         x.shape[1], _dptr(out), _row_stride(out))
         self._check(rc)
         return out
 
     def block_mean_of_hop(self, hop: int, x: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
         """the same for block `hop` of the last sampled mini-batch, counts taken on the device;
         may be queued before sample_blocks_end; writes out[:n_dst[hop]]"""
-        assert x.dim() == 2 and x.is_contiguous()
-        assert out.is_contiguous() and out.dim() == 2 and out.shape[1] == x.shape[1] and out.dtype == x.dtype
-        rc = lib().a3_block_mean_of_hop(self._h, hop, _dptr(x), self._dtype_code(x), x.shape[1],
-                                        _dptr(out), out.shape[0])
+        assert out.dim() == 2 and out.shape[1] == x.shape[1] and out.dtype == x.dtype
+        rc = lib().a3_block_mean_of_hop_strided(self._h, hop, _dptr(x), _row_stride(x),
+                                                self._dtype_code(x), x.shape[1], _dptr(out),
+                                                _row_stride(out), out.shape[0])
         self._check(rc)
         return out
 
@@ -441,13 +468,15 @@ class Pipeline:
             ref = feat_dev if feat_dev is not None else feat_host
             assert ref is not None and ref.dim() == 2
             assert feat_host is None or feat_host.is_pinned(), "feat_host must be pinned host memory"
-            assert out.is_contiguous() and out.dim() == 2 and out.shape[1] == ref.shape[1] and out.dtype == ref.dtype
+            assert out.dim() == 2 and out.shape[1] == ref.shape[1] and out.dtype == ref.dtype
             row_bytes, out_rows = ref.shape[1] * ref.element_size(), out.shape[0]
         fan = (C.c_int32 * len(fanouts))(*fanouts)
         rc = lib().a3_pipeline_submit(self._h, _dptr(indptr), _dptr(indices), indices.element_size(),
                                       indptr.shape[0] - 1, _dptr(seeds), seeds.shape[0], fan,
                                       len(fanouts), _dptr(cache_map), bias_q16, rng_seed,
-                                      _dptr(feat_dev), _dptr(feat_host), row_bytes, _dptr(out), out_rows)
+                                      _dptr(feat_dev), _row_stride(feat_dev), _dptr(feat_host),
+                                      _row_stride(feat_host), row_bytes, _dptr(out), _row_stride(out),
+                                      out_rows)
         self._check(rc)
         self._begun.append((indices.dtype, indices.device))
 

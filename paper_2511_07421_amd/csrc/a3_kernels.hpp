@@ -1393,6 +1393,8 @@ __global__ __launch_bounds__(kTileThreads) void k_relabel(const IdxT* gid, const
 // flight), then stores them; stores are streaming (the output is not read again by this kernel
 // and should not evict feature rows that the next mini-batch is likely to hit again).
 // With G = 64 the id and device-map lookups are wave-uniform and go through the scalar unit.
+// Rows may be padded: row r of a store starts at r * stride bytes, and vecs_per_row vectors are
+// copied (the host rounds the row up to a whole vector only where every stride has the room).
 // ---------------------------------------------------------------------------
 constexpr int kGatherThreads = 256;
 
@@ -1410,8 +1412,9 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restric
                                                            const int32_t* __restrict__ n_ids_dev,
                                                            int64_t id_limit,
                                                            uint32_t vecs_per_row,
-                                                           int64_t row_bytes, int log2_g,
-                                                           VecT* __restrict__ out) {
+                                                           int64_t dev_stride, int64_t host_stride,
+                                                           int64_t out_stride, int log2_g,
+                                                           char* __restrict__ out) {
   // the row count may live on the device (gather queued before the host knows it); n_ids then
   // is the launch bound and the output capacity
   if (n_ids_dev) {
@@ -1443,7 +1446,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restric
       if (kWaveRow) c = __builtin_amdgcn_readfirstlane(c);
       slot = c;
     }
-    const char* rowp = slot >= 0 ? feat_dev + slot * row_bytes : feat_host + (-slot - 1) * row_bytes;
+    const char* rowp = slot >= 0 ? feat_dev + slot * dev_stride : feat_host + (-slot - 1) * host_stride;
     src[r] = reinterpret_cast<const VecT*>(rowp);
   }
   for (uint32_t c0 = 0; c0 < vecs_per_row; c0 += G * U) {
@@ -1458,7 +1461,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restric
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       if (live[r]) {
-        VecT* dst = out + (r0 + r) * (int64_t)vecs_per_row;
+        VecT* dst = reinterpret_cast<VecT*>(out + (r0 + r) * out_stride);
 #pragma unroll
         for (int k = 0; k < U; ++k) {
           const uint32_t c = c0 + (uint32_t)k * G + lane;
@@ -1505,9 +1508,10 @@ __global__ __launch_bounds__(kMeanThreads) void k_block_mean(const int32_t* __re
                                                              const int32_t* __restrict__ n_dst_dev,
                                                              int64_t n_src,
                                                              const int32_t* __restrict__ n_src_dev,
-                                                             const T* __restrict__ x,
-                                                             uint32_t vecs_per_row, int log2_g,
-                                                             T* __restrict__ out) {
+                                                             const char* __restrict__ x,
+                                                             int64_t x_stride, uint32_t vecs_per_row,
+                                                             int log2_g, char* __restrict__ out,
+                                                             int64_t out_stride) {
   typedef typename MeanVec<T, VW>::type VecT;
   // the counts may live on the device (queued before the host knows them); the arguments then
   // are launch bounds and capacities
@@ -1521,8 +1525,7 @@ __global__ __launch_bounds__(kMeanThreads) void k_block_mean(const int32_t* __re
   const int64_t i = ((int64_t)blockIdx.x * kMeanThreads + threadIdx.x) >> log2_g;
   if (i >= n_dst) return;
   const int32_t e0 = indptr[i], e1 = indptr[i + 1];
-  const VecT* xv = reinterpret_cast<const VecT*>(x);
-  VecT* ov = reinterpret_cast<VecT*>(out) + i * (int64_t)vecs_per_row;
+  VecT* ov = reinterpret_cast<VecT*>(out + i * out_stride);
   const float deg = (float)(e1 - e0);
   for (uint32_t c0 = 0; c0 < vecs_per_row; c0 += G * C) {
     float acc[C][VW];
@@ -1537,7 +1540,7 @@ __global__ __launch_bounds__(kMeanThreads) void k_block_mean(const int32_t* __re
       for (int t = 0; t < kMeanEdgesInFlight; ++t) {
         const int32_t j = e + t < e1 ? indices[e + t] : -1;
         live[t] = j >= 0 && (int64_t)j < n_src;
-        row[t] = xv + (int64_t)(live[t] ? j : 0) * vecs_per_row;
+        row[t] = reinterpret_cast<const VecT*>(x + (int64_t)(live[t] ? j : 0) * x_stride);
       }
       VecT v[kMeanEdgesInFlight][C];
 #pragma unroll

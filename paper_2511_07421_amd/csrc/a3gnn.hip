@@ -400,17 +400,22 @@ int sample_finish(a3_ctx* ctx, a3_blocks* out) {
   return A3_OK;
 }
 
+// strides of a gather: bytes from one row to the next in the device store, the host store, the output
+struct GatherStrides {
+  int64_t dev, host, out;
+};
+
 template <typename VecT, typename IdxT, int U, int R, bool kWaveRow>
 void launch_gather_as(a3_ctx* ctx, int log2_g, const void* feat_dev, const void* feat_host,
                       const int32_t* cache_map, const void* ids, int64_t n_ids,
-                      const int32_t* n_ids_dev, int64_t id_limit, int64_t row_bytes, uint32_t vpr,
+                      const int32_t* n_ids_dev, int64_t id_limit, const GatherStrides& st, uint32_t vpr,
                       void* out) {
   const int64_t groups = (n_ids + R - 1) / R;
   const unsigned grid = blocks_for(groups << log2_g, a3::kGatherThreads);
   hipLaunchKernelGGL((a3::k_gather<VecT, IdxT, U, R, kWaveRow>), dim3(grid),
                      dim3(a3::kGatherThreads), 0, ctx->stream, (const char*)feat_dev,
                      (const char*)feat_host, cache_map, (const IdxT*)ids, n_ids, n_ids_dev, id_limit,
-                     vpr, row_bytes, log2_g, (VecT*)out);
+                     vpr, st.dev, st.host, st.out, log2_g, (char*)out);
 }
 
 // lanes per row: the smallest power of two covering the row's vectors, at most a wavefront;
@@ -418,12 +423,13 @@ void launch_gather_as(a3_ctx* ctx, int log2_g, const void* feat_dev, const void*
 template <typename VecT, typename IdxT>
 void launch_gather(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
                    const int32_t* cache_map, const void* ids, int64_t n_ids,
-                   const int32_t* n_ids_dev, int64_t id_limit, int64_t row_bytes, void* out) {
-  const uint32_t vpr = (uint32_t)(row_bytes / (int64_t)sizeof(VecT));
+                   const int32_t* n_ids_dev, int64_t id_limit, const GatherStrides& st,
+                   int64_t copy_bytes, void* out) {
+  const uint32_t vpr = (uint32_t)(copy_bytes / (int64_t)sizeof(VecT));
   int log2_g = 0;
   while (log2_g < 6 && (1u << log2_g) < vpr) ++log2_g;
 #define A3_GATHER(U, R, W) \
-  launch_gather_as<VecT, IdxT, U, R, W>(ctx, log2_g, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, vpr, out)
+  launch_gather_as<VecT, IdxT, U, R, W>(ctx, log2_g, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, st, vpr, out)
   if (log2_g < 6) {
     A3_GATHER(1, 4, false);
   } else {
@@ -439,31 +445,53 @@ void launch_gather(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
 template <typename IdxT>
 void gather_by_width(a3_ctx* ctx, int width, const void* feat_dev, const void* feat_host,
                      const int32_t* cache_map, const void* ids, int64_t n_ids,
-                     const int32_t* n_ids_dev, int64_t id_limit, int64_t row_bytes, void* out) {
+                     const int32_t* n_ids_dev, int64_t id_limit, const GatherStrides& st,
+                     int64_t copy_bytes, void* out) {
   switch (width) {
-    case 16: launch_gather<a3::vec16_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, out); break;
-    case 8: launch_gather<a3::vec8_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, out); break;
-    case 4: launch_gather<a3::vec4_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, out); break;
-    default: launch_gather<a3::vec2_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, out); break;
+    case 16: launch_gather<a3::vec16_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, st, copy_bytes, out); break;
+    case 8: launch_gather<a3::vec8_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, st, copy_bytes, out); break;
+    case 4: launch_gather<a3::vec4_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, st, copy_bytes, out); break;
+    default: launch_gather<a3::vec2_t, IdxT>(ctx, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, st, copy_bytes, out); break;
   }
 }
 
-// shared by the two gather entry points; arguments already validated
+// The widest vector (16, 8, 4 or 2 bytes) that keeps every row start of every buffer aligned.
+// A row that is not a whole number of such vectors is rounded up to one if every stride leaves
+// the room (padded rows: the copy then carries some padding along); otherwise the vector shrinks.
+// `strides` and `ptrs`: the buffers in use (a null pointer and its stride count for nothing).
+int pick_copy_width(int64_t row_bytes, const void* const* ptrs, const int64_t* strides, int n,
+                    int64_t min_width, int64_t* copy_bytes) {
+  for (int64_t width = 16; width >= min_width; width >>= 1) {
+    const int64_t rounded = (row_bytes + width - 1) / width * width;
+    bool ok = true;
+    for (int b = 0; b < n && ok; ++b) {
+      if (!ptrs[b]) continue;
+      ok = ((uintptr_t)ptrs[b] % (uintptr_t)width) == 0 && strides[b] % width == 0 && rounded <= strides[b];
+    }
+    if (ok) {
+      *copy_bytes = rounded;
+      return (int)width;
+    }
+  }
+  return 0;
+}
+
+// shared by the gather entry points; arguments already validated
 int gather_enqueue(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
                    const int32_t* cache_map, const void* ids, int32_t idx_bytes, int64_t n_ids,
-                   const int32_t* n_ids_dev, int64_t id_limit, int64_t row_bytes, void* out) {
-  // widest vector that divides the row and keeps every row start aligned in all three buffers
-  const uintptr_t align_bits = (uintptr_t)feat_dev | (uintptr_t)feat_host | (uintptr_t)out |
-                               (uintptr_t)row_bytes;
-  if (align_bits & 1)
-    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: buffers must be 2-byte aligned");
-  int width = 16;
-  while (width > 2 && (align_bits & (uintptr_t)(width - 1))) width >>= 1;
+                   const int32_t* n_ids_dev, int64_t id_limit, int64_t row_bytes,
+                   const GatherStrides& st, void* out) {
+  const void* ptrs[3] = {feat_dev, feat_host, out};
+  const int64_t strides[3] = {st.dev, st.host, st.out};
+  int64_t copy_bytes = row_bytes;
+  const int width = pick_copy_width(row_bytes, ptrs, strides, 3, 2, &copy_bytes);
+  if (width == 0)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: buffers and strides must be 2-byte aligned");
   prof_mark(ctx, 1, 0);
   if (idx_bytes == 4)
-    gather_by_width<int32_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, out);
+    gather_by_width<int32_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, st, copy_bytes, out);
   else
-    gather_by_width<int64_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, row_bytes, out);
+    gather_by_width<int64_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, st, copy_bytes, out);
   prof_mark(ctx, 1, 1);
   A3_HIP(ctx, hipGetLastError());
   return A3_OK;
@@ -472,16 +500,16 @@ int gather_enqueue(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
 template <typename T, int VW>
 void launch_block_mean(a3_ctx* ctx, const int32_t* indptr, const int32_t* indices, int64_t n_dst,
                        const int32_t* n_dst_dev, int64_t n_src, const int32_t* n_src_dev,
-                       const void* x, int64_t dim, void* out) {
-  const uint32_t vecs = (uint32_t)(dim / VW);
+                       const void* x, int64_t x_stride, int64_t copy_bytes, void* out, int64_t out_stride) {
+  const uint32_t vecs = (uint32_t)(copy_bytes / (int64_t)(VW * sizeof(T)));
   int log2_g = 0;
   while ((1u << log2_g) < vecs && log2_g < 6) ++log2_g;
   const uint32_t per_lane = (vecs + (1u << log2_g) - 1) >> log2_g;
   const unsigned blocks = blocks_for(n_dst << log2_g, a3::kMeanThreads);
-#define A3_MEAN(C)                                                                                   \
-  hipLaunchKernelGGL((a3::k_block_mean<T, VW, C>), dim3(blocks), dim3(a3::kMeanThreads), 0,         \
-                     ctx->stream, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, (const T*)x, \
-                     vecs, log2_g, (T*)out)
+#define A3_MEAN(C)                                                                                    \
+  hipLaunchKernelGGL((a3::k_block_mean<T, VW, C>), dim3(blocks), dim3(a3::kMeanThreads), 0,          \
+                     ctx->stream, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, (const char*)x, \
+                     x_stride, vecs, log2_g, (char*)out, out_stride)
   if (per_lane <= 1) A3_MEAN(1);
   else if (per_lane <= 2) A3_MEAN(2);
   else if (per_lane <= 4) A3_MEAN(4);
@@ -489,28 +517,32 @@ void launch_block_mean(a3_ctx* ctx, const int32_t* indptr, const int32_t* indice
 #undef A3_MEAN
 }
 
-// shared by the two aggregation entry points; arguments already validated
+// shared by the aggregation entry points; arguments already validated
 int block_mean_enqueue(a3_ctx* ctx, const int32_t* indptr, const int32_t* indices, int64_t n_dst,
                        const int32_t* n_dst_dev, int64_t n_src, const int32_t* n_src_dev,
-                       const void* x, int32_t x_dtype, int64_t dim, void* out) {
-  // widest vector (16 bytes at most) that divides a row and keeps every row start aligned
+                       const void* x, int64_t x_stride, int32_t x_dtype, int64_t dim, void* out,
+                       int64_t out_stride) {
   const int64_t elem = x_dtype == A3_F32 ? 4 : 2;
-  const uintptr_t align_bits = (uintptr_t)x | (uintptr_t)out | (uintptr_t)(dim * elem);
-  if (align_bits & (uintptr_t)(elem - 1))
-    return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean: buffers must be aligned to their element type");
-  int64_t width = 16;
-  while (width > elem && (align_bits & (uintptr_t)(width - 1))) width >>= 1;
+  const void* ptrs[2] = {x, out};
+  const int64_t strides[2] = {x_stride, out_stride};
+  int64_t copy_bytes = dim * elem;
+  const int64_t width = pick_copy_width(dim * elem, ptrs, strides, 2, elem, &copy_bytes);
+  if (width == 0)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean: buffers and strides must be aligned to the element type");
   prof_mark(ctx, 2, 0);
+#define A3_MEAN_AS(T, VW) \
+  launch_block_mean<T, VW>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, x_stride, copy_bytes, out, out_stride)
   if (x_dtype == A3_F32) {
-    if (width == 16) launch_block_mean<float, 4>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
-    else if (width == 8) launch_block_mean<float, 2>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
-    else launch_block_mean<float, 1>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
+    if (width == 16) A3_MEAN_AS(float, 4);
+    else if (width == 8) A3_MEAN_AS(float, 2);
+    else A3_MEAN_AS(float, 1);
   } else {
-    if (width == 16) launch_block_mean<_Float16, 8>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
-    else if (width == 8) launch_block_mean<_Float16, 4>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
-    else if (width == 4) launch_block_mean<_Float16, 2>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
-    else launch_block_mean<_Float16, 1>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, dim, out);
+    if (width == 16) A3_MEAN_AS(_Float16, 8);
+    else if (width == 8) A3_MEAN_AS(_Float16, 4);
+    else if (width == 4) A3_MEAN_AS(_Float16, 2);
+    else A3_MEAN_AS(_Float16, 1);
   }
+#undef A3_MEAN_AS
   prof_mark(ctx, 2, 1);
   A3_HIP(ctx, hipGetLastError());
   return A3_OK;
@@ -524,12 +556,25 @@ int check_block_mean_args(a3_ctx* ctx, int32_t x_dtype, int64_t dim) {
   return A3_OK;
 }
 
+// a stride of 0 stands for "packed": rows follow each other at row_bytes
+int resolve_stride(a3_ctx* ctx, const char* who, int64_t row_bytes, int64_t* stride) {
+  if (*stride == 0) *stride = row_bytes;
+  if (*stride < row_bytes || (*stride & 1) || *stride > (1ll << 31))
+    return fail(ctx, A3_ERR_INVALID_ARG,
+                std::string(who) + ": a row stride must be 0 (packed) or even, at least row_bytes, at most 2^31");
+  return A3_OK;
+}
+
 int check_gather_args(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
-                      const int32_t* cache_map, int64_t row_bytes) {
+                      const int32_t* cache_map, int64_t row_bytes, GatherStrides* st) {
   if (row_bytes <= 0 || (row_bytes & 1))
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: row_bytes must be positive and even");
   if (row_bytes > (1ll << 30))
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: row_bytes above 2^30");
+  int rc = resolve_stride(ctx, "a3_gather_features", row_bytes, &st->dev);
+  if (rc == A3_OK) rc = resolve_stride(ctx, "a3_gather_features", row_bytes, &st->host);
+  if (rc == A3_OK) rc = resolve_stride(ctx, "a3_gather_features", row_bytes, &st->out);
+  if (rc != A3_OK) return rc;
   if (!feat_dev && !feat_host)
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: both feature stores are null");
   if (!cache_map && !feat_dev)
@@ -737,9 +782,11 @@ extern "C" int a3_sample_blocks(a3_ctx* ctx, const int64_t* indptr, const void* 
   return a3_sample_blocks_end(ctx, out);
 }
 
-extern "C" int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
-                                  const int32_t* cache_map, const void* ids, int32_t idx_bytes,
-                                  int64_t n_ids, int64_t row_bytes, void* out) {
+extern "C" int a3_gather_features_strided(a3_ctx* ctx, const void* feat_dev, int64_t dev_stride,
+                                          const void* feat_host, int64_t host_stride,
+                                          const int32_t* cache_map, const void* ids,
+                                          int32_t idx_bytes, int64_t n_ids, int64_t row_bytes,
+                                          void* out, int64_t out_stride) {
   if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_gather_features: ctx is null");
   if (idx_bytes != 4 && idx_bytes != 8)
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: idx_bytes must be 4 or 8");
@@ -748,8 +795,9 @@ extern "C" int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void*
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: row_bytes must be positive and even");
   if (n_ids > 0 && (!ids || !out))
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: ids or out is null");
+  GatherStrides st{dev_stride, host_stride, out_stride};
   if (n_ids > 0) {
-    const int rc = check_gather_args(ctx, feat_dev, feat_host, cache_map, row_bytes);
+    const int rc = check_gather_args(ctx, feat_dev, feat_host, cache_map, row_bytes, &st);
     if (rc != A3_OK) return rc;
   }
   if (ctx->flags & A3_HOST_ONLY)
@@ -757,16 +805,26 @@ extern "C" int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void*
   if (n_ids == 0) return A3_OK;
   A3_HIP(ctx, hipSetDevice(ctx->device));
   return gather_enqueue(ctx, feat_dev, feat_host, cache_map, ids, idx_bytes, n_ids, nullptr, 0,
-                        row_bytes, out);
+                        row_bytes, st, out);
 }
 
-extern "C" int a3_gather_input_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
-                                        const int32_t* cache_map, int64_t row_bytes, void* out,
-                                        int64_t out_rows) {
+extern "C" int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
+                                  const int32_t* cache_map, const void* ids, int32_t idx_bytes,
+                                  int64_t n_ids, int64_t row_bytes, void* out) {
+  return a3_gather_features_strided(ctx, feat_dev, 0, feat_host, 0, cache_map, ids, idx_bytes, n_ids,
+                                    row_bytes, out, 0);
+}
+
+extern "C" int a3_gather_input_features_strided(a3_ctx* ctx, const void* feat_dev,
+                                                int64_t dev_stride, const void* feat_host,
+                                                int64_t host_stride, const int32_t* cache_map,
+                                                int64_t row_bytes, void* out, int64_t out_stride,
+                                                int64_t out_rows) {
   if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_gather_input_features: ctx is null");
   if (out_rows < 0 || (out_rows > 0 && !out))
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_input_features: bad output buffer");
-  const int rc = check_gather_args(ctx, feat_dev, feat_host, cache_map, row_bytes);
+  GatherStrides st{dev_stride, host_stride, out_stride};
+  const int rc = check_gather_args(ctx, feat_dev, feat_host, cache_map, row_bytes, &st);
   if (rc != A3_OK) return rc;
   if (ctx->flags & A3_HOST_ONLY)
     return fail(ctx, A3_ERR_HIP, "a3_gather_features: context was created without a device");
@@ -776,18 +834,30 @@ extern "C" int a3_gather_input_features(a3_ctx* ctx, const void* feat_dev, const
   if (bound == 0) return A3_OK;
   A3_HIP(ctx, hipSetDevice(ctx->device));
   return gather_enqueue(ctx, feat_dev, feat_host, cache_map, ctx->S, ctx->last_idx_bytes, bound,
-                        &ctx->d_state->n_src[ctx->last_hops - 1], ctx->last_num_nodes, row_bytes,
+                        &ctx->d_state->n_src[ctx->last_hops - 1], ctx->last_num_nodes, row_bytes, st,
                         out);
 }
 
-extern "C" int a3_block_mean(a3_ctx* ctx, const int32_t* blk_indptr, const int32_t* blk_indices,
-                             int64_t n_dst, int64_t n_src, const void* x, int32_t x_dtype,
-                             int64_t dim, void* out) {
+extern "C" int a3_gather_input_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
+                                        const int32_t* cache_map, int64_t row_bytes, void* out,
+                                        int64_t out_rows) {
+  return a3_gather_input_features_strided(ctx, feat_dev, 0, feat_host, 0, cache_map, row_bytes, out, 0,
+                                          out_rows);
+}
+
+extern "C" int a3_block_mean_strided(a3_ctx* ctx, const int32_t* blk_indptr,
+                                     const int32_t* blk_indices, int64_t n_dst, int64_t n_src,
+                                     const void* x, int64_t x_stride, int32_t x_dtype, int64_t dim,
+                                     void* out, int64_t out_stride) {
   if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_block_mean: ctx is null");
   if (n_dst < 0 || n_src < 0) return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean: negative size");
   if (n_dst > 0x7FFFFFFFLL || n_src > 0x7FFFFFFFLL)
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean: more than 2^31-1 rows");
-  const int rc = check_block_mean_args(ctx, x_dtype, dim);
+  int rc = check_block_mean_args(ctx, x_dtype, dim);
+  if (rc != A3_OK) return rc;
+  const int64_t row_bytes = dim * (x_dtype == A3_F32 ? 4 : 2);
+  rc = resolve_stride(ctx, "a3_block_mean", row_bytes, &x_stride);
+  if (rc == A3_OK) rc = resolve_stride(ctx, "a3_block_mean", row_bytes, &out_stride);
   if (rc != A3_OK) return rc;
   // blk_indices may be null: a block without edges has none, and only the device knows
   if (n_dst > 0 && (!blk_indptr || !x || !out))
@@ -796,16 +866,27 @@ extern "C" int a3_block_mean(a3_ctx* ctx, const int32_t* blk_indptr, const int32
     return fail(ctx, A3_ERR_HIP, "a3_block_mean: context was created without a device");
   if (n_dst == 0) return A3_OK;
   A3_HIP(ctx, hipSetDevice(ctx->device));
-  return block_mean_enqueue(ctx, blk_indptr, blk_indices, n_dst, nullptr, n_src, nullptr, x, x_dtype,
-                            dim, out);
+  return block_mean_enqueue(ctx, blk_indptr, blk_indices, n_dst, nullptr, n_src, nullptr, x, x_stride,
+                            x_dtype, dim, out, out_stride);
 }
 
-extern "C" int a3_block_mean_of_hop(a3_ctx* ctx, int32_t hop, const void* x, int32_t x_dtype,
-                                    int64_t dim, void* out, int64_t out_rows) {
+extern "C" int a3_block_mean(a3_ctx* ctx, const int32_t* blk_indptr, const int32_t* blk_indices,
+                             int64_t n_dst, int64_t n_src, const void* x, int32_t x_dtype,
+                             int64_t dim, void* out) {
+  return a3_block_mean_strided(ctx, blk_indptr, blk_indices, n_dst, n_src, x, 0, x_dtype, dim, out, 0);
+}
+
+extern "C" int a3_block_mean_of_hop_strided(a3_ctx* ctx, int32_t hop, const void* x,
+                                            int64_t x_stride, int32_t x_dtype, int64_t dim,
+                                            void* out, int64_t out_stride, int64_t out_rows) {
   if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_block_mean_of_hop: ctx is null");
   if (out_rows < 0 || (out_rows > 0 && !out))
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean_of_hop: bad output buffer");
-  const int rc = check_block_mean_args(ctx, x_dtype, dim);
+  int rc = check_block_mean_args(ctx, x_dtype, dim);
+  if (rc != A3_OK) return rc;
+  const int64_t row_bytes = dim * (x_dtype == A3_F32 ? 4 : 2);
+  rc = resolve_stride(ctx, "a3_block_mean_of_hop", row_bytes, &x_stride);
+  if (rc == A3_OK) rc = resolve_stride(ctx, "a3_block_mean_of_hop", row_bytes, &out_stride);
   if (rc != A3_OK) return rc;
   if (!x) return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean_of_hop: x is null");
   if (ctx->flags & A3_HOST_ONLY)
@@ -818,8 +899,13 @@ extern "C" int a3_block_mean_of_hop(a3_ctx* ctx, int32_t hop, const void* x, int
   if (bound == 0) return A3_OK;
   A3_HIP(ctx, hipSetDevice(ctx->device));
   return block_mean_enqueue(ctx, ctx->blk_indptr[hop], ctx->blk_indices[hop], bound,
-                            &ctx->d_state->n_dst[hop], 0, &ctx->d_state->n_src[hop], x, x_dtype, dim,
-                            out);
+                            &ctx->d_state->n_dst[hop], 0, &ctx->d_state->n_src[hop], x, x_stride,
+                            x_dtype, dim, out, out_stride);
+}
+
+extern "C" int a3_block_mean_of_hop(a3_ctx* ctx, int32_t hop, const void* x, int32_t x_dtype,
+                                    int64_t dim, void* out, int64_t out_rows) {
+  return a3_block_mean_of_hop_strided(ctx, hop, x, 0, x_dtype, dim, out, 0, out_rows);
 }
 
 namespace {
@@ -1147,8 +1233,9 @@ extern "C" int a3_pipeline_submit(a3_pipeline* p, const int64_t* indptr, const v
                                   int32_t idx_bytes, int64_t num_nodes, const void* seeds,
                                   int64_t num_seeds, const int32_t* fanouts, int32_t num_hops,
                                   const int32_t* cache_map, uint32_t bias_q16, uint64_t rng_seed,
-                                  const void* feat_dev, const void* feat_host, int64_t row_bytes,
-                                  void* out, int64_t out_rows) {
+                                  const void* feat_dev, int64_t dev_stride, const void* feat_host,
+                                  int64_t host_stride, int64_t row_bytes, void* out,
+                                  int64_t out_stride, int64_t out_rows) {
   if (!p) return pfail(nullptr, A3_ERR_INVALID_ARG, "a3_pipeline_submit: pipeline is null");
   if (p->submitted - p->waited >= p->n)
     return pfail(p, A3_ERR_CAPACITY, "a3_pipeline_submit: every worker has a mini-batch in flight; wait first");
@@ -1158,7 +1245,8 @@ extern "C" int a3_pipeline_submit(a3_pipeline* p, const int64_t* indptr, const v
   if (row_bytes > 0) {  // refuse a bad retrieve before anything is queued
     if (out_rows < 0 || (out_rows > 0 && !out))
       return pfail(p, A3_ERR_INVALID_ARG, "a3_pipeline_submit: bad output buffer");
-    const int rc = check_gather_args(c, feat_dev, feat_host, cache_map, row_bytes);
+    GatherStrides st{dev_stride, host_stride, out_stride};
+    const int rc = check_gather_args(c, feat_dev, feat_host, cache_map, row_bytes, &st);
     if (rc != A3_OK) return pfail(p, rc, c->err);
   }
   int rc = a3_sample_blocks_begin(c, indptr, indices, idx_bytes, num_nodes, seeds, num_seeds, fanouts,
@@ -1174,7 +1262,8 @@ extern "C" int a3_pipeline_submit(a3_pipeline* p, const int64_t* indptr, const v
       if (e != hipSuccess) return pfail(p, A3_ERR_HIP, std::string("a3_pipeline_submit: hipStreamWaitEvent: ") + hipGetErrorString(e));
       c->stream = p->batch_stream;
     }
-    rc = a3_gather_input_features(c, feat_dev, feat_host, cache_map, row_bytes, out, out_rows);
+    rc = a3_gather_input_features_strided(c, feat_dev, dev_stride, feat_host, host_stride, cache_map,
+                                          row_bytes, out, out_stride, out_rows);
     hipStream_t used = c->stream;
     c->stream = own;
     if (rc != A3_OK) {

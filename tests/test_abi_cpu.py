@@ -136,9 +136,9 @@ def test_pipeline_argument_errors(L):
     dummy = C.create_string_buffer(64)
     p = C.cast(dummy, C.c_void_p)
 
-    def submit(indptr=p, ns=4, bias=65536, row_bytes=0, out=None, out_rows=0, feat=None):
-        return L.a3_pipeline_submit(h, indptr, p, 4, 10, p, ns, fan, 2, None, bias, 0, feat, None,
-                                    row_bytes, out, out_rows)
+    def submit(indptr=p, ns=4, bias=65536, row_bytes=0, out=None, out_rows=0, feat=None, stride=0):
+        return L.a3_pipeline_submit(h, indptr, p, 4, 10, p, ns, fan, 2, None, bias, 0, feat, stride, None,
+                                    0, row_bytes, out, 0, out_rows)
 
     assert submit(indptr=None) == a3.A3_ERR_INVALID_ARG
     assert submit(bias=1) == a3.A3_ERR_INVALID_ARG
@@ -147,6 +147,7 @@ def test_pipeline_argument_errors(L):
     assert submit(row_bytes=3, out=p, out_rows=1, feat=p) == a3.A3_ERR_INVALID_ARG  # odd row
     assert submit(row_bytes=8, out=None, out_rows=4, feat=p) == a3.A3_ERR_INVALID_ARG
     assert submit(row_bytes=8, out=p, out_rows=4, feat=None) == a3.A3_ERR_INVALID_ARG  # no store
+    assert submit(row_bytes=8, out=p, out_rows=4, feat=p, stride=6) == a3.A3_ERR_INVALID_ARG  # stride < row
     assert submit() == a3.A3_ERR_HIP  # valid arguments, but no device behind the pipeline
     assert b"without a device" in L.a3_pipeline_last_error(h)
     assert L.a3_pipeline_wait(h, C.byref(blocks)) == a3.A3_ERR_INVALID_ARG  # still nothing in flight
@@ -204,4 +205,25 @@ def test_cache_policy_argument_errors(L):
     assert fifo(rows=None) == a3.A3_ERR_INVALID_ARG
     assert fifo(ib=3) == a3.A3_ERR_INVALID_ARG
     assert fifo() == a3.A3_ERR_HIP
+    assert L.a3_destroy(h) == a3.A3_OK
+
+
+def test_strided_argument_errors(L):
+    rc, h = _create(L, 8, [3, 2], a3.A3_HOST_ONLY)
+    assert rc == a3.A3_OK
+    dummy = C.create_string_buffer(64)
+    p = C.cast(dummy, C.c_void_p)
+
+    def gather(ds=0, hs=0, os_=0, rb=8):
+        return L.a3_gather_features_strided(h, p, ds, p, hs, None, p, 4, 2, rb, p, os_)
+
+    assert gather(ds=6) == a3.A3_ERR_INVALID_ARG          # stride below the row
+    assert b"stride" in L.a3_last_error(h)
+    assert gather(hs=9) == a3.A3_ERR_INVALID_ARG          # odd stride
+    assert gather(os_=-16) == a3.A3_ERR_INVALID_ARG
+    assert gather(ds=128, hs=0, os_=16) == a3.A3_ERR_HIP  # valid, but no device
+    assert L.a3_gather_input_features_strided(h, p, 4, None, 0, None, 8, p, 0, 2) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_block_mean_strided(h, p, p, 2, 3, p, 12, a3.A3_F32, 4, p, 0) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_block_mean_strided(h, p, p, 2, 3, p, 32, a3.A3_F32, 4, p, 64) == a3.A3_ERR_HIP
+    assert L.a3_block_mean_of_hop_strided(h, 0, p, 0, a3.A3_F16, 4, p, 6, 2) == a3.A3_ERR_INVALID_ARG
     assert L.a3_destroy(h) == a3.A3_OK

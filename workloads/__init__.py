@@ -7,5 +7,5 @@ batches, generated from integer hashes so that a given (config, seed) always
 yields the same arrays on a given device type.
 """
 from .graphs import powerlaw_degrees, chung_lu_csr, make_graph, Graph  # noqa: F401
-from .features import make_features, degree_ranked_cache, CacheSplit, seed_batch  # noqa: F401
+from .features import make_features, degree_ranked_cache, padded_rows, CacheSplit, seed_batch  # noqa: F401
 from .configs import CONFIGS, Workload, get_config  # noqa: F401

@@ -21,6 +21,20 @@ def make_features(num_nodes: int, dim: int, dtype=torch.float32, feat_seed: int 
     return out
 
 
+def padded_rows(n_rows: int, dim: int, dtype, device="cpu", row_align: int = 0,
+                pin_memory: bool = False) -> torch.Tensor:
+    """An [n_rows, dim] tensor whose rows start row_align bytes apart or a multiple of it
+    (row_align = 0: packed).  It is a column slice of a wider buffer, so rows are dense but
+    separated by padding; 128 gives every row whole cache lines."""
+    elem = torch.empty(0, dtype=dtype).element_size()
+    wide = dim
+    if row_align:
+        assert row_align % elem == 0
+        wide = (dim * elem + row_align - 1) // row_align * row_align // elem
+    buf = torch.zeros((n_rows, wide), dtype=dtype, device=device, pin_memory=pin_memory)
+    return buf[:, :dim] if wide != dim else buf
+
+
 @dataclass
 class CacheSplit:
     cache_map: torch.Tensor            # int32 [N]: c >= 0 -> row c of feat_dev; c < 0 -> row -c-1 of feat_host
@@ -30,11 +44,12 @@ class CacheSplit:
 
 
 def degree_ranked_cache(graph: Graph, full: Optional[torch.Tensor], frac: float,
-                        pin_host: bool = False) -> CacheSplit:
+                        pin_host: bool = False, row_align: int = 0) -> CacheSplit:
     """Static cache of the hottest rows, hotness = degree (the policy the paper cites from
     PaGraph in Sec. II-B and uses, as 'most frequently accessed', in its ablation).
     Rank nodes by (degree descending, id ascending); the first ceil(frac * N) ranks live in
-    the device cache at slot = rank, the others in the host store at slot = rank - n_cached."""
+    the device cache at slot = rank, the others in the host store at slot = rank - n_cached.
+    row_align > 0 pads the rows of both stores (see padded_rows)."""
     N = graph.num_nodes
     n_cached = min(N, int(math.ceil(frac * N)))
     deg = graph.degrees()
@@ -46,10 +61,17 @@ def degree_ranked_cache(graph: Graph, full: Optional[torch.Tensor], frac: float,
     if full is not None:
         order_f = order.to(full.device)
         if n_cached > 0:
-            feat_dev = full[order_f[:n_cached]].contiguous()
+            if row_align:
+                feat_dev = padded_rows(n_cached, full.shape[1], full.dtype, full.device, row_align)
+                step = 1 << 20
+                for r0 in range(0, n_cached, step):
+                    r1 = min(n_cached, r0 + step)
+                    feat_dev[r0:r1] = full[order_f[r0:r1]]
+            else:
+                feat_dev = full[order_f[:n_cached]].contiguous()
         if n_cached < N:
             rest = order_f[n_cached:]
-            host = torch.empty((N - n_cached, full.shape[1]), dtype=full.dtype, pin_memory=pin_host)
+            host = padded_rows(N - n_cached, full.shape[1], full.dtype, "cpu", row_align, pin_memory=pin_host)
             step = 1 << 20
             for r0 in range(0, N - n_cached, step):
                 r1 = min(N - n_cached, r0 + step)
