@@ -10,7 +10,8 @@ import torch
 import oracle
 import paper_2511_07421_amd as a3
 from helpers import blocks_equal, check_block_invariants
-from workloads import get_config, make_graph, make_features, degree_ranked_cache, seed_batch
+from workloads import (get_config, make_graph, make_features, degree_ranked_cache, padded_rows,
+                       seed_batch)
 
 pytestmark = pytest.mark.gpu
 Q = 65536
@@ -49,22 +50,31 @@ def _run(name, gammas, check_rows, n_batches=1, full_hops=None):
     g = make_graph(w.num_nodes, w.mean_degree, w.d_min, w.d_max, w.a, w.symmetric, w.graph_seed,
                    w.idx_dtype, device=DEV)
     full = make_features(w.num_nodes, w.feat_dim, w.feat_dtype, device=DEV)
-    split = degree_ranked_cache(g, full, w.cache_frac, pin_host=True)
+    # as bench.py: rows of the stores and of the output padded to a multiple of 128 bytes
+    split = degree_ranked_cache(g, full, w.cache_frac, pin_host=True, row_align=128)
     torch.cuda.synchronize()
     print(f"[gen] {name}: {g.stats()} cached={split.n_cached} in {time.time() - t0:.1f}s", flush=True)
     ip_h, ix_h = g.indptr.cpu().numpy(), g.indices.cpu().numpy()
     cm_h = split.cache_map.cpu().numpy()
     idt = ix_h.dtype
     ctx = a3.Context(w.batch, w.fanouts)
+    cap_rows = w.batch
+    for f in w.fanouts:
+        cap_rows *= 1 + f
+    cap_rows = min(cap_rows, w.num_nodes)
+    out = padded_rows(cap_rows, w.feat_dim, w.feat_dtype, DEV, 128)
     for gamma in gammas:
         for b in range(n_batches):
             seeds = seed_batch(w.num_nodes, w.batch, 0, b, dtype=idt)
             print(f"[case] {name} gamma={gamma} batch={b}", flush=True)
             t0 = time.time()
-            got_d = ctx.sample_blocks(g.indptr, g.indices, torch.from_numpy(seeds).to(DEV), w.fanouts,
-                                      split.cache_map, int(gamma * Q), b)
-            rows = ctx.gather_features(split.feat_dev, split.feat_host, split.cache_map,
-                                       got_d.input_nodes)
+            # the step exactly as bench.py queues it: sampling, the gather of its input nodes with
+            # the row count taken on the device, then the wait for the counts
+            ctx.sample_blocks_begin(g.indptr, g.indices, torch.from_numpy(seeds).to(DEV), w.fanouts,
+                                    split.cache_map, int(gamma * Q), b)
+            ctx.gather_input_features(split.feat_dev, split.feat_host, split.cache_map, out)
+            got_d = ctx.sample_blocks_end()
+            rows = out[: got_d.n_src[-1]]
             torch.cuda.synchronize()
             t1 = time.time()
             got = got_d.to_host()
