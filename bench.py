@@ -211,6 +211,11 @@ def main():
         "sample_edges_per_s": n_edges / (ms_sample * 1e-3),
         "ms_sample": ms_sample / K,
         "ms_gather": ms_gather / K,
+        "ms_sample_median_min": [sorted(ms_s)[len(ms_s) // 2], min(ms_s)],
+        "ms_gather_median_min": [sorted(ms_g)[len(ms_g) // 2], min(ms_g)],
+        # rows that are not in the HBM cache cross PCIe (zero-copy reads of pinned host memory)
+        "pcie_GBps": (n_in / K) * (1.0 - hit_rate) * row_bytes / gather_avg_s / 1e9 if hit_rate < 1.0 else 0.0,
+        "hbm_traffic_GBps": traffic / gather_avg_s / 1e9 if traffic else None,
         "edges_per_step": n_edges / K,
         "input_rows_per_step": n_in / K,
         "cache_hit_rate": hit_rate,

@@ -1,16 +1,21 @@
-// HIP kernels of the sampling / reindex / gather path (gfx950, wave64).
+// HIP kernels of the sampling / reindex / gather path (gfx950, wave64) and of the steps around it.
 //
-// Per hop six launches; workgroups of one kernel never exchange data with each other, results
-// pass from kernel to kernel only (each XCD has its own L2, and making a store visible to
-// another XCD inside a kernel costs a write-back of that L2):
+// Per hop four to six launches; workgroups of one kernel never exchange data with each other,
+// results pass from kernel to kernel only (each XCD has its own L2, and making a store visible
+// to another XCD inside a kernel costs a write-back of that L2):
 //   k_frontier    degrees of the frontier nodes, tile-local prefix of the per-node edge counts,
-//                 tile sums, nodes binned by degree
-//   k_scan_tiles  exclusive scan of the tile sums (one workgroup)
-//   k_sample      keyed selection; small-degree bins by groups of 4/8/16 lanes, the rest one
-//                 wavefront per node; records first occurrences in node_map
+//                 tile sums, node records binned by degree
+//   k_scan_tiles  exclusive scan of the tile sums (one workgroup; only above 1024 tiles,
+//                 otherwise the consumers scan the tile sums themselves in LDS)
+//   k_sample      keyed selection; small-degree bins by groups of 4/8/16 lanes, wide nodes one
+//                 wavefront each, hubs one workgroup each; records first occurrences in node_map
 //   k_flag        which sampled edge is the first occurrence of a new node; tile-local prefix
-//   k_scan_tiles  numbering of the new nodes across tiles
+//   k_scan_tiles  numbering of the new nodes across tiles (as above)
 //   k_relabel     local ids of all edges, new nodes appended to the frontier
+// Once per call: k_cached_bits (weighted calls: one bit per node from the device map),
+// k_finish_call (reset of the relabel map, counts to the host).
+// Then: k_gather (feature retrieve), k_block_mean (neighbour aggregation of one block),
+// k_count_accesses / k_rank_* / k_fifo_* (cache policies).
 #pragma once
 #include "a3_device.hpp"
 
