@@ -17,6 +17,8 @@
 // Then: k_gather (feature retrieve), k_block_mean (neighbour aggregation of one block),
 // k_count_accesses / k_rank_* / k_fifo_* (cache policies).
 #pragma once
+#include <type_traits>
+
 #include "a3_device.hpp"
 
 namespace a3 {
@@ -808,7 +810,12 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
   const bool want_b = kWeighted && a.capb > 0;
   const uint32_t X1 = want_b ? second_list_floor(keep, a.bias_q16) : 0u;
   if (!a.force_radix && !prefiltered) {
-    for (uint32_t q0 = 0; q0 < n_quads; q0 += kWave) {
+    // One step: 64 quads = 256 slots.  Only the last step of a row can hold slots past its end,
+    // so the steps before it run without the range test (tail = false): a lane's condition is
+    // then one comparison, which is also its ballot.
+    const uint32_t b_span = X0 - X1;  // second list: X1 <= x < X0, as one unsigned comparison
+    auto step = [&](uint32_t q0, auto tail) {
+      constexpr bool kTail = decltype(tail)::value;
       const uint32_t q = q0 + lane;
       uint32_t x[4];
       philox4x32_10(q, pk, x);
@@ -816,7 +823,8 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
       uint64_t mk[4];
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        pass[w] = (4u * q + (uint32_t)w < deg) && (x[w] >= X0);
+        pass[w] = x[w] >= X0;
+        if (kTail) pass[w] = pass[w] && (4u * q + (uint32_t)w < deg);
         mk[w] = __ballot(pass[w]);
       }
       if (mk[0] | mk[1] | mk[2] | mk[3]) {
@@ -836,7 +844,8 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
         uint64_t mb[4];
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-          pb[w] = (4u * q + (uint32_t)w < deg) && (x[w] >= X1) && (x[w] < X0);
+          pb[w] = (x[w] - X1) < b_span;
+          if (kTail) pb[w] = pb[w] && (4u * q + (uint32_t)w < deg);
           mb[w] = __ballot(pb[w]);
         }
         if (mb[0] | mb[1] | mb[2] | mb[3]) {
@@ -851,7 +860,11 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
           cnt_b += (uint32_t)(__popcll(mb[0]) + __popcll(mb[1]) + __popcll(mb[2]) + __popcll(mb[3]));
         }
       }
-    }
+    };
+    const uint32_t whole_steps_end = (deg >> 2) & ~(uint32_t)(kWave - 1);
+    uint32_t q0 = 0;
+    for (; q0 < whole_steps_end; q0 += kWave) step(q0, std::false_type{});
+    for (; q0 < n_quads; q0 += kWave) step(q0, std::true_type{});
     wave_sync();
   }
   // the lists can replace the second scan if both are complete
@@ -1140,7 +1153,9 @@ __device__ __forceinline__ void hub_scan(const SampleArgs<IdxT>& a, const NodeRe
     const uint32_t share = (((n_quads + n_waves - 1) / n_waves) + kWave - 1) & ~(uint32_t)(kWave - 1);
     const uint32_t q_begin = wave * share;
     const uint32_t q_end = min(q_begin + share, n_quads);
-    for (uint32_t q0 = q_begin; q0 < q_end; q0 += kWave) {
+    const uint32_t b_span = X0 - X1;
+    auto step = [&](uint32_t q0, auto tail) {
+      constexpr bool kTail = decltype(tail)::value;
       const uint32_t q = q0 + lane;
       uint32_t x[4];
       philox4x32_10(q, pk, x);
@@ -1148,7 +1163,8 @@ __device__ __forceinline__ void hub_scan(const SampleArgs<IdxT>& a, const NodeRe
       uint64_t mk[4];
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        pass[w] = (4u * q + (uint32_t)w < deg) && (x[w] >= X0);
+        pass[w] = x[w] >= X0;
+        if (kTail) pass[w] = pass[w] && (4u * q + (uint32_t)w < deg);
         mk[w] = __ballot(pass[w]);
       }
       if (mk[0] | mk[1] | mk[2] | mk[3]) {
@@ -1167,7 +1183,8 @@ __device__ __forceinline__ void hub_scan(const SampleArgs<IdxT>& a, const NodeRe
         uint64_t mb[4];
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-          pb[w] = (4u * q + (uint32_t)w < deg) && (x[w] >= X1) && (x[w] < X0);
+          pb[w] = (x[w] - X1) < b_span;
+          if (kTail) pb[w] = pb[w] && (4u * q + (uint32_t)w < deg);
           mb[w] = __ballot(pb[w]);
         }
         if (mb[0] | mb[1] | mb[2] | mb[3]) {
@@ -1185,7 +1202,12 @@ __device__ __forceinline__ void hub_scan(const SampleArgs<IdxT>& a, const NodeRe
           }
         }
       }
-    }
+    };
+    // steps that lie wholly inside the row need no range test (see sample_node_wave)
+    const uint32_t whole_steps_end = min(q_end, (deg >> 2) & ~(uint32_t)(kWave - 1));
+    uint32_t q0 = q_begin;
+    for (; q0 < whole_steps_end; q0 += kWave) step(q0, std::false_type{});
+    for (; q0 < q_end; q0 += kWave) step(q0, std::true_type{});
   }
   if (lane == 0) counts[wave] = mine;
   __syncthreads();
