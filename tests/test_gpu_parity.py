@@ -84,6 +84,23 @@ def test_weighted_candidate_lists_of_every_size():
     ctx.close()
 
 
+def test_largest_fanouts():
+    """fanouts up to the library's maximum (1024): candidate lists beyond the register paths,
+    several chosen slots per lane, fewer wavefronts per workgroup for lack of LDS"""
+    g = make_graph(20_000, 700.0, 40, 12_000, 2.1, True, 5, torch.int32)
+    deg = (g.indptr[1:] - g.indptr[:-1]).numpy()
+    d_ip, d_ix = g.indptr.to(DEV), g.indices.to(DEV)
+    w = get_config("mini_social")
+    order = np.argsort(-deg, kind="stable")
+    seeds = np.concatenate([order[:6], order[3000:3006], order[-4:]]).astype(np.int32)
+    cm = degree_ranked_cache(g, None, 0.5).cache_map.numpy()
+    for fan in ([a3.A3_MAX_FANOUT], [200, 3], [65, 64], [500, 1]):
+        ctx = a3.Context(len(seeds), fan)
+        for gamma in (1.0, 4.0):
+            _compare(ctx, w, g, d_ip, d_ix, seeds, fan, cm, gamma, 31, "large fanout")
+        ctx.close()
+
+
 def test_exhaustive_selection_path_matches_oracle():
     for name in ["tiny", "mini_copurchase"]:
         w, g, d_ip, d_ix = _graph(name)
