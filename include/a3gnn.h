@@ -38,7 +38,7 @@ extern "C" {
 
 #define A3_OK 0
 #define A3_ERR_INVALID_ARG (-1) /* null required pointer, bad width, fanout < 1, gamma < 1, ... */
-#define A3_ERR_CAPACITY (-2)    /* request exceeds what the context was created for */
+#define A3_ERR_CAPACITY (-2)    /* request exceeds what the context was created for, or what one call can take */
 #define A3_ERR_HIP (-3)         /* HIP runtime failure, or no usable device */
 #define A3_ERR_INPUT (-4)       /* A3_VALIDATE found seeds out of range or repeated */
 
@@ -132,7 +132,8 @@ int a3_sample_blocks_end(a3_ctx* ctx, a3_blocks* out);
  *   ids         device, idx_bytes wide, [n_ids] (typically a3_blocks.input_nodes).
  *   row_bytes   > 0, multiple of 2.
  *   out         device [n_ids, row_bytes], caller-allocated.
- * Rows are copied byte for byte.  Asynchronous on the context's stream.
+ * Rows are copied byte for byte.  Asynchronous on the context's stream.  At most 2^26 rows per
+ * call (A3_ERR_CAPACITY beyond; split the call).
  * A needed store that is NULL is reported as A3_ERR_INVALID_ARG only when it
  * can be known on the host (both NULL); otherwise behaviour is undefined. */
 int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
@@ -176,7 +177,8 @@ int a3_gather_input_features_strided(a3_ctx* ctx, const void* feat_dev, int64_t 
  *                for the outermost hop these are the rows a3_gather_input_features wrote.
  *   out          device [n_dst, dim], same type as x, caller-allocated.
  * Sums are taken in fp32 in edge order, then divided by the edge count and rounded once to the
- * output type.  Asynchronous on the context's stream.  Errors: A3_ERR_INVALID_ARG, A3_ERR_HIP. */
+ * output type.  Asynchronous on the context's stream.  Errors: A3_ERR_INVALID_ARG, A3_ERR_HIP,
+ * A3_ERR_CAPACITY (more than 2^26 destinations in one call). */
 #define A3_F32 0
 #define A3_F16 1
 int a3_block_mean(a3_ctx* ctx, const int32_t* blk_indptr, const int32_t* blk_indices, int64_t n_dst,

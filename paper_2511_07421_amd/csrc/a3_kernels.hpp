@@ -145,9 +145,10 @@ __device__ __forceinline__ uint32_t tile_prefix_to_lds(const int32_t* tile_sums,
 // ---------------------------------------------------------------------------
 // small utility kernels
 // ---------------------------------------------------------------------------
+// n may exceed what one launch can give a thread each (2^32 threads): the grid strides
 __global__ void k_fill_i32(int32_t* p, int64_t n, int32_t value) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = value;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = value;
 }
 
 // A3_VALIDATE only: seeds -> S with range and uniqueness checks; a bad batch empties the frontier

@@ -103,6 +103,10 @@ int dev_alloc(a3_ctx* ctx, T** p, int64_t count) {
   return A3_OK;
 }
 
+// One launch holds fewer than 2^32 threads: kernels that give every row a group of lanes refuse
+// more rows than that in one call (the caller splits the call).
+inline bool too_many_threads(int64_t threads) { return threads >= (1ll << 32) - 1024; }
+
 inline unsigned blocks_for(int64_t n, int per_block) {
   return (unsigned)std::max<int64_t>(1, (n + per_block - 1) / per_block);
 }
@@ -194,7 +198,7 @@ int ensure_node_map(a3_ctx* ctx, int64_t num_nodes) {
     ctx->node_map_dirty = true;
   }
   if (ctx->node_map_dirty) {
-    hipLaunchKernelGGL(a3::k_fill_i32, dim3(blocks_for(ctx->node_map_cap, 256)), dim3(256), 0,
+    hipLaunchKernelGGL(a3::k_fill_i32, dim3(std::min(blocks_for(ctx->node_map_cap, 256), 1u << 20)), dim3(256), 0,
                        ctx->stream, ctx->node_map, ctx->node_map_cap, a3::kMapEmpty);
     A3_HIP(ctx, hipGetLastError());
     ctx->node_map_dirty = false;
@@ -487,6 +491,8 @@ int gather_enqueue(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
   const int width = pick_copy_width(row_bytes, ptrs, strides, 3, 2, &copy_bytes);
   if (width == 0)
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: buffers and strides must be 2-byte aligned");
+  if (too_many_threads(n_ids * 64))
+    return fail(ctx, A3_ERR_CAPACITY, "a3_gather_features: more than 2^26 rows in one call");
   prof_mark(ctx, 1, 0);
   if (idx_bytes == 4)
     gather_by_width<int32_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, st, copy_bytes, out);
@@ -529,6 +535,8 @@ int block_mean_enqueue(a3_ctx* ctx, const int32_t* indptr, const int32_t* indice
   const int64_t width = pick_copy_width(dim * elem, ptrs, strides, 2, elem, &copy_bytes);
   if (width == 0)
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_block_mean: buffers and strides must be aligned to the element type");
+  if (too_many_threads(n_dst * 64))
+    return fail(ctx, A3_ERR_CAPACITY, "a3_block_mean: more than 2^26 destinations in one call");
   prof_mark(ctx, 2, 0);
 #define A3_MEAN_AS(T, VW) \
   launch_block_mean<T, VW>(ctx, indptr, indices, n_dst, n_dst_dev, n_src, n_src_dev, x, x_stride, copy_bytes, out, out_stride)
@@ -958,6 +966,8 @@ extern "C" int a3_cache_count_accesses(a3_ctx* ctx, const void* ids, int32_t idx
   if (ctx->flags & A3_HOST_ONLY)
     return fail(ctx, A3_ERR_HIP, "a3_cache_count_accesses: context was created without a device");
   if (n_ids == 0) return A3_OK;
+  if (too_many_threads(n_ids))
+    return fail(ctx, A3_ERR_CAPACITY, "a3_cache_count_accesses: more than 2^32 ids in one call");
   A3_HIP(ctx, hipSetDevice(ctx->device));
   const unsigned blocks = blocks_for(n_ids, a3::kTileThreads);
   if (idx_bytes == 4)
@@ -1065,6 +1075,8 @@ extern "C" int a3_cache_fifo_update(a3_ctx* ctx, int32_t* cache_map, int64_t num
   if (align_bits & 1)
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_fifo_update: buffers must be 2-byte aligned");
   if (n_ids == 0) return A3_OK;
+  if (too_many_threads(n_ids * 64))
+    return fail(ctx, A3_ERR_CAPACITY, "a3_cache_fifo_update: more than 2^26 ids in one call");
   A3_HIP(ctx, hipSetDevice(ctx->device));
   const int64_t n_tiles = (n_ids + a3::kTile - 1) / a3::kTile;
   rc = ensure_buffer(ctx, &ctx->fifo_rank, &ctx->fifo_rank_cap, n_ids);

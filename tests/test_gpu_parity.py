@@ -101,6 +101,45 @@ def test_largest_fanouts():
         ctx.close()
 
 
+def test_node_ids_above_two_to_the_32():
+    """8-byte ids whose high word is not zero (it is part of the Philox counter): a graph of
+    2^32 + 1000 nodes, all of them isolated except a thousand around the 2^32 boundary.  The CSR
+    row starts are 34 GB on the device; on the host the array comes zero-mapped and the oracle
+    touches only the frontier's entries."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 80 << 30:
+        pytest.skip("needs 80 GB of free device memory")
+    N = (1 << 32) + 1000
+    lo = (1 << 32) - 500                     # nodes lo .. lo + 999 have neighbours, among themselves
+    n_act, deg = 1000, 300
+    rng = np.random.default_rng(9)
+    rows = np.stack([np.sort(rng.choice(n_act, size=deg, replace=False)) for _ in range(n_act)]) + lo
+    indices = rows.reshape(-1).astype(np.int64)
+    ip_h = np.zeros(N + 1, dtype=np.int64)   # calloc: untouched pages cost nothing
+    ip_h[lo:lo + n_act + 1] = np.arange(n_act + 1, dtype=np.int64) * deg
+    ip_h[lo + n_act:] = n_act * deg
+    d_ip = torch.zeros(N + 1, dtype=torch.int64, device=DEV)
+    d_ip[lo:lo + n_act + 1] = torch.arange(n_act + 1, dtype=torch.int64, device=DEV) * deg
+    d_ip[lo + n_act:] = n_act * deg
+    d_ix = torch.from_numpy(indices).to(DEV)
+    seeds = (lo + rng.choice(n_act, size=40, replace=False)).astype(np.int64)
+    assert (seeds >= 1 << 32).any() and (seeds < 1 << 32).any()
+    ctx = a3.Context(64, [10, 5])
+    print(f"[case] ids above 2^32: N={N} seeds={len(seeds)}", flush=True)
+    got = ctx.sample_blocks(d_ip, d_ix, torch.from_numpy(seeds).to(DEV), [10, 5], None, Q, 77).to_host()
+    want = oracle.sample_blocks(ip_h, indices, seeds, [10, 5], None, Q, 77)
+    blocks_equal(got, want)
+    assert (got.input_nodes >= 1 << 32).any()
+    # 4-byte ids cannot name these nodes: refused, not truncated
+    with pytest.raises(a3.A3Error) as ei:
+        ctx.sample_blocks(d_ip, torch.zeros(4, dtype=torch.int32, device=DEV),
+                          torch.zeros(1, dtype=torch.int32, device=DEV), [2])
+    assert ei.value.code == a3.A3_ERR_INVALID_ARG
+    ctx.close()
+    del d_ip
+    torch.cuda.empty_cache()
+
+
 def test_exhaustive_selection_path_matches_oracle():
     for name in ["tiny", "mini_copurchase"]:
         w, g, d_ip, d_ix = _graph(name)
