@@ -84,6 +84,21 @@ def test_weighted_candidate_lists_of_every_size():
     ctx.close()
 
 
+def test_one_weight_class_equals_uniform_sampling():
+    """everything cached or nothing cached: gamma has no effect (Sec. III-A: equal weights are
+    plain uniform sampling), on the oracle and on the GPU alike"""
+    w, g, d_ip, d_ix = _graph("mini_social")
+    ctx = a3.Context(128, [25, 10])
+    seeds = seed_batch(w.num_nodes, 100, 1, 3)
+    ref = _compare(ctx, w, g, d_ip, d_ix, seeds, [25, 10], None, 1.0, 4, "no map")
+    for frac in (0.0, 1.0):
+        cm = degree_ranked_cache(g, None, frac).cache_map.numpy()
+        for gamma in (1.0, 4.0, 1000.0):
+            got = _compare(ctx, w, g, d_ip, d_ix, seeds, [25, 10], cm, gamma, 4, f"one class frac={frac}")
+            blocks_equal(got, ref)
+    ctx.close()
+
+
 def test_largest_fanouts():
     """fanouts up to the library's maximum (1024): candidate lists beyond the register paths,
     several chosen slots per lane, fewer wavefronts per workgroup for lack of LDS"""
