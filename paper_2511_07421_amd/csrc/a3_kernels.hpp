@@ -31,7 +31,7 @@ constexpr int kTileShift = 10;
 
 constexpr int32_t kErrBadSeed = 1;  // seed outside [0, num_nodes)
 constexpr int32_t kErrDupSeed = 2;  // a seed appears twice
-constexpr int32_t kErrHugeRow = 4;  // a row with more than 2^31 - 1 entries
+constexpr int32_t kErrHugeRow = 4;  // a row of negative length or with more than 2^31 - 1 entries
 // an index left its array (bad ids in the inputs, or a logic error): one bit per guard
 constexpr int32_t kErrFrontierId = 8, kErrFlagId = 16, kErrFirstPosNeg = 32, kErrFirstPosLate = 64,
                   kErrNewNode = 128, kErrEmit = 256;
@@ -59,7 +59,7 @@ struct DevState {
 struct NodeRec {
   int64_t v;          // global id
   int64_t row;        // indptr[v]
-  uint32_t deg;       // degree, clipped to 2^31 - 1
+  uint32_t deg;       // degree (0 for a row that k_frontier refused)
   int32_t i;          // position in the frontier (destination id of the block)
   int32_t local_off;  // edges of earlier nodes of the same scan tile
   int32_t pad;
@@ -281,10 +281,9 @@ __global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<Id
       } else {
         atomicOr(&a.st->error, kErrFrontierId);
       }
-      if (deg < 0) deg = 0;
-      if (deg > 0x7FFFFFFF) {
-        atomicOr(&a.st->error, kErrHugeRow);
-        deg = 0x7FFFFFFF;
+      if (deg < 0 || deg > 0x7FFFFFFF) {  // not a CSR this library can sample: the call fails,
+        atomicOr(&a.st->error, kErrHugeRow);  // and the row is not touched
+        deg = 0;
       }
       cnt[k] = deg < (int64_t)a.fanout ? (uint32_t)deg : (uint32_t)a.fanout;
       bin[k] = degree_bin((uint32_t)deg);

@@ -381,7 +381,8 @@ int sample_finish(a3_ctx* ctx, a3_blocks* out) {
                                              : "a3_sample_blocks: a seed appears twice");
   }
   if (hs.error & a3::kErrHugeRow)
-    return fail(ctx, A3_ERR_CAPACITY, "a3_sample_blocks: a CSR row has more than 2^31-1 entries");
+    return fail(ctx, A3_ERR_CAPACITY,
+                "a3_sample_blocks: a CSR row has negative length or more than 2^31-1 entries");
   if (hs.error & a3::kErrInternal)
     return fail(ctx, A3_ERR_HIP,
                 "a3_sample_blocks: an index left its array (ids in indices/seeds outside the "

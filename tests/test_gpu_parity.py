@@ -84,6 +84,23 @@ def test_weighted_candidate_lists_of_every_size():
     ctx.close()
 
 
+def test_malformed_row_lengths_are_refused_not_followed():
+    """row starts that do not increase, or a row longer than 2^31-1: an error code, no sampling
+    of that row (its neighbour slots would lie outside `indices`)"""
+    indices = torch.arange(6, dtype=torch.int32, device=DEV) % 3
+    ctx = a3.Context(4, [2])
+    seeds = torch.tensor([0, 1, 2], dtype=torch.int32, device=DEV)
+    # every row START below stays inside `indices` (6 entries); only a row's LENGTH is wrong:
+    # row 1 of the first has length -2, row 2 of the second 2^32 + 5
+    for indptr in ([0, 4, 2, 6], [0, 2, 4, (1 << 32) + 9]):
+        with pytest.raises(a3.A3Error) as ei:
+            ctx.sample_blocks(torch.tensor(indptr, dtype=torch.int64, device=DEV), indices, seeds, [2])
+        assert ei.value.code == a3.A3_ERR_CAPACITY
+    ok = ctx.sample_blocks(torch.tensor([0, 2, 4, 6], dtype=torch.int64, device=DEV), indices, seeds, [2])
+    assert ok.n_edges == [6]
+    ctx.close()
+
+
 def test_one_weight_class_equals_uniform_sampling():
     """everything cached or nothing cached: gamma has no effect (Sec. III-A: equal weights are
     plain uniform sampling), on the oracle and on the GPU alike"""
