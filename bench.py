@@ -167,7 +167,7 @@ def main():
     ms_gather = sum(ms_g) * K / len(ms_g)
     # hit rate of the last timed batch (outside the timed region)
     ids_l = last_ids.long()
-    hit_rate = float((d_cm[ids_l] >= 0).float().mean().item()) if ids_l.numel() else 1.0
+    hit_rate = int((d_cm[ids_l] >= 0).sum().item()) / ids_l.numel() if ids_l.numel() else 1.0
 
     # neighbour slots the last timed batch had to draw for (nodes with degree above the fanout)
     scanned = 0
