@@ -12,6 +12,7 @@ import torch
 
 import oracle
 import paper_2511_07421_amd as a3
+from helpers import blocks_equal
 from workloads import get_config, make_graph, make_features, degree_ranked_cache, seed_batch
 
 pytestmark = pytest.mark.gpu
@@ -117,15 +118,20 @@ def test_block_mean_on_sampled_blocks(name):
     ctx.gather_input_features(fd, split.feat_host, d_cm, rows)
     ctx.block_mean_of_hop(H - 1, rows, agg)           # queued before the host knows any count
     blk = ctx.sample_blocks_end()
-    hb = blk.to_host()
     torch.cuda.synchronize()
-    x_np = rows[: blk.n_src[-1]].cpu().numpy()
-    want = oracle.block_mean(hb.blk_indptr[-1], hb.blk_indices[-1], x_np)
+    # the oracle's own chain: its blocks, its rows, its means (nothing of the GPU's feeds it)
+    ob = oracle.sample_blocks(g.indptr.numpy(), g.indices.numpy(), seeds, w.fanouts,
+                              split.cache_map.numpy(), 65536, 3)
+    blocks_equal(blk.to_host(), ob)
+    x_np = oracle.gather_features(split.feat_dev.numpy(),
+                                  None if split.feat_host is None else split.feat_host.numpy(),
+                                  split.cache_map.numpy(), ob.input_nodes)
+    want = oracle.block_mean(ob.blk_indptr[-1], ob.blk_indices[-1], x_np)
     got = agg[: blk.n_dst[-1]].cpu().numpy().astype(np.float64)
-    tol = _bound(hb.blk_indptr[-1], hb.blk_indices[-1], x_np, want, x_np.dtype == np.float16)
+    tol = _bound(ob.blk_indptr[-1], ob.blk_indices[-1], x_np, want, x_np.dtype == np.float16)
     assert np.all(np.abs(got - want) <= tol)
     assert torch.all(agg[blk.n_dst[-1]:] == 7.0)      # rows past n_dst are not written
     # inner blocks through the explicit entry point
     for h in range(H - 1):
-        _check(ctx, hb.blk_indptr[h], hb.blk_indices[h], x_np[: blk.n_src[h]], f"{name} hop {h}")
+        _check(ctx, ob.blk_indptr[h], ob.blk_indices[h], x_np[: ob.n_src[h]], f"{name} hop {h}")
     ctx.close()

@@ -104,7 +104,12 @@ def _run(name, gammas, check_rows, n_batches=1, full_hops=None):
                 t2 = time.time()
                 print(f"[time] gpu {t1 - t0:.3f}s oracle+checks {t2 - t1:.1f}s edges={got.n_edges} "
                       f"n_src={got.n_src}", flush=True)
-                ids = got.input_nodes.astype(np.int64)
+                # the oracle did not produce this hop's input nodes, so nothing of them goes to it:
+                # sampled rows are compared with the generator's table by plain indexing
+                gi = torch.from_numpy(np.unique(np.linspace(0, got.n_src[-1] - 1, check_rows).astype(np.int64))).to(DEV)
+                ids_d = got_d.input_nodes.long()[gi]
+                assert torch.equal(rows[gi], full[ids_d])
+                continue
             # gathered rows: every row against the generator's table through the split, via the oracle
             if check_rows < ids.shape[0]:
                 pick = np.unique(np.linspace(0, ids.shape[0] - 1, check_rows).astype(np.int64))

@@ -75,23 +75,26 @@ def test_strided_block_mean_and_device_count_path(world, dim, dtype, align):
     ctx.gather_input_features(d_fd, None, d_cm, rows)
     ctx.block_mean_of_hop(H - 1, rows, agg)
     blk = ctx.sample_blocks_end()
-    hb = blk.to_host()
     torch.cuda.synchronize()
-    n_in, n_dst = blk.n_src[-1], blk.n_dst[-1]
-    x_np = rows[:n_in].cpu().numpy()
-    assert x_np.tobytes() == full[torch.from_numpy(hb.input_nodes).long()].numpy().tobytes()
-    want = oracle.block_mean(hb.blk_indptr[-1], hb.blk_indices[-1], np.ascontiguousarray(x_np))
+    # the oracle's own chain (packed rows; it knows nothing of padding)
+    ob = oracle.sample_blocks(g.indptr.numpy(), g.indices.numpy(), seeds, w.fanouts,
+                              split.cache_map.numpy(), Q, 5)
+    blocks_equal(blk.to_host(), ob)
+    n_in, n_dst = ob.n_src[-1], ob.n_dst[-1]
+    x_np = oracle.gather_features(np.ascontiguousarray(split.feat_dev.numpy()), None,
+                                  split.cache_map.numpy(), ob.input_nodes)
+    assert rows[:n_in].cpu().numpy().tobytes() == x_np.tobytes()
+    want = oracle.block_mean(ob.blk_indptr[-1], ob.blk_indices[-1], x_np)
     got = agg[:n_dst].cpu().numpy().astype(np.float64)
-    mean_abs = oracle.block_mean(hb.blk_indptr[-1], hb.blk_indices[-1],
-                                 np.abs(np.ascontiguousarray(x_np).astype(np.float32)))
-    d = np.diff(hb.blk_indptr[-1]).astype(np.float64)[:, None]
+    mean_abs = oracle.block_mean(ob.blk_indptr[-1], ob.blk_indices[-1], np.abs(x_np.astype(np.float32)))
+    d = np.diff(ob.blk_indptr[-1]).astype(np.float64)[:, None]
     tol = (d + 1) * 2.0 ** -24 * mean_abs * 1.0000001
     if dtype == torch.float16:
         tol = tol + 2.0 ** -11 * np.abs(want) + 2.0 ** -25
     assert np.all(np.abs(got - want) <= tol)
     # explicit entry point: padded x into a packed result
     got2 = ctx.block_mean(blk.blk_indptr[0], blk.blk_indices[0], rows[: blk.n_src[0]])
-    want2 = oracle.block_mean(hb.blk_indptr[0], hb.blk_indices[0], np.ascontiguousarray(x_np[: blk.n_src[0]]))
+    want2 = oracle.block_mean(ob.blk_indptr[0], ob.blk_indices[0], x_np[: ob.n_src[0]])
     np.testing.assert_allclose(got2.cpu().numpy().astype(np.float64), want2, rtol=2e-3, atol=2e-3)
     ctx.close()
 
