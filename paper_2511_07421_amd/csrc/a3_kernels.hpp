@@ -1251,8 +1251,9 @@ __device__ __forceinline__ void run_group_role(const SampleArgs<IdxT>& a, const 
 
 constexpr int kSampleMaxThreads = 256;
 
-// Workgroups take roles by index: role_blocks[0..2] serve the small-degree bins with lane groups,
-// role_blocks[3] the wide nodes (one wavefront each), role_blocks[4] the hubs (one workgroup each).
+// Workgroups take roles by index: the first role_blocks[4] serve the hubs (one workgroup each), the
+// next role_blocks[3] the wide nodes (one wavefront each), then role_blocks[2], [1], [0] the
+// small-degree bins with lane groups of 16, 8, 4.
 template <typename IdxT, bool kWeighted>
 __global__ __launch_bounds__(kSampleMaxThreads) void k_sample(const SampleArgs<IdxT> a) {
   extern __shared__ uint64_t lds[];
@@ -1269,21 +1270,28 @@ __global__ __launch_bounds__(kSampleMaxThreads) void k_sample(const SampleArgs<I
       a.blk_indptr[n_dst] = (int32_t)total;
     }
   }
+  // Workgroups start in index order, so the roles with the longest-running workgroups come
+  // first (hubs, then wide nodes) and the short ones of the small-degree bins fill the end of the
+  // launch; the other way round the hubs would start last and the launch end with their tail.
   uint32_t b = blockIdx.x;
-  if (b < a.role_blocks[0]) return run_group_role<IdxT, 4, kWeighted>(a, tile_offs, 0, b, a.role_blocks[0], n_dst);
-  b -= a.role_blocks[0];
-  if (b < a.role_blocks[1]) return run_group_role<IdxT, 8, kWeighted>(a, tile_offs, 1, b, a.role_blocks[1], n_dst);
-  b -= a.role_blocks[1];
-  if (b < a.role_blocks[2]) return run_group_role<IdxT, 16, kWeighted>(a, tile_offs, 2, b, a.role_blocks[2], n_dst);
-  b -= a.role_blocks[2];
+  const bool hub_role = b < a.role_blocks[4];  // the same for the whole workgroup
+  if (!hub_role) {
+    b -= a.role_blocks[4];
+    if (b >= a.role_blocks[3]) {
+      b -= a.role_blocks[3];
+      if (b < a.role_blocks[2]) return run_group_role<IdxT, 16, kWeighted>(a, tile_offs, 2, b, a.role_blocks[2], n_dst);
+      b -= a.role_blocks[2];
+      if (b < a.role_blocks[1]) return run_group_role<IdxT, 8, kWeighted>(a, tile_offs, 1, b, a.role_blocks[1], n_dst);
+      b -= a.role_blocks[1];
+      return run_group_role<IdxT, 4, kWeighted>(a, tile_offs, 0, b, a.role_blocks[0], n_dst);
+    }
+  }
   // the wavefront's index inside the workgroup, held in a scalar register so that the node loops
   // below are uniform control flow for the whole wavefront
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(threadIdx.x >> 6));
   const uint32_t n_waves = blockDim.x >> 6;
   // wide nodes and hubs share one loop (and one copy of the selection code): a wavefront takes a
   // wide node by itself; a hub is scanned by the whole workgroup and finished by wavefront 0
-  const bool hub_role = b >= a.role_blocks[3];  // the same for the whole workgroup
-  if (hub_role) b -= a.role_blocks[3];
   const int bin = hub_role ? 4 : 3;
   const int64_t n_nodes = a.st->bin_count[bin];
   const NodeRec* recs = a.bins[bin];
