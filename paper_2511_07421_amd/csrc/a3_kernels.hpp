@@ -49,6 +49,7 @@ struct DevState {
   int32_t n_edges[kMaxHops];
   int32_t error;
   int32_t n_radix;  // nodes that went through the exhaustive selection path
+  int32_t class_mix;  // weighted calls: bit 0 some node is cached, bit 1 some node is not
   // scratch of the running hop; zero between hops and between calls
   int32_t bin_count[kNumBins];
 };
@@ -191,6 +192,7 @@ __global__ void k_finish_call(const IdxT* S, DevState* st, int last_hop, int64_t
     *host_state = *st;
     st->error = 0;
     st->n_radix = 0;
+    st->class_mix = 0;
   }
   if (i >= n) return;
   const int64_t v = (int64_t)S[i];
@@ -201,24 +203,56 @@ __global__ void k_finish_call(const IdxT* S, DevState* st, int last_hop, int64_t
 // step a1: frontier degrees -> edge offsets, degree bins
 // ---------------------------------------------------------------------------
 // One bit per node from the device map: bit u of the bitmap = (cache_map[u] >= 0).  A wavefront
-// turns 64 consecutive entries into one 64-bit word with a ballot.
+// turns 64 consecutive entries into one 64-bit word with a ballot.  Each workgroup also notes
+// whether it met cached nodes (bit 0) and uncached ones (bit 1); k_class_mix folds the notes:
+// with one class only (everything or nothing cached) all weights are equal and the sampler takes
+// the uniform path whatever the bias rate.
 __global__ __launch_bounds__(kTileThreads) void k_cached_bits(const int32_t* __restrict__ cache_map,
-                                                             int64_t num_nodes, uint64_t* __restrict__ bits) {
+                                                             int64_t num_nodes, uint64_t* __restrict__ bits,
+                                                             int32_t* __restrict__ block_seen) {
+  __shared__ uint32_t seen_lds[kTileThreads / kWave];
   const int64_t n_words = (num_nodes + 63) >> 6;
   const int64_t n_waves = (int64_t)gridDim.x * (kTileThreads / kWave);
   const uint32_t lane = lane_id();
+  uint32_t seen = 0;  // same value in every lane of the wavefront
   for (int64_t w0 = ((int64_t)blockIdx.x * kTileThreads + threadIdx.x) >> 6; w0 < n_words; w0 += 4 * n_waves) {
     int32_t c[4];
+    bool valid[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int64_t u = ((w0 + k * n_waves) << 6) + lane;
-      c[k] = u < num_nodes ? cache_map[u] : -1;
+      valid[k] = u < num_nodes;
+      c[k] = valid[k] ? cache_map[u] : -1;
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const uint64_t word = __ballot(c[k] >= 0);
+      const uint64_t in_range = __ballot(valid[k]);
+      seen |= (word ? 1u : 0u) | ((in_range & ~word) ? 2u : 0u);
       if (lane == 0 && w0 + k * n_waves < n_words) bits[w0 + k * n_waves] = word;
     }
+  }
+  if (lane == 0) seen_lds[threadIdx.x >> 6] = seen;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t all = 0;
+    for (int w = 0; w < kTileThreads / kWave; ++w) all |= seen_lds[w];
+    block_seen[blockIdx.x] = (int32_t)all;
+  }
+}
+
+__global__ __launch_bounds__(kTileThreads) void k_class_mix(const int32_t* __restrict__ block_seen, int n_blocks,
+                                                           DevState* st) {
+  __shared__ uint32_t seen_lds[kTileThreads / kWave];
+  uint32_t seen = 0;
+  for (int b = threadIdx.x; b < n_blocks; b += kTileThreads) seen |= (uint32_t)block_seen[b];
+  const uint32_t wave_seen = (__ballot(seen & 1u) ? 1u : 0u) | (__ballot(seen & 2u) ? 2u : 0u);
+  if (lane_id() == 0) seen_lds[threadIdx.x >> 6] = wave_seen;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t all = 0;
+    for (int w = 0; w < kTileThreads / kWave; ++w) all |= seen_lds[w];
+    st->class_mix = (int32_t)all;
   }
 }
 
@@ -807,7 +841,9 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
   // a cached slot, so that the row need not be scanned again
   uint64_t* list_b = rest + 4 * (size_t)m + 2 * (size_t)a.xcap;  // [capb]
   uint32_t cnt_b = pre_cnt_b;
-  const bool want_b = kWeighted && a.capb > 0;
+  // with one weight class in the whole graph the weighted kernel takes the uniform path
+  const bool two_classes = kWeighted && a.st->class_mix == 3;
+  const bool want_b = two_classes && a.capb > 0;
   const uint32_t X1 = want_b ? second_list_floor(keep, a.bias_q16) : 0u;
   if (!a.force_radix && !prefiltered) {
     // One step: 64 quads = 256 slots.  Only the last step of a row can hold slots past its end,
@@ -869,7 +905,7 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
   }
   // the lists can replace the second scan if both are complete
   const bool lists_ok = want_b && !a.force_radix && cnt >= m && cnt <= a.cap && cnt_b <= a.capb;
-  if (kWeighted && lists_ok) {
+  if (two_classes && lists_ok) {
     uint64_t* E = rest + 4 * (size_t)m;  // [2 xcap], the challenger buffers of the rescanning path
     if (weighted_from_lists<IdxT>(a, row, cand, cnt, list_b, cnt_b, m, E, 2 * a.xcap, rest, emit)) {
       wave_sync();
@@ -879,7 +915,7 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
   if (!a.force_radix && cnt >= m && cnt <= a.cap && cnt <= 4 * kWave) {
     // the usual case: few candidates, selected in registers.  With equal weights the winners
     // are final and are written out at once; otherwise they become the first reservoir.
-    constexpr bool final_now = !kWeighted;
+    const bool final_now = !two_classes;
     auto take = [&](uint32_t pos, uint64_t key) {
       if (final_now)
         emit(pos, (uint32_t)key);
@@ -909,7 +945,7 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
   }
   wave_sync();
 
-  if (!kWeighted) {
+  if (!two_classes) {
     // all weights equal: the m largest draws are the answer; emit in slot order
     for (uint32_t j = lane; j < m; j += kWave) {
       const uint32_t s = (uint32_t)selk[j];
@@ -1032,7 +1068,7 @@ __device__ void sample_node_group(const SampleArgs<IdxT>& a, const int32_t* tile
 #pragma unroll
   for (int w = 0; w < 4; ++w) alive |= (4u * gl + w < deg) ? (1u << w) : 0u;
   uint64_t K[4] = {0, 0, 0, 0};
-  if (kWeighted) {
+  if (kWeighted && a.st->class_mix == 3) {
     bool cached[4];
     bool any_c = false, any_u = false;
 #pragma unroll
@@ -1132,7 +1168,7 @@ __device__ __forceinline__ void hub_scan(const SampleArgs<IdxT>& a, const NodeRe
   // the second candidate list of the weighted case is shared: wavefronts reserve space in it
   // with one LDS atomic per append (its order does not matter)
   uint64_t* list_b = rest + 4 * (size_t)a.fanout + 2 * (size_t)a.xcap;
-  const bool want_b = kWeighted && a.capb > 0;
+  const bool want_b = kWeighted && a.capb > 0 && a.st->class_mix == 3;
   if (want_b) {
     if (threadIdx.x == 0) *shared_cnt_b = 0;
     __syncthreads();

@@ -45,6 +45,7 @@ struct a3_ctx {
   int64_t node_map_cap = 0;
   uint64_t* cached_bits = nullptr;  // one bit per node, rebuilt from the device map by every weighted call
   int64_t cached_bits_words = 0;
+  int32_t* block_seen = nullptr;  // per workgroup of k_cached_bits: which weight classes it met
   bool node_map_dirty = false;
   int32_t* fifo_rank = nullptr;   // FIFO update: per id, rank among its tile's misses (grown on demand)
   int64_t fifo_rank_cap = 0;
@@ -206,6 +207,8 @@ int ensure_node_map(a3_ctx* ctx, int64_t num_nodes) {
   return A3_OK;
 }
 
+constexpr int64_t kCachedBitsBlocks = 2048;
+
 // The bitmap of cached nodes that the weighted kernels look up, rebuilt from the caller's device
 // map on every call (one streaming pass over 4 bytes per node; the map may have changed).
 int build_cached_bits(a3_ctx* ctx, const int32_t* cache_map, int64_t num_nodes) {
@@ -224,9 +227,11 @@ int build_cached_bits(a3_ctx* ctx, const int32_t* cache_map, int64_t num_nodes) 
   }
   if (words == 0) return A3_OK;
   // a wavefront makes four words per round; 2048 workgroups at most
-  const unsigned blocks = (unsigned)std::min<int64_t>((words + 15) / 16, 2048);
+  const unsigned blocks = (unsigned)std::min<int64_t>((words + 15) / 16, kCachedBitsBlocks);
   hipLaunchKernelGGL(a3::k_cached_bits, dim3(blocks), dim3(a3::kTileThreads), 0, ctx->stream, cache_map,
-                     num_nodes, ctx->cached_bits);
+                     num_nodes, ctx->cached_bits, ctx->block_seen);
+  hipLaunchKernelGGL(a3::k_class_mix, dim3(1), dim3(a3::kTileThreads), 0, ctx->stream, ctx->block_seen,
+                     (int)blocks, ctx->d_state);
   A3_HIP(ctx, hipGetLastError());
   return A3_OK;
 }
@@ -654,6 +659,7 @@ extern "C" int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t
   chk(dev_alloc(ctx, &ctx->tile_offs2, ctx->cap_tiles));
   for (int b = 0; b < a3::kNumBins; ++b) chk(dev_alloc(ctx, &ctx->bins[b], ctx->cap_dst[max_hops - 1]));
   chk(dev_alloc(ctx, &ctx->d_state, 1));
+  chk(dev_alloc(ctx, &ctx->block_seen, kCachedBitsBlocks));
   if (rc == A3_OK) {
     static_assert(sizeof(DevState) % sizeof(int32_t) == 0, "DevState is a block of int32");
     hipLaunchKernelGGL(a3::k_fill_i32, dim3(1), dim3(256), 0, ctx->stream, (int32_t*)ctx->d_state,
