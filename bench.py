@@ -199,7 +199,10 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int32/int64 indices + byte copies of %s rows" % str(w.feat_dtype).replace("torch.", ""),
+        # the arithmetic of the path: 32-bit draws (Philox words), 64-bit integer keys; rows are copied
+        "dtype": "u32",
+        "dtype_note": "u32 draws and u64 integer keys; %d-byte ids; %s rows copied byte for byte"
+                      % (ib, str(w.feat_dtype).replace("torch.", "")),
         "data": "synthetic",
         "config": {"workload": w.name, "num_nodes": stats["num_nodes"], "nnz": stats["nnz"],
                    "mean_degree": round(stats["mean_degree"], 2), "max_degree": stats["max_degree"],
