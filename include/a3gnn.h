@@ -132,8 +132,7 @@ int a3_sample_blocks_end(a3_ctx* ctx, a3_blocks* out);
  *   ids         device, idx_bytes wide, [n_ids] (typically a3_blocks.input_nodes).
  *   row_bytes   > 0, multiple of 2.
  *   out         device [n_ids, row_bytes], caller-allocated.
- * Rows are copied byte for byte.  Asynchronous on the context's stream.  At most 2^26 rows per
- * call (A3_ERR_CAPACITY beyond; split the call).
+ * Rows are copied byte for byte.  Asynchronous on the context's stream.
  * A needed store that is NULL is reported as A3_ERR_INVALID_ARG only when it
  * can be known on the host (both NULL); otherwise behaviour is undefined. */
 int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,

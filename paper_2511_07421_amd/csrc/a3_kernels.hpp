@@ -1494,9 +1494,12 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restric
   }
   const uint32_t G = 1u << log2_g;
   const uint32_t lane = threadIdx.x & (G - 1);
-  const int64_t group = ((int64_t)blockIdx.x * kGatherThreads + threadIdx.x) >> log2_g;
+  // the grid is capped and strides over the groups of rows
+  const int64_t n_groups = (n_ids + R - 1) / R;
+  const int64_t group_step = ((int64_t)gridDim.x * kGatherThreads) >> log2_g;
+  for (int64_t group = ((int64_t)blockIdx.x * kGatherThreads + threadIdx.x) >> log2_g; group < n_groups;
+       group += group_step) {
   const int64_t r0 = group * R;
-  if (r0 >= n_ids) return;
   const VecT* src[R];
   bool live[R];
 #pragma unroll
@@ -1540,6 +1543,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restric
         }
       }
     }
+  }
   }
 }
 

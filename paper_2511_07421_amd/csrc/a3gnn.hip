@@ -410,6 +410,9 @@ int sample_finish(a3_ctx* ctx, a3_blocks* out) {
   return A3_OK;
 }
 
+// workgroups of a retrieve launch: 32 per CU
+constexpr unsigned kGatherMaxBlocks = 8192;
+
 // strides of a gather: bytes from one row to the next in the device store, the host store, the output
 struct GatherStrides {
   int64_t dev, host, out;
@@ -421,7 +424,9 @@ void launch_gather_as(a3_ctx* ctx, int log2_g, const void* feat_dev, const void*
                       const int32_t* n_ids_dev, int64_t id_limit, const GatherStrides& st, uint32_t vpr,
                       void* out) {
   const int64_t groups = (n_ids + R - 1) / R;
-  const unsigned grid = blocks_for(groups << log2_g, a3::kGatherThreads);
+  // the launch bound can be several times the real row count (it lives on the device): a capped
+  // grid strides over the rows instead of starting tens of thousands of idle workgroups
+  const unsigned grid = std::min(blocks_for(groups << log2_g, a3::kGatherThreads), kGatherMaxBlocks);
   hipLaunchKernelGGL((a3::k_gather<VecT, IdxT, U, R, kWaveRow>), dim3(grid),
                      dim3(a3::kGatherThreads), 0, ctx->stream, (const char*)feat_dev,
                      (const char*)feat_host, cache_map, (const IdxT*)ids, n_ids, n_ids_dev, id_limit,
@@ -497,8 +502,6 @@ int gather_enqueue(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
   const int width = pick_copy_width(row_bytes, ptrs, strides, 3, 2, &copy_bytes);
   if (width == 0)
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_gather_features: buffers and strides must be 2-byte aligned");
-  if (too_many_threads(n_ids * 64))
-    return fail(ctx, A3_ERR_CAPACITY, "a3_gather_features: more than 2^26 rows in one call");
   prof_mark(ctx, 1, 0);
   if (idx_bytes == 4)
     gather_by_width<int32_t>(ctx, width, feat_dev, feat_host, cache_map, ids, n_ids, n_ids_dev, id_limit, st, copy_bytes, out);
