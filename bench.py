@@ -235,6 +235,23 @@ def main():
                      "avg_launch_seconds": gather_avg_s},
     }
 
+    # what this machine's host link gives a plain copy: 256 MiB from pinned host memory to the device,
+    # by the runtime's copy engine (outside the timed region; only where rows cross the link)
+    if split.feat_host is not None and hit_rate < 1.0:
+        n_copy = 256 << 20
+        src = torch.empty(n_copy, dtype=torch.uint8, pin_memory=True)
+        dst = torch.empty(n_copy, dtype=torch.uint8, device=dev)
+        dst.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(4):
+            dst.copy_(src, non_blocking=True)
+        e1.record()
+        torch.cuda.synchronize()
+        result["pcie_plain_copy_GBps"] = 4 * n_copy / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
+
     # the step after the path: mean aggregation of the gathered rows over the outermost block
     # (a3_block_mean_of_hop), timed by the library's events on a few of the same mini-batches
     if w.feat_dtype in (torch.float32, torch.float16):
@@ -336,6 +353,34 @@ def main():
             "gather_GBps": o_rows * row_bytes / max(o_gather, 1e-9) / 1e9,
             "ms_sample": o_sample * 1e3 / done, "ms_gather": o_gather * 1e3 / done,
         }
+        # the unchanged oracle over independent mini-batches, one per thread, on the host's cores
+        # (its C code runs outside the interpreter lock); skipped where one mini-batch alone
+        # outlasts the CPU budget
+        n_thr = min(16, os.cpu_count() or 1, K - done)
+        if n_thr > 1 and spent / done <= args.cpu_seconds:
+            from concurrent.futures import ThreadPoolExecutor
+
+            def one(b):
+                ob = oracle.sample_blocks(ip_h, ix_h, seeds_h[b], w.fanouts, cm_h, bias_q16, b)
+                oracle.gather_features(fd_h, fh_h, cm_h, ob.input_nodes.astype(idx_np))
+                return sum(ob.n_edges)
+
+            seeds_h = {b: seeds[b].cpu().numpy() for b in range(W + done, W + done + n_thr)}
+            c0 = time.perf_counter()
+            with ThreadPoolExecutor(n_thr) as pool:
+                a_edges = sum(pool.map(one, sorted(seeds_h)))
+            a_s = time.perf_counter() - c0
+            model = ""
+            try:
+                with open("/proc/cpuinfo") as f:
+                    model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "")
+            except OSError:
+                pass
+            result["cpu_baseline_all_cores"] = {
+                "value": a_edges / a_s, "unit": "sampled edges/s", "cores": n_thr, "kind": "oracle",
+                "sample": "%d further timed mini-batches, one per thread, %.1f s wall" % (n_thr, a_s),
+                "cpu_model": model,
+            }
         # the same mini-batches on the library's own multi-threaded host sampler (the paper's
         # "Sampling Device = CPU, Workers = n"): sampling + reindex only, bit-identical blocks
         n_workers = min(16, os.cpu_count() or 1)
