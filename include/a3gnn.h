@@ -66,6 +66,14 @@ int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t max_seeds,
 int a3_destroy(a3_ctx* ctx);
 /* hipStream_t for subsequent calls; pending work on the old stream is waited for. */
 int a3_set_stream(a3_ctx* ctx, void* hip_stream);
+/* Tuning of the feature retrieve (Alg. 0 line 10) where both stores are given: n workgroups of
+ * each launch are set aside for the rows in host memory and the others copy the device rows.
+ * n = 0, a context's default: none are, every workgroup copies rows of both stores as they come,
+ * the fastest when the retrieve has the GPU to itself.  A small n (16 fill a PCIe 5.0 x16 link)
+ * keeps the link's requests in flight few, so that kernels running beside the retrieve on other
+ * streams are not held up behind them; pipelines with more than one worker set 16 on their
+ * contexts.  n in [0, 1024], A3_ERR_INVALID_ARG otherwise.  Results do not depend on n. */
+int a3_set_gather_host_workgroups(a3_ctx* ctx, int32_t n);
 /* Text of the last error on ctx (ctx == NULL: of the last failed a3_create in
  * this thread).  Owned by the library; valid until the next call. */
 const char* a3_last_error(const a3_ctx* ctx);
@@ -133,8 +141,8 @@ int a3_sample_blocks_end(a3_ctx* ctx, a3_blocks* out);
  *   row_bytes   > 0, multiple of 2.
  *   out         device [n_ids, row_bytes], caller-allocated.
  * Rows are copied byte for byte.  Asynchronous on the context's stream.
- * A needed store that is NULL is reported as A3_ERR_INVALID_ARG only when it
- * can be known on the host (both NULL); otherwise behaviour is undefined. */
+ * Both stores NULL is A3_ERR_INVALID_ARG; with one store NULL, the rows that map to it are not
+ * written (out keeps what it held there). */
 int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
                        const int32_t* cache_map, const void* ids, int32_t idx_bytes, int64_t n_ids,
                        int64_t row_bytes, void* out);

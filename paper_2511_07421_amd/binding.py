@@ -56,6 +56,8 @@ def lib():
         L.a3_destroy.restype = C.c_int
         L.a3_set_stream.argtypes = [C.c_void_p, C.c_void_p]
         L.a3_set_stream.restype = C.c_int
+        L.a3_set_gather_host_workgroups.argtypes = [C.c_void_p, C.c_int32]
+        L.a3_set_gather_host_workgroups.restype = C.c_int
         L.a3_last_error.argtypes = [C.c_void_p]
         L.a3_last_error.restype = C.c_char_p
         L.a3_sample_blocks.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,
@@ -259,6 +261,9 @@ class Context:
 
     def set_stream(self, stream: int):
         self._check(lib().a3_set_stream(self._h, C.c_void_p(stream)))
+
+    def set_gather_host_workgroups(self, n: int):
+        self._check(lib().a3_set_gather_host_workgroups(self._h, n))
 
     def profile_read(self, kind: int) -> List[float]:
         """device milliseconds of the calls of this kind (0 sample, 1 gather) since the last read"""

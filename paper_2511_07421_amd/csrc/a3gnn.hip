@@ -27,6 +27,7 @@ struct a3_ctx {
   int64_t cap_dst[A3_MAX_HOPS + 1] = {0};  // arena capacity per hop
   int64_t cap_edges[A3_MAX_HOPS] = {0};
   int64_t cap_tiles = 0;
+  unsigned gather_host_blocks = 0;  // workgroups of a retrieve that serve rows in host memory
 
   // arena (device)
   void* S = nullptr;  // local -> global, 8 bytes per entry reserved
@@ -412,6 +413,16 @@ int sample_finish(a3_ctx* ctx, a3_blocks* out) {
 
 // workgroups of a retrieve launch: 32 per CU
 constexpr unsigned kGatherMaxBlocks = 8192;
+// Workgroups of a retrieve launch set aside for the rows in host memory; 0 = none, every
+// workgroup copies rows of both stores as they come.  A context by itself uses 0: the device rows
+// then hide under the host link's time completely (1.01 ms for 427 k rows of 400 bytes, 26 % of
+// them in host memory; with workgroups set aside the device rows delay the link's by 0.04 ms).
+// The workers of an overlapping pipeline use 16, two per XCD, which still fill the link (43.9 of
+// 44.1 GB/s; 24 reach 42.3, 8 reach 34) with few requests in flight: with the link's requests
+// coming from every workgroup, the HBM requests of the next mini-batch's sampling queue behind
+// them and the overlap is lost (1.55 instead of 1.12 ms per step).
+constexpr unsigned kGatherHostBlocksAlone = 0;
+constexpr unsigned kGatherHostBlocksShared = 16;
 
 // strides of a gather: bytes from one row to the next in the device store, the host store, the output
 struct GatherStrides {
@@ -426,11 +437,13 @@ void launch_gather_as(a3_ctx* ctx, int log2_g, const void* feat_dev, const void*
   const int64_t groups = (n_ids + R - 1) / R;
   // the launch bound can be several times the real row count (it lives on the device): a capped
   // grid strides over the rows instead of starting tens of thousands of idle workgroups
-  const unsigned grid = std::min(blocks_for(groups << log2_g, a3::kGatherThreads), kGatherMaxBlocks);
-  hipLaunchKernelGGL((a3::k_gather<VecT, IdxT, U, R, kWaveRow>), dim3(grid),
-                     dim3(a3::kGatherThreads), 0, ctx->stream, (const char*)feat_dev,
+  const unsigned dev_blocks = std::max(1u, std::min(blocks_for(groups << log2_g, a3::kGatherThreads), kGatherMaxBlocks));
+  // with a device map and a host store, a few workgroups are set aside for the rows in host memory
+  const unsigned host_blocks = (cache_map && feat_host) ? ctx->gather_host_blocks : 0u;
+  hipLaunchKernelGGL((a3::k_gather<VecT, IdxT, U, R, kWaveRow>), dim3(dev_blocks + host_blocks),
+                     dim3(a3::kGatherThreads), host_blocks ? a3::kGatherHostLds : 0u, ctx->stream, (const char*)feat_dev,
                      (const char*)feat_host, cache_map, (const IdxT*)ids, n_ids, n_ids_dev, id_limit,
-                     vpr, st.dev, st.host, st.out, log2_g, (char*)out);
+                     vpr, st.dev, st.host, st.out, log2_g, host_blocks, (char*)out);
 }
 
 // lanes per row: the smallest power of two covering the row's vectors, at most a wavefront;
@@ -622,6 +635,7 @@ extern "C" int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t
   ctx->device = hip_device;
   ctx->stream = (hipStream_t)hip_stream;
   ctx->flags = flags;
+  ctx->gather_host_blocks = kGatherHostBlocksAlone;
   ctx->max_seeds = max_seeds;
   ctx->max_hops = max_hops;
   ctx->cap_dst[0] = max_seeds;
@@ -732,6 +746,14 @@ extern "C" int a3_set_stream(a3_ctx* ctx, void* hip_stream) {
     A3_HIP(ctx, hipStreamSynchronize(ctx->stream));
   }
   ctx->stream = (hipStream_t)hip_stream;
+  return A3_OK;
+}
+
+extern "C" int a3_set_gather_host_workgroups(a3_ctx* ctx, int32_t n) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_set_gather_host_workgroups: ctx is null");
+  if (n < 0 || n > 1024)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_set_gather_host_workgroups: n must be in [0, 1024]");
+  ctx->gather_host_blocks = (unsigned)n;
   return A3_OK;
 }
 
@@ -1213,6 +1235,7 @@ extern "C" int a3_pipeline_create(a3_pipeline** out, int hip_device, int mode, i
     }
     rc = a3_create(&p->ctx[w], hip_device, p->stream[w], max_seeds, max_hops, max_fanouts, flags);
     if (rc != A3_OK) pfail(nullptr, rc, std::string("a3_pipeline_create: ") + a3_last_error(nullptr));
+    else if (p->n > 1) p->ctx[w]->gather_host_blocks = kGatherHostBlocksShared;
   }
   if (rc == A3_OK && mode == A3_PIPE_MODE2 && !host_only) {
     hipError_t e = hipStreamCreateWithFlags(&p->batch_stream, hipStreamNonBlocking);

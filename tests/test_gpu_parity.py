@@ -249,12 +249,14 @@ def test_gather_matches_oracle(dim, dtype):
     w, g, _, _ = _graph("tiny")
     full = make_features(g.num_nodes, dim, dtype, feat_seed=2)
     ctx = a3.Context(16, [2])
-    for frac in [1.0, 0.2, 0.0]:
+    for frac, host_workgroups in [(1.0, 0), (0.2, 0), (0.2, 5), (0.0, 0)]:
+        ctx.set_gather_host_workgroups(host_workgroups)   # 5: host rows by workgroups of their own
         split = degree_ranked_cache(g, full, frac, pin_host=True)
         d_cm = split.cache_map.to(DEV)
         d_fd = None if split.feat_dev is None else split.feat_dev.to(DEV)
         for n_ids, idt in [(0, np.int32), (1, np.int64), (777, np.int32), (5000, np.int64)]:
-            print(f"[case] gather dim={dim} {dtype} frac={frac} n_ids={n_ids} idx={idt.__name__}", flush=True)
+            print(f"[case] gather dim={dim} {dtype} frac={frac} host_workgroups={host_workgroups} "
+                  f"n_ids={n_ids} idx={idt.__name__}", flush=True)
             ids = seed_batch(g.num_nodes, n_ids, 4, n_ids, dtype=idt) if n_ids else np.zeros(0, dtype=idt)
             got = ctx.gather_features(d_fd, split.feat_host, d_cm, torch.from_numpy(ids).to(DEV))
             torch.cuda.synchronize()
@@ -299,6 +301,46 @@ def test_split_call_and_device_count_gather_match_oracle():
                                            split.cache_map.numpy(), want.input_nodes[:n])
         assert out[:n].cpu().numpy().tobytes() == want_rows.tobytes()
         assert bool((out[n:] == 7.0).all()), "rows beyond the count or the capacity stay untouched"
+    ctx.close()
+
+
+@pytest.mark.parametrize("host_workgroups", [0, 16, 3])
+@pytest.mark.parametrize("dim,dtype", [(100, torch.float32), (602, torch.float32), (8, torch.float16)])
+def test_gather_partly_cached_many_rows_and_missing_stores(dim, dtype, host_workgroups):
+    """more rows than the workgroups set aside for host rows see in one round, repeated ids,
+    every cache fraction with both stores given; then a store withheld: its rows stay untouched"""
+    w, g, _, _ = _graph("tiny")
+    full = make_features(g.num_nodes, dim, dtype, feat_seed=9)
+    rng = np.random.default_rng(dim)
+    ids = rng.integers(0, g.num_nodes, size=70_001).astype(np.int32)
+    d_ids = torch.from_numpy(ids).to(DEV)
+    ctx = a3.Context(16, [2])
+    ctx.set_gather_host_workgroups(host_workgroups)
+    with pytest.raises(a3.A3Error):
+        ctx.set_gather_host_workgroups(1025)
+    spare_host = torch.zeros((1, dim), dtype=dtype).pin_memory()
+    spare_dev = torch.zeros((1, dim), dtype=dtype, device=DEV)
+    for frac in [1.0, 0.95, 0.3, 0.0]:
+        print(f"[case] gather many rows dim={dim} {dtype} frac={frac} host_workgroups={host_workgroups}", flush=True)
+        split = degree_ranked_cache(g, full, frac, pin_host=True)
+        d_cm = split.cache_map.to(DEV)
+        d_fd = spare_dev if split.feat_dev is None else split.feat_dev.to(DEV)
+        f_h = spare_host if split.feat_host is None else split.feat_host
+        got = ctx.gather_features(d_fd, f_h, d_cm, d_ids)
+        torch.cuda.synchronize()
+        fd = None if split.feat_dev is None else split.feat_dev.numpy()
+        fh = None if split.feat_host is None else split.feat_host.numpy()
+        want = oracle.gather_features(fd, fh, split.cache_map.numpy(), ids)
+        assert got.cpu().numpy().tobytes() == want.tobytes()
+        if 0.0 < frac < 1.0:
+            cached = split.cache_map.numpy()[ids] >= 0
+            for keep_dev in (True, False):
+                out = torch.full((len(ids), dim), 7.0, dtype=dtype, device=DEV)
+                ctx.gather_features(d_fd if keep_dev else None, None if keep_dev else f_h, d_cm, d_ids, out=out)
+                o = out.cpu().numpy()
+                mine = cached if keep_dev else ~cached
+                assert o[mine].tobytes() == want[mine].tobytes()
+                assert np.all(o[~mine] == 7.0)
     ctx.close()
 
 
