@@ -35,6 +35,17 @@ int a3cpu_destroy(a3cpu_sampler* s);
 int a3cpu_workers(const a3cpu_sampler* s);
 const char* a3cpu_last_error(const a3cpu_sampler* s);
 
+/* The sampler computes its draws (Philox4x32-10, the generator behind Alg. 1's random keys in
+ * this library) with the widest vector instructions the CPU has: AVX-512, AVX2 or none.  This
+ * check runs every form the CPU supports over the same counters, keys, bars and row ends and
+ * compares what they list with the scalar form's list.  Returns the number of cases that differ
+ * (0 = all forms agree); *forms_checked (may be NULL) receives how many vector forms were run. */
+int a3cpu_check_vector_forms(int* forms_checked);
+/* Which form later calls use, process-wide (not to be changed while a call runs): 0 = the widest
+ * the CPU has (the default), 1 = scalar, 2 = AVX2, 3 = AVX-512.  A3CPU_ERR_INVALID_ARG for a
+ * form this CPU lacks.  Results never depend on the form. */
+int a3cpu_set_vector_form(int form);
+
 /* Same layout and meaning as a3_blocks, arrays in host memory owned by the sampler, valid until
  * its next call or a3cpu_destroy. */
 typedef struct {

@@ -42,6 +42,10 @@ def _lib():
                                           C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_int32,
                                           C.c_void_p, C.c_uint32, C.c_uint64, C.POINTER(_CpuBlocks)]
         L.a3cpu_sample_blocks.restype = C.c_int
+        L.a3cpu_check_vector_forms.argtypes = [C.POINTER(C.c_int)]
+        L.a3cpu_check_vector_forms.restype = C.c_int
+        L.a3cpu_set_vector_form.argtypes = [C.c_int]
+        L.a3cpu_set_vector_form.restype = C.c_int
         _typed = True
     return L
 
@@ -54,6 +58,17 @@ def _copy(p, n, dtype):
     if n == 0 or not p:
         return np.zeros(0, dtype=dtype)
     return np.ctypeslib.as_array(C.cast(p, C.POINTER(np.ctypeslib.as_ctypes_type(dtype))), shape=(n,)).copy()
+
+
+def check_vector_forms():
+    """(cases in which a vector form of the draws differs from the scalar form, vector forms run)"""
+    n = C.c_int(0)
+    return _lib().a3cpu_check_vector_forms(C.byref(n)), n.value
+
+
+def set_vector_form(form: int) -> bool:
+    """0 = widest available, 1 = scalar, 2 = AVX2, 3 = AVX-512; False if this CPU lacks the form"""
+    return _lib().a3cpu_set_vector_form(form) == 0
 
 
 class CpuSampler:

@@ -39,6 +39,32 @@ def test_cpu_sampler_matches_oracle(name):
     s3.close()
 
 
+def test_vector_forms_of_the_draws_agree_with_the_scalar_form():
+    differ, forms = a3.check_vector_forms()
+    assert differ == 0
+    print(f"vector forms checked on this CPU: {forms}")
+
+
+@pytest.mark.parametrize("form", [1, 2, 3])
+def test_cpu_sampler_matches_oracle_in_every_vector_form(form):
+    """the whole sampler with its draws forced to the scalar, AVX2 and AVX-512 forms; rows longer
+    than one group of 64 slots, row ends inside a group, both weight classes"""
+    if not a3.set_vector_form(form):
+        pytest.skip("this CPU lacks the form")
+    try:
+        w, g, ip, ix = _graph("mini_social")
+        cm = degree_ranked_cache(g, None, 0.3).cache_map.numpy()
+        s2 = a3.CpuSampler(2)
+        for gamma, fan in ((1.0, w.fanouts), (4.0, w.fanouts), (1.0, [31, 2]), (8.0, [1, 40])):
+            seeds = seed_batch(w.num_nodes, 48, 0, 5, dtype=ix.dtype)
+            got = s2.sample_blocks(ip, ix, seeds, fan, cm, int(gamma * Q), 11)
+            want = oracle.sample_blocks(ip, ix, seeds, fan, cm, int(gamma * Q), 11)
+            blocks_equal(got, want)
+        s2.close()
+    finally:
+        assert a3.set_vector_form(0)
+
+
 def test_result_does_not_depend_on_the_number_of_workers():
     w, g, ip, ix = _graph("mini_social")
     cm = degree_ranked_cache(g, None, 0.5).cache_map.numpy()
