@@ -45,6 +45,13 @@ int a3cpu_check_vector_forms(int* forms_checked);
  * the CPU has (the default), 1 = scalar, 2 = AVX2, 3 = AVX-512.  A3CPU_ERR_INVALID_ARG for a
  * form this CPU lacks.  Results never depend on the form. */
 int a3cpu_set_vector_form(int form);
+/* With one weight class a row is scanned once against a fixed bar that about 2 m + 12 of its draws
+ * clear (m = fanout), and a second time with running bars in the rare case that fewer than m did.
+ * This sets the first bar's expected count to `percent` of 2 m + 12, process-wide (default 100;
+ * not to be changed while a call runs): larger values make the second scan rarer still, small
+ * ones frequent, which is how the tests reach it.  percent in [1, 10000].  Results never depend
+ * on it. */
+int a3cpu_set_first_bar_percent(int percent);
 
 /* Same layout and meaning as a3_blocks, arrays in host memory owned by the sampler, valid until
  * its next call or a3cpu_destroy. */

@@ -10,4 +10,6 @@ from .binding import (  # noqa: F401
     A3_OK, A3_ERR_INVALID_ARG, A3_ERR_CAPACITY, A3_ERR_HIP, A3_ERR_INPUT,
     A3_VALIDATE, A3_NO_EIDS, A3_HOST_ONLY, A3_FORCE_RADIX, A3_PROFILE, A3_PROFILE_DEPTH, A3_MAX_HOPS, A3_MAX_FANOUT,
 )
-from .cpu_sampler import CpuSampler, check_vector_forms, set_vector_form  # noqa: F401
+from .cpu_sampler import (  # noqa: F401
+    CpuSampler, check_vector_forms, set_vector_form, set_first_bar_percent,
+)

@@ -46,6 +46,8 @@ def _lib():
         L.a3cpu_check_vector_forms.restype = C.c_int
         L.a3cpu_set_vector_form.argtypes = [C.c_int]
         L.a3cpu_set_vector_form.restype = C.c_int
+        L.a3cpu_set_first_bar_percent.argtypes = [C.c_int]
+        L.a3cpu_set_first_bar_percent.restype = C.c_int
         _typed = True
     return L
 
@@ -69,6 +71,11 @@ def check_vector_forms():
 def set_vector_form(form: int) -> bool:
     """0 = widest available, 1 = scalar, 2 = AVX2, 3 = AVX-512; False if this CPU lacks the form"""
     return _lib().a3cpu_set_vector_form(form) == 0
+
+
+def set_first_bar_percent(percent: int) -> bool:
+    """expected number of draws that clear the one-class scan's fixed bar, in percent of 2 m + 12"""
+    return _lib().a3cpu_set_first_bar_percent(percent) == 0
 
 
 class CpuSampler:

@@ -218,6 +218,9 @@ PhiloxGroupFn philox_group_form(int form) {
 
 PhiloxGroupFn philox_group = philox_group_form(0);
 
+// how many draws of a row the fixed bar of the one-class scan lets through, in percent of 2 m + 12
+int first_bar_percent = 100;
+
 // log2(U) for U in [1, 2^32] as Q6.32: shift-and-square on a Q1.31 mantissa, truncated products
 inline uint64_t log2_q32(uint64_t U) {
   int e = 63 - __builtin_clzll(U);
@@ -303,7 +306,7 @@ void select_node(const Graph<IdxT>& g, int64_t v, uint32_t hop, uint32_t fanout,
     // One class: any bar that lets at least m draws through gives the same answer.  Try one that
     // about 2 m + 12 draws of the row clear (fewer than m do so about once in 10^5 rows at m = 10,
     // less often for larger m); then the row is scanned once with a fixed bar and no trimming.
-    const double expect = 2.0 * m + 12.0;
+    const double expect = (2.0 * m + 12.0) * first_bar_percent / 100.0;
     if ((double)deg > 2.0 * expect) {
       const uint32_t x_try = (uint32_t)(4294967296.0 * (1.0 - expect / (double)deg));
       for (uint64_t s0 = 0; s0 < deg; s0 += kGroupSlots) {
@@ -607,6 +610,13 @@ extern "C" int a3cpu_set_vector_form(int form) {
   const PhiloxGroupFn fn = (form >= 0 && form <= 3) ? philox_group_form(form) : nullptr;
   if (!fn) return fail(nullptr, A3CPU_ERR_INVALID_ARG, "a3cpu_set_vector_form: no such form on this CPU");
   philox_group = fn;
+  return A3CPU_OK;
+}
+
+extern "C" int a3cpu_set_first_bar_percent(int percent) {
+  if (percent < 1 || percent > 10000)
+    return fail(nullptr, A3CPU_ERR_INVALID_ARG, "a3cpu_set_first_bar_percent: percent must be in [1, 10000]");
+  first_bar_percent = percent;
   return A3CPU_OK;
 }
 

@@ -65,6 +65,24 @@ def test_cpu_sampler_matches_oracle_in_every_vector_form(form):
         assert a3.set_vector_form(0)
 
 
+@pytest.mark.parametrize("percent", [1, 30, 60, 10000])
+def test_one_class_scan_with_too_few_and_too_many_survivors(percent):
+    """a first bar that far too few draws clear (the second scan takes over: always at 1 %, for
+    part of the rows at 30 and 60 %), and one that everything clears"""
+    assert not a3.set_first_bar_percent(0)
+    assert a3.set_first_bar_percent(percent)
+    try:
+        w, g, ip, ix = _graph("mini_social")
+        s2 = a3.CpuSampler(2)
+        for fan in ([25, 10], [1, 3], [64]):
+            seeds = seed_batch(w.num_nodes, 64, 2, 7, dtype=ix.dtype)
+            blocks_equal(s2.sample_blocks(ip, ix, seeds, fan, None, Q, 3),
+                         oracle.sample_blocks(ip, ix, seeds, fan, None, Q, 3))
+        s2.close()
+    finally:
+        assert a3.set_first_bar_percent(100)
+
+
 def test_result_does_not_depend_on_the_number_of_workers():
     w, g, ip, ix = _graph("mini_social")
     cm = degree_ranked_cache(g, None, 0.5).cache_map.numpy()
