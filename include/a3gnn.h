@@ -40,10 +40,11 @@ extern "C" {
 #define A3_ERR_INVALID_ARG (-1) /* null required pointer, bad width, fanout < 1, gamma < 1, ... */
 #define A3_ERR_CAPACITY (-2)    /* request exceeds what the context was created for, or what one call can take */
 #define A3_ERR_HIP (-3)         /* HIP runtime failure, or no usable device */
-#define A3_ERR_INPUT (-4)       /* A3_VALIDATE found seeds out of range or repeated */
+#define A3_ERR_INPUT (-4)       /* A3_VALIDATE or an a3_validate_* call found the input malformed */
 
 /* a3_create flags */
-#define A3_VALIDATE 1u       /* check seeds (range, uniqueness) on the device before sampling */
+#define A3_VALIDATE 1u       /* check seeds (range, uniqueness) on the device before sampling;
+                                graph and device map: a3_validate_graph, a3_validate_cache_map */
 #define A3_NO_EIDS 2u        /* do not produce blk_eids */
 #define A3_HOST_ONLY 4u      /* no device: calls validate their arguments, then fail with A3_ERR_HIP */
 #define A3_FORCE_RADIX 8u    /* testing: always use the exhaustive selection path */
@@ -118,6 +119,20 @@ int a3_sample_blocks(a3_ctx* ctx, const int64_t* indptr, const void* indices, in
                      int64_t num_nodes, const void* seeds, int64_t num_seeds,
                      const int32_t* fanouts, int32_t num_hops, const int32_t* cache_map,
                      uint32_t bias_q16, uint64_t rng_seed, a3_blocks* out);
+
+/* One-time checks of what a3_sample_blocks and a3_gather_features take on trust (the graph and
+ * the device map of the problem statement, Sec. III): run them once per graph / per map, not per
+ * mini-batch.  Synchronous; they read nothing outside the sizes given here.
+ * a3_validate_graph: indptr (device int64 [num_nodes + 1]) starts at 0, never decreases and ends
+ *   at nnz; indices (device, idx_bytes wide, [nnz]) holds ids in [0, num_nodes), and every row is
+ *   strictly increasing (sorted, no neighbour twice).
+ * a3_validate_cache_map: every entry c of cache_map (device int32 [num_nodes]) names a row of its
+ *   store (0 <= c < n_dev_rows, or 0 <= -c-1 < n_host_rows) and no two nodes name the same row.
+ * A3_ERR_INPUT with the kind of violation in a3_last_error, else A3_OK. */
+int a3_validate_graph(a3_ctx* ctx, const int64_t* indptr, const void* indices, int32_t idx_bytes,
+                      int64_t num_nodes, int64_t nnz);
+int a3_validate_cache_map(a3_ctx* ctx, const int32_t* cache_map, int64_t num_nodes, int64_t n_dev_rows,
+                          int64_t n_host_rows);
 
 /* The same call split in two, so that the host does not wait between sampling and feature
  * retrieve (Sec. III-B counts that wait as lost throughput).  a3_sample_blocks_begin checks the

@@ -56,6 +56,10 @@ def lib():
         L.a3_destroy.restype = C.c_int
         L.a3_set_stream.argtypes = [C.c_void_p, C.c_void_p]
         L.a3_set_stream.restype = C.c_int
+        L.a3_validate_graph.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64]
+        L.a3_validate_graph.restype = C.c_int
+        L.a3_validate_cache_map.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64]
+        L.a3_validate_cache_map.restype = C.c_int
         L.a3_set_gather_host_workgroups.argtypes = [C.c_void_p, C.c_int32]
         L.a3_set_gather_host_workgroups.restype = C.c_int
         L.a3_last_error.argtypes = [C.c_void_p]
@@ -264,6 +268,19 @@ class Context:
 
     def set_gather_host_workgroups(self, n: int):
         self._check(lib().a3_set_gather_host_workgroups(self._h, n))
+
+    def validate_graph(self, indptr: torch.Tensor, indices: torch.Tensor):
+        """raises A3Error (A3_ERR_INPUT) unless (indptr, indices) is a CSR with sorted, repeat-free rows"""
+        assert indptr.dtype == torch.int64 and indptr.is_contiguous() and indptr.numel() >= 1
+        assert indices.dtype in (torch.int32, torch.int64) and indices.is_contiguous()
+        self._check(lib().a3_validate_graph(self._h, _dptr(indptr), _dptr(indices), indices.element_size(),
+                                            indptr.numel() - 1, indices.numel()))
+
+    def validate_cache_map(self, cache_map: torch.Tensor, n_dev_rows: int, n_host_rows: int):
+        """raises A3Error (A3_ERR_INPUT) unless every node names a row of its store and none is shared"""
+        assert cache_map.dtype == torch.int32 and cache_map.is_contiguous()
+        self._check(lib().a3_validate_cache_map(self._h, _dptr(cache_map), cache_map.numel(), n_dev_rows,
+                                                n_host_rows))
 
     def profile_read(self, kind: int) -> List[float]:
         """device milliseconds of the calls of this kind (0 sample, 1 gather) since the last read"""

@@ -987,6 +987,88 @@ int resolve_ids(a3_ctx* ctx, const char* who, const void** ids, int32_t* idx_byt
 }
 }  // namespace
 
+namespace {
+
+// runs one validation launch (queued by `launch` with the device word it reports into) and
+// returns the bits it found; `words` zeroed uint32 words of scratch are handed to the launch
+template <typename Launch>
+int run_validation(a3_ctx* ctx, const char* who, int64_t words, int32_t* found_bits, Launch launch) {
+  A3_HIP(ctx, hipSetDevice(ctx->device));
+  int32_t* d = nullptr;  // [0]: the bits found; [1 ...]: scratch
+  A3_HIP(ctx, hipMalloc((void**)&d, (size_t)(words + 1) * sizeof(int32_t)));
+  const unsigned fill_blocks = (unsigned)std::min<int64_t>((words + 1 + 255) / 256, 1 << 20);
+  hipLaunchKernelGGL(a3::k_fill_i32, dim3(fill_blocks), dim3(256), 0, ctx->stream, d, words + 1, 0);
+  launch(d, (uint32_t*)(d + 1));
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) e = hipMemcpyAsync(found_bits, d, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  (void)hipFree(d);
+  if (e != hipSuccess) return hip_fail(ctx, e, who);
+  return A3_OK;
+}
+
+}  // namespace
+
+extern "C" int a3_validate_graph(a3_ctx* ctx, const int64_t* indptr, const void* indices, int32_t idx_bytes,
+                                 int64_t num_nodes, int64_t nnz) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_validate_graph: ctx is null");
+  if (!indptr) return fail(ctx, A3_ERR_INVALID_ARG, "a3_validate_graph: indptr is null");
+  if (idx_bytes != 4 && idx_bytes != 8)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_validate_graph: idx_bytes must be 4 or 8");
+  if (num_nodes < 0 || nnz < 0) return fail(ctx, A3_ERR_INVALID_ARG, "a3_validate_graph: negative size");
+  if (nnz > 0 && !indices) return fail(ctx, A3_ERR_INVALID_ARG, "a3_validate_graph: indices is null");
+  if (idx_bytes == 4 && num_nodes > 0x7FFFFFFFLL)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_validate_graph: num_nodes needs 8-byte ids");
+  if (ctx->flags & A3_HOST_ONLY)
+    return fail(ctx, A3_ERR_HIP, "a3_validate_graph: context was created without a device");
+  const unsigned blocks = (unsigned)std::max<int64_t>(1, std::min<int64_t>((num_nodes + 3) / 4, 16384));
+  int32_t bits = 0;
+  const int rc = run_validation(ctx, "a3_validate_graph", 0, &bits, [&](int32_t* found, uint32_t*) {
+    if (idx_bytes == 4)
+      hipLaunchKernelGGL(a3::k_validate_rows<int32_t>, dim3(blocks), dim3(a3::kTileThreads), 0, ctx->stream,
+                         indptr, (const int32_t*)indices, num_nodes, nnz, found);
+    else
+      hipLaunchKernelGGL(a3::k_validate_rows<int64_t>, dim3(blocks), dim3(a3::kTileThreads), 0, ctx->stream,
+                         indptr, (const int64_t*)indices, num_nodes, nnz, found);
+  });
+  if (rc != A3_OK) return rc;
+  if (bits & a3::kBadIndptrEnds)
+    return fail(ctx, A3_ERR_INPUT, "a3_validate_graph: indptr[0] is not 0 or indptr[num_nodes] is not nnz");
+  if (bits & a3::kBadIndptrOrder)
+    return fail(ctx, A3_ERR_INPUT, "a3_validate_graph: indptr decreases, is negative or exceeds nnz");
+  if (bits & a3::kBadNeighbourId)
+    return fail(ctx, A3_ERR_INPUT, "a3_validate_graph: a neighbour id is outside [0, num_nodes)");
+  if (bits & a3::kBadRowOrder)
+    return fail(ctx, A3_ERR_INPUT, "a3_validate_graph: a row is not strictly increasing (unsorted, or a neighbour twice)");
+  return A3_OK;
+}
+
+extern "C" int a3_validate_cache_map(a3_ctx* ctx, const int32_t* cache_map, int64_t num_nodes,
+                                     int64_t n_dev_rows, int64_t n_host_rows) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_validate_cache_map: ctx is null");
+  if (num_nodes < 0 || n_dev_rows < 0 || n_host_rows < 0)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_validate_cache_map: negative size");
+  if (n_dev_rows > 0x80000000LL || n_host_rows > 0x80000000LL)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_validate_cache_map: a store of more than 2^31 rows has no int32 slots");
+  if (num_nodes > 0 && !cache_map) return fail(ctx, A3_ERR_INVALID_ARG, "a3_validate_cache_map: cache_map is null");
+  if (ctx->flags & A3_HOST_ONLY)
+    return fail(ctx, A3_ERR_HIP, "a3_validate_cache_map: context was created without a device");
+  if (num_nodes == 0) return A3_OK;
+  const int64_t words = (n_dev_rows + n_host_rows + 31) / 32;
+  const unsigned blocks = (unsigned)std::min<int64_t>((num_nodes + a3::kTileThreads - 1) / a3::kTileThreads, 16384);
+  int32_t bits = 0;
+  const int rc = run_validation(ctx, "a3_validate_cache_map", words, &bits, [&](int32_t* found, uint32_t* seen) {
+    hipLaunchKernelGGL(a3::k_validate_map, dim3(blocks), dim3(a3::kTileThreads), 0, ctx->stream, cache_map,
+                       num_nodes, n_dev_rows, n_host_rows, seen, found);
+  });
+  if (rc != A3_OK) return rc;
+  if (bits & a3::kBadMapSlot)
+    return fail(ctx, A3_ERR_INPUT, "a3_validate_cache_map: an entry points outside its store");
+  if (bits & a3::kBadMapRepeat)
+    return fail(ctx, A3_ERR_INPUT, "a3_validate_cache_map: two nodes share a row");
+  return A3_OK;
+}
+
 extern "C" int a3_cache_count_accesses(a3_ctx* ctx, const void* ids, int32_t idx_bytes, int64_t n_ids,
                                        int64_t num_nodes, uint32_t* counts) {
   if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_cache_count_accesses: ctx is null");

@@ -227,3 +227,25 @@ def test_strided_argument_errors(L):
     assert L.a3_block_mean_strided(h, p, p, 2, 3, p, 32, a3.A3_F32, 4, p, 64) == a3.A3_ERR_HIP
     assert L.a3_block_mean_of_hop_strided(h, 0, p, 0, a3.A3_F16, 4, p, 6, 2) == a3.A3_ERR_INVALID_ARG
     assert L.a3_destroy(h) == a3.A3_OK
+
+
+def test_validate_argument_errors(L):
+    L.a3_validate_graph.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64]
+    L.a3_validate_cache_map.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64]
+    rc, h = _create(L, 8, [3, 2], a3.A3_HOST_ONLY)
+    assert rc == a3.A3_OK
+    dummy = C.create_string_buffer(64)
+    p = C.cast(dummy, C.c_void_p)
+    assert L.a3_validate_graph(h, None, p, 4, 3, 5) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_validate_graph(h, p, None, 4, 3, 5) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_validate_graph(h, p, p, 2, 3, 5) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_validate_graph(h, p, p, 4, -1, 5) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_validate_graph(h, p, p, 4, 1 << 31, 5) == a3.A3_ERR_INVALID_ARG   # needs 8-byte ids
+    assert L.a3_validate_graph(h, p, p, 8, 3, 5) == a3.A3_ERR_HIP                 # valid, but no device
+    assert L.a3_validate_cache_map(h, None, 3, 1, 2) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_validate_cache_map(h, p, 3, -1, 2) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_validate_cache_map(h, p, 3, (1 << 31) + 1, 2) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_validate_cache_map(h, p, 3, 1, 2) == a3.A3_ERR_HIP
+    assert L.a3_set_gather_host_workgroups(h, 16) == a3.A3_OK
+    assert L.a3_set_gather_host_workgroups(h, -1) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_destroy(h) == a3.A3_OK

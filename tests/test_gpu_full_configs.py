@@ -58,6 +58,9 @@ def _run(name, gammas, check_rows, n_batches=1, full_hops=None):
     cm_h = split.cache_map.cpu().numpy()
     idt = ix_h.dtype
     ctx = a3.Context(w.batch, w.fanouts)
+    # the generators' outputs satisfy what the sampler takes on trust, at full size
+    ctx.validate_graph(g.indptr, g.indices)
+    ctx.validate_cache_map(split.cache_map, split.n_cached, w.num_nodes - split.n_cached)
     cap_rows = w.batch
     for f in w.fanouts:
         cap_rows *= 1 + f
