@@ -15,7 +15,8 @@
 // Once per call: k_cached_bits (weighted calls: one bit per node from the device map),
 // k_finish_call (reset of the relabel map, counts to the host).
 // Then: k_gather (feature retrieve), k_block_mean (neighbour aggregation of one block),
-// k_count_accesses / k_rank_* / k_fifo_* (cache policies).
+// k_count_accesses / k_rank_* / k_fifo_* (cache policies), k_validate_rows / k_validate_map
+// (one-time checks of the caller's graph and device map).
 #pragma once
 #include <type_traits>
 
