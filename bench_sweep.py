@@ -3,8 +3,9 @@
 
 Shows where locality-aware sampling pays off (paper Sec. II-B Motivation 2, Sec. IV-C ablation):
 for every batch size x HBM cache fraction x bias rate gamma it reports the cache hit rate of the
-input nodes, the number of input rows, and the device time of sampling and of the feature gather
-(HBM rows + pinned-host rows over PCIe).  Prints a markdown table; the graph is generated once.
+input nodes, the number of input rows, the device time of sampling and of the feature gather
+(HBM rows + pinned-host rows over PCIe), and the wall time per mini-batch with two mini-batches
+in flight (a3_pipeline_*, parallel mode 2: sampling beside the previous retrieve).  Prints a markdown table; the graph is generated once.
 
     python bench_sweep.py [--steps 10] [--batches 256,1024,4096,16384] [--cache 0.05,0.2,0.5,1.0]
                           [--gammas 1,2,4,8] [--workload copurchase]
@@ -12,6 +13,7 @@ input nodes, the number of input rows, and the device time of sampling and of th
 import argparse
 import os
 import sys
+import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
@@ -47,8 +49,8 @@ def main():
     print(f"# sweep on `{w.name}`: N={st['num_nodes']:,}, nnz={st['nnz']:,}, fanouts {w.fanouts}, "
           f"{w.row_bytes}-B rows, {K} timed mini-batches per cell (device times from HIP events)")
     print("| batch | cache | gamma | hit rate | input rows | ms sample | ms gather | ms total | "
-          "vs gamma=1 | PCIe GB/s |")
-    print("|---|---|---|---|---|---|---|---|---|---|")
+          "vs gamma=1 | PCIe GB/s | ms per step, 2 in flight | vs gamma=1 |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|")
     for frac in fracs:
         split = degree_ranked_cache(g, full, frac, pin_host=True)
         for batch in batches:
@@ -58,9 +60,11 @@ def main():
                 cap_rows *= 1 + f
             cap_rows = min(cap_rows, w.num_nodes)
             out = torch.empty((cap_rows, w.feat_dim), dtype=w.feat_dtype, device=dev)
+            out2 = torch.empty_like(out)
+            pipe = a3.Pipeline(a3.A3_PIPE_MODE2, 2, batch, w.fanouts)
             seeds = [torch.from_numpy(seed_batch(w.num_nodes, batch, 0, b, dtype=idx_np)).to(dev)
                      for b in range(K + W)]
-            base_total = None
+            base_total = base_piped = None
             for gamma in gammas:
                 q = int(round(gamma * 65536))
                 hits = rows = 0
@@ -83,11 +87,29 @@ def main():
                     base_total = total
                 miss_bytes = (rows - hits) / K * w.row_bytes
                 pcie = miss_bytes / (ms_g * 1e-3) / 1e9 if rows > hits else 0.0
+                # the same mini-batches with two in flight (Sec. III-B, parallel mode 2: the next
+                # mini-batch is sampled beside this one's retrieve, retrieves one at a time): wall time
+                outs = (out, out2)
+                t0 = 0.0
+                for j in range(K + W + 2):
+                    if j == W:          # drain the warm-up mini-batches; the K timed ones follow
+                        torch.cuda.synchronize()
+                        t0 = time.perf_counter()
+                    if j >= 2:
+                        pipe.wait()
+                    if j < K + W:
+                        pipe.submit(g.indptr, g.indices, seeds[j], w.fanouts, split.cache_map, q, j,
+                                    split.feat_dev, split.feat_host, outs[j % 2])
+                torch.cuda.synchronize()
+                piped = (time.perf_counter() - t0) * 1e3 / K
+                if gamma == gammas[0]:
+                    base_piped = piped
                 print(f"| {batch} | {frac:.0%} | {gamma:g} | {hits / max(rows, 1):.3f} | {rows // K} | "
-                      f"{ms_s:.3f} | {ms_g:.3f} | {total:.3f} | {base_total / total:.2f}x | {pcie:.1f} |",
-                      flush=True)
+                      f"{ms_s:.3f} | {ms_g:.3f} | {total:.3f} | {base_total / total:.2f}x | {pcie:.1f} | "
+                      f"{piped:.3f} | {base_piped / piped:.2f}x |", flush=True)
+            pipe.close()
             ctx.close()
-            del out
+            del out, out2
         del split
 
 
