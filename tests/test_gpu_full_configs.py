@@ -133,6 +133,15 @@ def _run(name, gammas, check_rows, n_batches=1, full_hops=None):
                                                np.arange(pick.shape[0], dtype=np.int64))
             got_rows = rows[torch.from_numpy(pick).to(DEV)].cpu().numpy()
             assert got_rows.tobytes() == want_rows.tobytes()
+            if split.feat_host is not None and b == 0:
+                # the same retrieve with workgroups set aside for the host rows (as the pipelines'
+                # workers run it), at full size: the same rows, all of them
+                ctx.set_gather_host_workgroups(16)
+                again = torch.zeros((got_d.n_src[-1], w.feat_dim), dtype=w.feat_dtype, device=DEV)
+                ctx.gather_features(split.feat_dev, split.feat_host, split.cache_map, got_d.input_nodes, out=again)
+                ctx.set_gather_host_workgroups(0)
+                assert torch.equal(again, rows)
+                del again
     ctx.close()
 
 
