@@ -8,8 +8,9 @@ ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "liba3gnn.so")
 BUILD_DIR = os.path.join(HERE, "_build")
 SOURCES = [os.path.join(HERE, "csrc", "a3gnn.hip"), os.path.join(HERE, "csrc", "a3cpu.cpp")]
-HEADERS = [os.path.join(HERE, "csrc", "a3_kernels.hpp"), os.path.join(HERE, "csrc", "a3_device.hpp"),
-           os.path.join(ROOT, "include", "a3gnn.h"), os.path.join(ROOT, "include", "a3gnn_cpu.h")]
+HEADERS = [os.path.join(HERE, "csrc", name) for name in sorted(os.listdir(os.path.join(HERE, "csrc")))
+           if name.endswith(".hpp")] + [os.path.join(ROOT, "include", "a3gnn.h"),
+                                        os.path.join(ROOT, "include", "a3gnn_cpu.h")]
 
 
 def build(force: bool = True, verbose: bool = False) -> str:

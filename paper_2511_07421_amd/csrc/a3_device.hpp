@@ -25,6 +25,17 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
   return v;
 }
 
+// LDS traffic between the lanes of one wavefront: LDS executes a wavefront's accesses in order,
+// so only the compiler has to be kept from moving them.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {  // set bits of mask in lower lanes
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
 // exclusive prefix sum across the 64 lanes of a wave
 __device__ __forceinline__ uint32_t wave_excl_scan_u32(uint32_t v) {
   uint32_t incl = v;

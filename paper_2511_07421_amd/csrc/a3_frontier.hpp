@@ -1,0 +1,158 @@
+// Step a1 of the path: the frontier's degrees, edge offsets and degree bins (k_frontier), and
+// for weighted calls the bitmap of cached nodes (k_cached_bits, k_class_mix).
+#pragma once
+#include "a3_common.hpp"
+
+namespace a3 {
+
+// ---------------------------------------------------------------------------
+// step a1: frontier degrees -> edge offsets, degree bins
+// ---------------------------------------------------------------------------
+// One bit per node from the device map: bit u of the bitmap = (cache_map[u] >= 0).  A wavefront
+// turns 64 consecutive entries into one 64-bit word with a ballot.  Each workgroup also notes
+// whether it met cached nodes (bit 0) and uncached ones (bit 1); k_class_mix folds the notes:
+// with one class only (everything or nothing cached) all weights are equal and the sampler takes
+// the uniform path whatever the bias rate.
+__global__ __launch_bounds__(kTileThreads) void k_cached_bits(const int32_t* __restrict__ cache_map,
+                                                             int64_t num_nodes, uint64_t* __restrict__ bits,
+                                                             int32_t* __restrict__ block_seen) {
+  __shared__ uint32_t seen_lds[kTileThreads / kWave];
+  const int64_t n_words = (num_nodes + 63) >> 6;
+  const int64_t n_waves = (int64_t)gridDim.x * (kTileThreads / kWave);
+  const uint32_t lane = lane_id();
+  uint32_t seen = 0;  // same value in every lane of the wavefront
+  for (int64_t w0 = ((int64_t)blockIdx.x * kTileThreads + threadIdx.x) >> 6; w0 < n_words; w0 += 4 * n_waves) {
+    int32_t c[4];
+    bool valid[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int64_t u = ((w0 + k * n_waves) << 6) + lane;
+      valid[k] = u < num_nodes;
+      c[k] = valid[k] ? cache_map[u] : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint64_t word = __ballot(c[k] >= 0);
+      const uint64_t in_range = __ballot(valid[k]);
+      seen |= (word ? 1u : 0u) | ((in_range & ~word) ? 2u : 0u);
+      if (lane == 0 && w0 + k * n_waves < n_words) bits[w0 + k * n_waves] = word;
+    }
+  }
+  if (lane == 0) seen_lds[threadIdx.x >> 6] = seen;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t all = 0;
+    for (int w = 0; w < kTileThreads / kWave; ++w) all |= seen_lds[w];
+    block_seen[blockIdx.x] = (int32_t)all;
+  }
+}
+
+__global__ __launch_bounds__(kTileThreads) void k_class_mix(const int32_t* __restrict__ block_seen, int n_blocks,
+                                                           DevState* st) {
+  __shared__ uint32_t seen_lds[kTileThreads / kWave];
+  uint32_t seen = 0;
+  for (int b = threadIdx.x; b < n_blocks; b += kTileThreads) seen |= (uint32_t)block_seen[b];
+  const uint32_t wave_seen = (__ballot(seen & 1u) ? 1u : 0u) | (__ballot(seen & 2u) ? 2u : 0u);
+  if (lane_id() == 0) seen_lds[threadIdx.x >> 6] = wave_seen;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t all = 0;
+    for (int w = 0; w < kTileThreads / kWave; ++w) all |= seen_lds[w];
+    st->class_mix = (int32_t)all;
+  }
+}
+
+template <typename IdxT>
+struct FrontierArgs {
+  const IdxT* seeds;  // non-null at hop 0 without validation: the frontier is read from here
+  int64_t num_seeds;
+  IdxT* S;
+  int32_t* node_map;
+  const int64_t* indptr;
+  DevState* st;
+  int32_t hop;
+  int32_t fanout;
+  int32_t* tile_sums;
+  int64_t num_nodes;
+  NodeRec* bins[kNumBins];   // node records per degree bin
+};
+
+__device__ __forceinline__ int degree_bin(uint32_t deg) {
+  return deg <= 16 ? 0 : deg <= 32 ? 1 : deg <= 64 ? 2 : deg <= kHubDegree ? 3 : 4;
+}
+
+template <typename IdxT>
+__global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<IdxT> a) {
+  __shared__ uint32_t lds4[4];
+  __shared__ uint32_t bin_n[kNumBins];
+  __shared__ uint32_t bin_base[kNumBins];
+  const bool from_seeds = a.seeds != nullptr;
+  if (from_seeds && blockIdx.x == 0 && threadIdx.x == 0) a.st->n_dst[0] = (int32_t)a.num_seeds;
+  const int64_t n = from_seeds ? a.num_seeds : (int64_t)a.st->n_dst[a.hop];
+  if ((int64_t)blockIdx.x * kTile >= n) return;
+  if (threadIdx.x < kNumBins) bin_n[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t base_i = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kTilePerThread;
+  uint32_t cnt[kTilePerThread];
+  uint32_t rank_in_bin[kTilePerThread];
+  int bin[kTilePerThread];
+  NodeRec rec[kTilePerThread];
+  uint32_t sum = 0;
+#pragma unroll
+  for (int k = 0; k < kTilePerThread; ++k) {
+    const int64_t i = base_i + k;
+    cnt[k] = 0;
+    bin[k] = -1;
+    rank_in_bin[k] = 0;
+    if (i < n) {
+      int64_t v;
+      if (from_seeds) {
+        const IdxT s = a.seeds[i];
+        v = (int64_t)s;
+        a.S[i] = s;
+        if (v >= 0 && v < a.num_nodes) a.node_map[v] = (int32_t)i;
+      } else {
+        v = (int64_t)a.S[i];
+      }
+      int64_t row = 0, deg = 0;
+      if (v >= 0 && v < a.num_nodes) {
+        row = a.indptr[v];
+        deg = a.indptr[v + 1] - row;
+      } else {
+        atomicOr(&a.st->error, kErrFrontierId);
+      }
+      if (deg < 0 || deg > 0x7FFFFFFF) {  // not a CSR this library can sample: the call fails,
+        atomicOr(&a.st->error, kErrHugeRow);  // and the row is not touched
+        deg = 0;
+      }
+      cnt[k] = deg < (int64_t)a.fanout ? (uint32_t)deg : (uint32_t)a.fanout;
+      bin[k] = degree_bin((uint32_t)deg);
+      rank_in_bin[k] = atomicAdd(&bin_n[bin[k]], 1u);
+      sum += cnt[k];
+      rec[k].v = v;
+      rec[k].row = row;
+      rec[k].deg = (uint32_t)deg;
+      rec[k].i = (int32_t)i;
+      rec[k].pad = 0;
+    }
+  }
+  uint32_t total;
+  uint32_t run = block_excl_scan_256(sum, lds4, &total);
+#pragma unroll
+  for (int k = 0; k < kTilePerThread; ++k) {
+    rec[k].local_off = (int32_t)run;
+    run += cnt[k];
+  }
+  // one global reservation per bin and block, then scatter the node records
+  if (threadIdx.x < kNumBins)
+    bin_base[threadIdx.x] = bin_n[threadIdx.x]
+                                ? (uint32_t)atomicAdd(&a.st->bin_count[threadIdx.x], (int32_t)bin_n[threadIdx.x])
+                                : 0u;
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kTilePerThread; ++k)
+    if (bin[k] >= 0) a.bins[bin[k]][bin_base[bin[k]] + rank_in_bin[k]] = rec[k];
+  if (threadIdx.x == 0) a.tile_sums[blockIdx.x] = (int32_t)total;
+}
+
+}  // namespace a3
