@@ -292,9 +292,27 @@ def main():
         ctx.close()
         pipes = []
         names = {a3.A3_PIPE_SEQUENTIAL: "sequential", a3.A3_PIPE_MODE1: "mode1", a3.A3_PIPE_MODE2: "mode2"}
-        for mode, n_w in [(a3.A3_PIPE_SEQUENTIAL, 1), (a3.A3_PIPE_MODE1, 2), (a3.A3_PIPE_MODE1, 3),
-                          (a3.A3_PIPE_MODE2, 2), (a3.A3_PIPE_MODE2, 3)]:
+        # the last entry adds the stage the paper's formulas call "train": a consumer on the
+        # caller's stream (the mean aggregation of the outermost block) that works on a finished
+        # mini-batch while the workers prepare the next ones
+        can_consume = w.feat_dtype in (torch.float32, torch.float16)
+        consumer = a3.Context(8, [1]) if can_consume else None
+        agg = None
+        if can_consume:
+            agg_rows = batch
+            for f in w.fanouts[:-1]:
+                agg_rows *= 1 + f
+            agg = padded_rows(min(agg_rows, w.num_nodes), w.feat_dim, w.feat_dtype, dev, args.row_align)
+        plans = [(a3.A3_PIPE_SEQUENTIAL, 1, False), (a3.A3_PIPE_MODE1, 2, False), (a3.A3_PIPE_MODE1, 3, False),
+                 (a3.A3_PIPE_MODE2, 2, False), (a3.A3_PIPE_MODE2, 3, False)]
+        if can_consume:
+            plans += [(a3.A3_PIPE_SEQUENTIAL, 1, True), (a3.A3_PIPE_MODE1, 3, True)]
+        for mode, n_w, consume in plans:
             pipe = a3.Pipeline(mode, n_w, batch, w.fanouts)
+            # a worker must not start its next mini-batch (which overwrites its blocks and its
+            # row buffer) before the consumer has read the previous one: an event per worker
+            worker_streams = [torch.cuda.ExternalStream(pipe.stream(k), device=dev) for k in range(n_w)]
+            consumed = [None] * n_w
             outs = [out] + [padded_rows(cap_rows, w.feat_dim, w.feat_dtype, dev, args.row_align)
                             for _ in range(n_w - 1)]
             torch.cuda.synchronize()
@@ -311,19 +329,29 @@ def main():
                     blk = pipe.wait()
                     if j - n_w >= first_timed:
                         p_edges += sum(blk.n_edges)
+                    if consume:
+                        k = (j - n_w) % n_w
+                        consumer.block_mean(blk.blk_indptr[-1], blk.blk_indices[-1],
+                                            outs[k][: blk.n_src[-1]], out=agg[: blk.n_dst[-1]])
+                        consumed[k] = torch.cuda.Event()
+                        consumed[k].record()
                 if j < len(order):
                     b = order[j]
+                    if consumed[j % n_w] is not None:
+                        worker_streams[j % n_w].wait_event(consumed[j % n_w])
                     pipe.submit(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b,
                                 split.feat_dev, split.feat_host, outs[j % n_w])
             torch.cuda.synchronize()
             p_s = time.perf_counter() - t_start
             assert p_edges == n_edges  # the same mini-batches, the same edges
-            pipes.append({"mode": names[mode], "workers": n_w, "ms_per_step": p_s * 1e3 / K,
-                          "edges_per_s": p_edges / p_s,
+            pipes.append({"mode": names[mode], "workers": n_w, "consumer": "block mean" if consume else None,
+                          "ms_per_step": p_s * 1e3 / K, "edges_per_s": p_edges / p_s,
                           "workspace_bytes": pipe.workspace_bytes,
                           "output_bytes": n_w * cap_rows * row_stride})
             pipe.close()
             del outs
+        if consumer is not None:
+            consumer.close()
         result["pipelines"] = pipes
 
     if args.cpu_seconds > 0:
