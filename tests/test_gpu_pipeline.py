@@ -100,3 +100,48 @@ def test_pipeline_sampling_only_and_error_batch(setup):
     blocks_equal(pipe.wait().to_host(), want[1][0])
     blocks_equal(pipe.wait().to_host(), want[2][0])
     pipe.close()
+
+
+def test_consumer_on_the_callers_stream_beside_the_workers(setup):
+    """the pattern of bench.py's consumer entries: every finished mini-batch is aggregated on the
+    caller's stream without a host wait, and a worker's next mini-batch (which overwrites its blocks
+    and its row buffer) waits for that aggregation through an event.  Every aggregate equals the
+    oracle's own chain (its blocks, its rows, its means) within the block mean's bound."""
+    w, d, want, gamma_q = setup
+    n = 3
+    pipe = a3.Pipeline(a3.A3_PIPE_MODE1, n, 256, w.fanouts)
+    consumer = a3.Context(8, [1])
+    cap_rows = 256
+    for f in w.fanouts:
+        cap_rows *= 1 + f
+    cap_rows = min(cap_rows, w.num_nodes)
+    outs = [torch.zeros((cap_rows, 24), dtype=torch.float32, device=DEV) for _ in range(n)]
+    nb = len(want)
+    aggs = [torch.zeros((want[b][0].n_dst[-1], 24), dtype=torch.float32, device=DEV) for b in range(nb)]
+    streams = [torch.cuda.ExternalStream(pipe.stream(k), device=torch.device(DEV)) for k in range(n)]
+    consumed = [None] * n
+    torch.cuda.synchronize()
+    for j in range(nb + n):
+        if j >= n:
+            b = j - n
+            blk = pipe.wait()
+            consumer.block_mean(blk.blk_indptr[-1], blk.blk_indices[-1], outs[b % n][: blk.n_src[-1]],
+                                out=aggs[b])
+            consumed[b % n] = torch.cuda.Event()
+            consumed[b % n].record()
+        if j < nb:
+            if consumed[j % n] is not None:
+                streams[j % n].wait_event(consumed[j % n])
+            pipe.submit(d["indptr"], d["indices"], d["seeds"][j], w.fanouts, d["cache_map"], gamma_q,
+                        100 + j, d["feat_dev"], d["feat_host"], outs[j % n])
+    torch.cuda.synchronize()
+    for b in range(nb):
+        ob, o_rows = want[b]
+        m_want = oracle.block_mean(ob.blk_indptr[-1], ob.blk_indices[-1], o_rows)
+        S = oracle.block_mean(ob.blk_indptr[-1], ob.blk_indices[-1], np.abs(o_rows))
+        deg = np.diff(ob.blk_indptr[-1]).astype(np.float64)[:, None]
+        tol = (deg + 1) * 2.0 ** -24 * S * 1.0000001
+        got = aggs[b].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - m_want) <= tol), f"aggregate of mini-batch {b}"
+    consumer.close()
+    pipe.close()
