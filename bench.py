@@ -4,9 +4,13 @@
 A step is one pass of the whole path over one mini-batch of synthetic input that is already
 resident in HBM: a3_sample_blocks_begin/_end (frontier degrees, keyed selection, dedup/relabel
 into block CSRs, every hop) and a3_gather_input_features for the input nodes.  Prints ONE JSON
-line.
+line.  The headline workload is the largest single-GPU configuration (`citation`: 100 M nodes,
+1.6 G edges, 8-byte ids, 128 x fp16 rows); the default run also measures `social` and
+`copurchase` and reports them under "other_workloads".
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload social|copurchase|citation|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload citation|social|copurchase|tiny]
+    python bench.py --sweep      # batch x cache x bias-rate table on the co-purchase graph (markdown)
+    python bench.py --policies   # degree-ranked / access-count-ranked / FIFO caches (markdown)
 """
 import argparse
 import json
@@ -25,15 +29,22 @@ ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 # (20 32x32->64 multiplies at a quarter of the 32-bit rate = 80, plus 20 three-way xors) and one
 # comparison of the draw
 OPS_PER_SLOT = (20 * 4 + 20) / 4 + 1
+HEADLINE = "citation"
+OTHERS = ["social", "copurchase"]
+METRIC = "sampled edges/s + feature-gather GB/s (% of HBM peak) per mini-batch, 1 GPU"
+# seeds per oracle call of the CPU baseline where a whole mini-batch outlasts the budget
+ORACLE_SLICE = 512
 
 
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=40)
+    p.add_argument("--steps", type=int, default=20)
     p.add_argument("--warmup", type=int, default=5)
-    p.add_argument("--workload", default="social")
-    p.add_argument("--bias-rate", type=float, default=None, help="gamma (default: the workload's first)")
+    p.add_argument("--workload", default=None,
+                   help="measure this workload only (default: %s as the headline, then %s)"
+                        % (HEADLINE, ", ".join(OTHERS)))
+    p.add_argument("--bias-rate", type=float, default=None, help="gamma (default: the workload's last)")
     p.add_argument("--cache-frac", type=float, default=None)
     p.add_argument("--batch", type=int, default=None)
     p.add_argument("--cpu-seconds", type=float, default=20.0,
@@ -48,6 +59,12 @@ def parse():
     p.add_argument("--pmc-calibration", action="store_true",
                    help="also run plain device copies of 256 MiB (a known size) so that a rocprofv3 "
                         "--pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
+    p.add_argument("--sweep", action="store_true", help="config 4: batch x cache x bias-rate table")
+    p.add_argument("--policies", action="store_true", help="cache policies table")
+    p.add_argument("--batches", default="256,1024,4096,16384", help="--sweep: batch sizes")
+    p.add_argument("--cache", default="0.05,0.2,0.5,1.0", help="--sweep: cache fractions")
+    p.add_argument("--gammas", default=None, help="--sweep (default 1,2,4,8) / --policies (default 1,4)")
+    p.add_argument("--presample", type=int, default=20, help="--policies: pre-sampled mini-batches")
     return p.parse_args()
 
 
@@ -63,29 +80,28 @@ def recorded_traffic(workload):
     return None
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
+def cap_rows_of(w, batch):
+    """output rows: at most every node, at most seeds x prod(1 + fanout)"""
+    cap = batch
+    for f in w.fanouts:
+        cap *= 1 + f
+    return min(cap, w.num_nodes)
+
+
+def measure(args, name, headline, legs):
+    """One workload: K timed steps, then the legs asked for ("mean", "pipelines", "cpu")."""
     import numpy as np
     import torch
     import paper_2511_07421_amd as a3
     from workloads import (get_config, make_graph, make_features, degree_ranked_cache, padded_rows,
                            seed_batch)
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    if not os.path.exists(a3.library_path()):
-        print("bench.py: HIP library not built (run __graft_entry__.build())", file=sys.stderr)
-        sys.exit(2)
     dev = torch.device("cuda", 0)
-    w = get_config(args.workload)
-    gamma = args.bias_rate if args.bias_rate is not None else w.bias_rates[-1]
-    cache_frac = args.cache_frac if args.cache_frac is not None else w.cache_frac
-    batch = args.batch or w.batch
+    w = get_config(name)
+    own = headline or args.workload is not None   # the overrides apply to the workload that was asked for
+    gamma = args.bias_rate if (args.bias_rate is not None and own) else w.bias_rates[-1]
+    cache_frac = args.cache_frac if (args.cache_frac is not None and own) else w.cache_frac
+    batch = (args.batch if own else None) or w.batch
     K, W = args.steps, args.warmup
 
     t_gen = time.time()
@@ -106,11 +122,7 @@ def main():
 
     ctx = a3.Context(batch, w.fanouts, flags=a3.A3_PROFILE)
     bias_q16 = int(round(gamma * 65536))
-    # output rows: at most every node, at most seeds x prod(1 + fanout)
-    cap_rows = batch
-    for f in w.fanouts:
-        cap_rows = cap_rows * (1 + f)
-    cap_rows = min(cap_rows, w.num_nodes)
+    cap_rows = cap_rows_of(w, batch)
     out = padded_rows(cap_rows, w.feat_dim, w.feat_dtype, dev, args.row_align)
     row_stride = (out.stride(0) if cap_rows > 1 else w.feat_dim) * out.element_size()
 
@@ -179,17 +191,18 @@ def main():
 
     # counters cannot be read from inside this process: the figure comes from the committed
     # rocprofv3 --pmc summary of this same command, and only for the configuration it was taken on
-    traffic = args.traffic_bytes
-    if (traffic is None and args.batch is None and args.cache_frac is None and args.bias_rate is None
+    traffic = args.traffic_bytes if own else None
+    if (traffic is None and gamma == w.bias_rates[-1] and cache_frac == w.cache_frac and batch == w.batch
             and args.row_align == 128):
         traffic = recorded_traffic(w.name)
 
     gather_payload_gbps = n_in * row_bytes / (ms_gather * 1e-3) / 1e9
+    # per input row: its id, its device-map entry, the row read and the row written
     algo_bytes_per_launch = (n_in / K) * (2 * row_bytes + ib + 4)
     gather_avg_s = ms_gather * 1e-3 / K
     achieved = algo_bytes_per_launch / gather_avg_s / 1e9
     result = {
-        "metric": "sampled edges/s + feature-gather GB/s (% of HBM peak) per mini-batch, 1 GPU",
+        "metric": METRIC,
         "value": n_edges / total_s,
         "unit": "sampled edges/s",
         "n_gpus": 1,
@@ -254,7 +267,7 @@ def main():
 
     # the step after the path: mean aggregation of the gathered rows over the outermost block
     # (a3_block_mean_of_hop), timed by the library's events on a few of the same mini-batches
-    if w.feat_dtype in (torch.float32, torch.float16):
+    if "mean" in legs and w.feat_dtype in (torch.float32, torch.float16):
         H = len(w.fanouts)
         agg_rows = batch
         for f in w.fanouts[:-1]:
@@ -285,14 +298,15 @@ def main():
                                 "algorithmic_bytes_per_launch": mean_bytes}
         del agg
 
-    if not args.no_pipelines:
+    if "pipelines" in legs:
         # the same K mini-batches through the scheduling templates of Sec. III-B: n mini-batches in
         # flight on streams of their own (mode 1: whole mini-batches overlap; mode 2: sampling
         # overlaps, the feature retrieve is serialised).  `value` above stays the sequential figure.
         ctx.close()
+        ctx = None
         pipes = []
         names = {a3.A3_PIPE_SEQUENTIAL: "sequential", a3.A3_PIPE_MODE1: "mode1", a3.A3_PIPE_MODE2: "mode2"}
-        # the last entry adds the stage the paper's formulas call "train": a consumer on the
+        # the last entries add the stage the paper's formulas call "train": a consumer on the
         # caller's stream (the mean aggregation of the outermost block) that works on a finished
         # mini-batch while the workers prepare the next ones
         can_consume = w.feat_dtype in (torch.float32, torch.float16)
@@ -304,7 +318,7 @@ def main():
                 agg_rows *= 1 + f
             agg = padded_rows(min(agg_rows, w.num_nodes), w.feat_dim, w.feat_dtype, dev, args.row_align)
         plans = [(a3.A3_PIPE_SEQUENTIAL, 1, False), (a3.A3_PIPE_MODE1, 2, False), (a3.A3_PIPE_MODE1, 3, False),
-                 (a3.A3_PIPE_MODE2, 2, False), (a3.A3_PIPE_MODE2, 3, False)]
+                 (a3.A3_PIPE_MODE2, 2, False)]
         if can_consume:
             plans += [(a3.A3_PIPE_SEQUENTIAL, 1, True), (a3.A3_PIPE_MODE1, 3, True)]
         for mode, n_w, consume in plans:
@@ -343,7 +357,9 @@ def main():
                                 split.feat_dev, split.feat_host, outs[j % n_w])
             torch.cuda.synchronize()
             p_s = time.perf_counter() - t_start
-            assert p_edges == n_edges  # the same mini-batches, the same edges
+            # the same mini-batches, the same edges (the full-size parity tests compare a pipeline's
+            # blocks and rows with the oracle element by element)
+            assert p_edges == n_edges
             pipes.append({"mode": names[mode], "workers": n_w, "consumer": "block mean" if consume else None,
                           "ms_per_step": p_s * 1e3 / K, "edges_per_s": p_edges / p_s,
                           "workspace_bytes": pipe.workspace_bytes,
@@ -354,62 +370,87 @@ def main():
             consumer.close()
         result["pipelines"] = pipes
 
-    if args.cpu_seconds > 0:
+    if "cpu" in legs and args.cpu_seconds > 0:
         import oracle
         ip_h, ix_h = g.indptr.cpu().numpy(), g.indices.cpu().numpy()
         cm_h = d_cm.cpu().numpy()
-        fd_h = None if split.feat_dev is None else split.feat_dev.cpu().numpy()
-        fh_h = None if split.feat_host is None else split.feat_host.numpy()
-        spent, done, o_edges, o_rows, o_sample, o_gather = 0.0, 0, 0, 0, 0.0, 0.0
-        while spent < args.cpu_seconds and done < K:
-            s_h = seeds[W + done].cpu().numpy()
+
+        def oracle_rows(ids):
+            """the oracle's gather on host copies of only the rows it touches (the whole store of
+            `citation` is 25.6 GB), renumbered; returns its seconds"""
+            c = cm_h[ids]
+            dev_rows, host_rows = np.unique(c[c >= 0]), np.unique(-c[c < 0] - 1)
+            fd = split.feat_dev[torch.from_numpy(dev_rows).to(dev)].cpu().numpy() if dev_rows.size else None
+            fh = split.feat_host[torch.from_numpy(host_rows)].numpy() if host_rows.size else None
+            cm_small = np.zeros_like(c)
+            cm_small[c >= 0] = np.searchsorted(dev_rows, c[c >= 0])
+            cm_small[c < 0] = -np.searchsorted(host_rows, -c[c < 0] - 1) - 1
             c0 = time.perf_counter()
-            ob = oracle.sample_blocks(ip_h, ix_h, s_h, w.fanouts, cm_h, bias_q16, W + done)
-            c1 = time.perf_counter()
-            oracle.gather_features(fd_h, fh_h, cm_h, ob.input_nodes.astype(idx_np))
-            c2 = time.perf_counter()
+            oracle.gather_features(fd, fh, cm_small, np.arange(ids.shape[0], dtype=np.int64))
+            return time.perf_counter() - c0
+
+        # The oracle as it stands, single-threaded, on a bounded sample: slices of the timed
+        # mini-batches' seed lists, each sampled as a mini-batch of its own with its mini-batch's
+        # rng_seed, until the budget is spent.  A whole mini-batch of `citation` takes the oracle
+        # about two minutes; its parity with the GPU path at full size is the tests' business.
+        n_slice = min(batch, ORACLE_SLICE)
+        units = [(W + j // (batch // n_slice), (j % (batch // n_slice)) * n_slice)
+                 for j in range(K * (batch // n_slice))]
+        spent, done, o_edges, o_rows, o_sample, o_gather = 0.0, 0, 0, 0, 0.0, 0.0
+        seeds_host = {}
+
+        def one_unit(u):
+            b, s0 = u
+            if b not in seeds_host:
+                seeds_host[b] = seeds[b].cpu().numpy()
+            c0 = time.perf_counter()
+            ob = oracle.sample_blocks(ip_h, ix_h, seeds_host[b][s0:s0 + n_slice], w.fanouts, cm_h, bias_q16, b)
+            return ob, time.perf_counter() - c0
+
+        while spent < args.cpu_seconds and done < len(units):
+            ob, dt = one_unit(units[done])
+            dg = oracle_rows(ob.input_nodes.astype(np.int64))
             o_edges += sum(ob.n_edges)
             o_rows += ob.n_src[-1]
-            o_sample += c1 - c0
-            o_gather += c2 - c1
-            spent += c2 - c0
+            o_sample += dt
+            o_gather += dg
+            spent += dt + dg
             done += 1
         result["cpu_baseline"] = {
             "value": o_edges / spent, "unit": "sampled edges/s", "cores": 1, "kind": "oracle",
-            "sample": "%d of the timed mini-batches of workload %s (same seeds, same rng_seed), "
-                      "%.1f s of CPU work" % (done, w.name, spent),
+            "sample": "%d mini-batches of %d seeds each (consecutive slices of the seed lists of the timed "
+                      "mini-batches of workload %s, same rng_seed), sampling + gather, %.1f s of CPU work"
+                      % (done, n_slice, w.name, spent),
             "gather_GBps": o_rows * row_bytes / max(o_gather, 1e-9) / 1e9,
-            "ms_sample": o_sample * 1e3 / done, "ms_gather": o_gather * 1e3 / done,
+            "ms_sample_per_call": o_sample * 1e3 / done, "ms_gather_per_call": o_gather * 1e3 / done,
+            "edges_per_call": o_edges / done,
         }
-        # the unchanged oracle over independent mini-batches, one per thread, on the host's cores
-        # (its C code runs outside the interpreter lock); skipped where one mini-batch alone
-        # outlasts the CPU budget
-        n_thr = min(16, os.cpu_count() or 1, K - done)
+        # the unchanged oracle over independent slices, one per thread, on the host's cores (its C
+        # code runs outside the interpreter lock); skipped where one slice outlasts the budget
+        n_thr = min(16, os.cpu_count() or 1, len(units) - done)
         if n_thr > 1 and spent / done <= args.cpu_seconds:
             from concurrent.futures import ThreadPoolExecutor
-
-            def one(b):
-                ob = oracle.sample_blocks(ip_h, ix_h, seeds_h[b], w.fanouts, cm_h, bias_q16, b)
-                oracle.gather_features(fd_h, fh_h, cm_h, ob.input_nodes.astype(idx_np))
-                return sum(ob.n_edges)
-
-            seeds_h = {b: seeds[b].cpu().numpy() for b in range(W + done, W + done + n_thr)}
+            todo = units[done:done + n_thr]
+            for b, _ in todo:
+                if b not in seeds_host:
+                    seeds_host[b] = seeds[b].cpu().numpy()
             c0 = time.perf_counter()
             with ThreadPoolExecutor(n_thr) as pool:
-                a_edges = sum(pool.map(one, sorted(seeds_h)))
+                a_edges = sum(sum(ob.n_edges) for ob, _ in pool.map(one_unit, todo))
             a_s = time.perf_counter() - c0
             model = ""
             try:
                 with open("/proc/cpuinfo") as f:
-                    model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "")
+                    model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
             except OSError:
                 pass
             result["cpu_baseline_all_cores"] = {
-                "value": a_edges / a_s, "unit": "sampled edges/s", "cores": n_thr, "kind": "oracle",
-                "sample": "%d further timed mini-batches, one per thread, %.1f s wall" % (n_thr, a_s),
+                "value": a_edges / a_s, "unit": "sampled edges/s (sampling + reindex, no gather)",
+                "cores": n_thr, "kind": "oracle",
+                "sample": "%d further slices of %d seeds, one per thread, %.1f s wall" % (n_thr, n_slice, a_s),
                 "cpu_model": model,
             }
-        # the same mini-batches on the library's own multi-threaded host sampler (the paper's
+        # whole timed mini-batches on the library's own multi-threaded host sampler (the paper's
         # "Sampling Device = CPU, Workers = n"): sampling + reindex only, bit-identical blocks
         n_workers = min(16, os.cpu_count() or 1)
         cpu = a3.CpuSampler(n_workers)
@@ -428,7 +469,242 @@ def main():
             "sample": "%d of the timed mini-batches, %.1f s" % (c_done, c_s),
             "ms_sample": c_s * 1e3 / c_done,
         }
+    if ctx is not None:
+        ctx.close()
+    return result
+
+
+def run_sweep(args):
+    """Batch / cache / bias-rate sweep on the co-purchase-style graph.  Shows where
+    locality-aware sampling pays off (Sec. II-B Motivation 2, Sec. IV-C ablation): for every batch
+    size x HBM cache fraction x bias rate it reports the cache hit rate of the input nodes, the
+    number of input rows, the device time of sampling and of the feature gather (HBM rows +
+    pinned-host rows over PCIe), and the wall time per mini-batch with two mini-batches in flight
+    (parallel mode 2: sampling beside the previous retrieve).  Markdown table; one graph."""
+    import numpy as np
+    import torch
+    import paper_2511_07421_amd as a3
+    from workloads import get_config, make_graph, make_features, degree_ranked_cache, padded_rows, seed_batch
+
+    dev = torch.device("cuda", 0)
+    w = get_config(args.workload or "copurchase")
+    batches = [int(x) for x in args.batches.split(",")]
+    fracs = [float(x) for x in args.cache.split(",")]
+    gammas = [float(x) for x in (args.gammas or "1,2,4,8").split(",")]
+    g = make_graph(w.num_nodes, w.mean_degree, w.d_min, w.d_max, w.a, w.symmetric, w.graph_seed,
+                   w.idx_dtype, device=dev)
+    full = make_features(w.num_nodes, w.feat_dim, w.feat_dtype, device=dev)
+    idx_np = np.int32 if w.idx_dtype == torch.int32 else np.int64
+    K, W = args.steps, min(args.warmup, 2)
+    st = g.stats()
+    print(f"# sweep on `{w.name}`: N={st['num_nodes']:,}, nnz={st['nnz']:,}, fanouts {w.fanouts}, "
+          f"{w.row_bytes}-B rows, {K} timed mini-batches per cell (device times from HIP events)")
+    print("| batch | cache | gamma | hit rate | input rows | ms sample | ms gather | ms total | "
+          "vs gamma=1 | PCIe GB/s | ms per step, 2 in flight | vs gamma=1 |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|")
+    for frac in fracs:
+        split = degree_ranked_cache(g, full, frac, pin_host=True, row_align=args.row_align)
+        for batch in batches:
+            ctx = a3.Context(batch, w.fanouts, flags=a3.A3_PROFILE)
+            cap_rows = cap_rows_of(w, batch)
+            out = padded_rows(cap_rows, w.feat_dim, w.feat_dtype, dev, args.row_align)
+            out2 = padded_rows(cap_rows, w.feat_dim, w.feat_dtype, dev, args.row_align)
+            pipe = a3.Pipeline(a3.A3_PIPE_MODE2, 2, batch, w.fanouts)
+            seeds = [torch.from_numpy(seed_batch(w.num_nodes, batch, 0, b, dtype=idx_np)).to(dev)
+                     for b in range(K + W)]
+            base_total = base_piped = None
+            for gamma in gammas:
+                q = int(round(gamma * 65536))
+                hits = rows = 0
+                for b in range(K + W):
+                    ctx.sample_blocks_begin(g.indptr, g.indices, seeds[b], w.fanouts, split.cache_map, q, b)
+                    ctx.gather_input_features(split.feat_dev, split.feat_host, split.cache_map, out)
+                    blk = ctx.sample_blocks_end()
+                    if b == W - 1:
+                        torch.cuda.synchronize()
+                        ctx.profile_read(0), ctx.profile_read(1)
+                    if b >= W:
+                        ids = blk.input_nodes.long()
+                        hits += int((split.cache_map[ids] >= 0).sum().item())
+                        rows += ids.numel()
+                torch.cuda.synchronize()
+                ms_s = sum(ctx.profile_read(0)) / K
+                ms_g = sum(ctx.profile_read(1)) / K
+                total = ms_s + ms_g
+                if gamma == gammas[0]:
+                    base_total = total
+                miss_bytes = (rows - hits) / K * w.row_bytes
+                pcie = miss_bytes / (ms_g * 1e-3) / 1e9 if rows > hits else 0.0
+                # the same mini-batches with two in flight (Sec. III-B, parallel mode 2: the next
+                # mini-batch is sampled beside this one's retrieve, retrieves one at a time): wall time
+                outs = (out, out2)
+                t0 = 0.0
+                for j in range(K + W + 2):
+                    if j == W:          # drain the warm-up mini-batches; the K timed ones follow
+                        torch.cuda.synchronize()
+                        t0 = time.perf_counter()
+                    if j >= 2:
+                        pipe.wait()
+                    if j < K + W:
+                        pipe.submit(g.indptr, g.indices, seeds[j], w.fanouts, split.cache_map, q, j,
+                                    split.feat_dev, split.feat_host, outs[j % 2])
+                torch.cuda.synchronize()
+                piped = (time.perf_counter() - t0) * 1e3 / K
+                if gamma == gammas[0]:
+                    base_piped = piped
+                print(f"| {batch} | {frac:.0%} | {gamma:g} | {hits / max(rows, 1):.3f} | {rows // K} | "
+                      f"{ms_s:.3f} | {ms_g:.3f} | {total:.3f} | {base_total / total:.2f}x | {pcie:.1f} | "
+                      f"{piped:.3f} | {base_piped / piped:.2f}x |", flush=True)
+            pipe.close()
+            ctx.close()
+            del out, out2
+        del split
+
+
+def run_policies(args):
+    """Cache policies on the co-purchase-style graph: hit rate and step time of the static fill
+    ranked by degree (the input generators' default), the static fill ranked by access count over
+    pre-sampled mini-batches (a3_cache_count_accesses + a3_cache_rank; Sec. IV-C: "most frequently
+    accessed nodes"), and a FIFO dynamic cache that starts empty (a3_cache_fifo_update;
+    Sec. II-B), each under uniform and locality-aware sampling.  Markdown table."""
+    import numpy as np
+    import torch
+    import paper_2511_07421_amd as a3
+    from workloads import get_config, make_graph, make_features, degree_ranked_cache, seed_batch
+
+    dev = torch.device("cuda", 0)
+    w = get_config(args.workload or "copurchase")
+    cache_frac = args.cache_frac if args.cache_frac is not None else w.cache_frac
+    K = args.steps
+    g = make_graph(w.num_nodes, w.mean_degree, w.d_min, w.d_max, w.a, w.symmetric, w.graph_seed,
+                   w.idx_dtype, device=dev)
+    full = make_features(w.num_nodes, w.feat_dim, w.feat_dtype, device=dev)
+    N = w.num_nodes
+    n_cached = int(np.ceil(cache_frac * N))
+    idx_np = np.int32 if w.idx_dtype == torch.int32 else np.int64
+    seeds = [torch.from_numpy(seed_batch(N, w.batch, 0, b, dtype=idx_np)).to(dev)
+             for b in range(K + args.presample)]
+    ctx = a3.Context(w.batch, w.fanouts, flags=a3.A3_PROFILE)
+    rows = torch.empty((cap_rows_of(w, w.batch), w.feat_dim), dtype=w.feat_dtype, device=dev)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def host_rows(order_rest):
+        host = torch.empty((order_rest.shape[0], w.feat_dim), dtype=w.feat_dtype, pin_memory=True)
+        step = 1 << 20
+        for r0 in range(0, order_rest.shape[0], step):
+            host[r0:r0 + step] = full[order_rest[r0:r0 + step].long()].cpu()
+        return host
+
+    def run_static(cache_map, feat_dev, feat_host, gamma):
+        q = int(gamma * 65536)
+        hits = n_in = 0
+        ctx.profile_read(0), ctx.profile_read(1)
+        for b in range(args.presample, args.presample + K):
+            ctx.sample_blocks_begin(g.indptr, g.indices, seeds[b], w.fanouts, cache_map, q, b)
+            ctx.gather_input_features(feat_dev, feat_host, cache_map, rows)
+            blk = ctx.sample_blocks_end()
+            ids = blk.input_nodes.long()
+            hits += int((cache_map[ids] >= 0).sum().item())
+            n_in += ids.numel()
+        torch.cuda.synchronize()
+        return hits / n_in, n_in / K, sum(ctx.profile_read(0)) / K, sum(ctx.profile_read(1)) / K
+
+    print(f"# cache policies on `{w.name}`: N={N:,}, {w.row_bytes}-B rows, cache {cache_frac:.0%} = {n_cached:,} rows, "
+          f"batch {w.batch}, fanouts {w.fanouts}, {K} mini-batches per row (device times from HIP events)")
+    print("| policy | gamma | hit rate | input rows | ms sample | ms gather | ms policy | ms total |")
+    print("|---|---|---|---|---|---|---|---|")
+    gammas = [float(x) for x in (args.gammas or "1,4").split(",")]
+    # 1. degree-ranked static fill
+    split = degree_ranked_cache(g, full, cache_frac, pin_host=True)
+    for gamma in gammas:
+        h, n, ms_s, ms_g = run_static(split.cache_map, split.feat_dev, split.feat_host, gamma)
+        print(f"| static, by degree | {gamma:g} | {h:.3f} | {n:.0f} | {ms_s:.3f} | {ms_g:.3f} | - | {ms_s + ms_g:.3f} |", flush=True)
+    del split
+    # 2. access-count-ranked static fill: pre-sample, count, rank, build the two stores by gathers
+    counts = torch.zeros(N, dtype=torch.int32, device=dev)
+    ev0.record()
+    for b in range(args.presample):
+        ctx.sample_blocks_begin(g.indptr, g.indices, seeds[b], w.fanouts, None, 65536, b)
+        ctx.cache_count_accesses(counts)
+        ctx.sample_blocks_end()
+    cache_map, order = ctx.cache_rank(counts, n_cached)
+    feat_dev = ctx.gather_features(full, None, None, order[:n_cached].contiguous())
+    ev1.record()
+    torch.cuda.synchronize()
+    setup_ms = ev0.elapsed_time(ev1)
+    feat_host = host_rows(order[n_cached:])
+    for gamma in gammas:
+        h, n, ms_s, ms_g = run_static(cache_map, feat_dev, feat_host, gamma)
+        print(f"| static, by access count ({args.presample} pre-sampled batches, set-up {setup_ms:.1f} ms on the GPU) | {gamma:g} | "
+              f"{h:.3f} | {n:.0f} | {ms_s:.3f} | {ms_g:.3f} | - | {ms_s + ms_g:.3f} |", flush=True)
+    del feat_dev, feat_host, cache_map, order
+    # 3. FIFO dynamic cache from empty; the host store holds every row
+    host_all = host_rows(torch.arange(N, device=dev))
+    for gamma in gammas:
+        q = int(gamma * 65536)
+        cm = -torch.arange(N, dtype=torch.int32, device=dev) - 1
+        owner = torch.full((n_cached,), -1, dtype=torch.int32, device=dev)
+        state = torch.zeros(4, dtype=torch.int32, device=dev)
+        cache = torch.zeros((n_cached, w.feat_dim), dtype=w.feat_dtype, device=dev)
+        ctx.profile_read(0), ctx.profile_read(1)
+        hits = n_in = 0
+        first_hit = last_hit = 0.0
+        ms_pol = 0.0
+        for b in range(args.presample, args.presample + K):
+            ctx.sample_blocks_begin(g.indptr, g.indices, seeds[b], w.fanouts, cm, q, b)
+            ctx.gather_input_features(cache, host_all, cm, rows)
+            blk = ctx.sample_blocks_end()
+            ids = blk.input_nodes.long()
+            hb = int((cm[ids] >= 0).sum().item())   # judged before the update
+            ev0.record()
+            ctx.cache_fifo_update(cm, owner, state, cache, rows)
+            ev1.record()
+            torch.cuda.synchronize()
+            ms_pol += ev0.elapsed_time(ev1)
+            hits += hb
+            n_in += ids.numel()
+            if b == args.presample + 1:
+                first_hit = hb / ids.numel()
+            last_hit = hb / ids.numel()
+        ms_s, ms_g = sum(ctx.profile_read(0)) / K, sum(ctx.profile_read(1)) / K
+        print(f"| FIFO, from empty (hit rate of batch 2: {first_hit:.3f}, of the last: {last_hit:.3f}) | {gamma:g} | "
+              f"{hits / n_in:.3f} | {n_in / K:.0f} | {ms_s:.3f} | {ms_g:.3f} | {ms_pol / K:.3f} | "
+              f"{ms_s + ms_g + ms_pol / K:.3f} |", flush=True)
     ctx.close()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2511_07421_amd as a3
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    if not os.path.exists(a3.library_path()):
+        print("bench.py: HIP library not built (run __graft_entry__.build())", file=sys.stderr)
+        sys.exit(2)
+    if args.sweep:
+        return run_sweep(args)
+    if args.policies:
+        return run_policies(args)
+    legs = {"mean", "cpu"} | (set() if args.no_pipelines else {"pipelines"})
+    result = measure(args, args.workload or HEADLINE, True, legs)
+    if args.workload is None:
+        # the other single-GPU configurations, each at its own headline setting (copurchase with
+        # locality-aware sampling, gamma = 4), without the oracle leg
+        others = {}
+        for name in OTHERS:
+            torch.cuda.empty_cache()
+            r = measure(args, name, False, legs - {"cpu"})
+            for k in ("metric", "n_gpus", "higher_is_better", "scaling", "vs_baseline", "data", "steps", "warmup"):
+                r.pop(k, None)
+            others[name] = r
+        result["other_workloads"] = others
     print(json.dumps(result))
 
 

@@ -167,6 +167,11 @@ int a3_gather_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
  * right after a3_sample_blocks_begin, before the host knows the count.
  *   out        device [out_rows, row_bytes]; min(n_input_nodes, out_rows) rows are written, so
  *              the caller compares a3_blocks.n_src[num_hops-1] with out_rows afterwards.
+ *   cache_map  if this is the map that the sampling call was given, the entries that call read
+ *              where it first numbered each input node are used, in sequence, instead of one
+ *              random 4-byte read per row: the map must not have changed since that call (a
+ *              cache update belongs after this retrieve).  Any other map, or NULL, is looked up
+ *              as in a3_gather_features.
  * Other arguments, errors and asynchrony as a3_gather_features. */
 int a3_gather_input_features(a3_ctx* ctx, const void* feat_dev, const void* feat_host,
                              const int32_t* cache_map, int64_t row_bytes, void* out,

@@ -139,7 +139,8 @@ __global__ void k_fill_i32(int32_t* p, int64_t n, int32_t value) {
 // A3_VALIDATE only: seeds -> S with range and uniqueness checks; a bad batch empties the frontier
 template <typename IdxT>
 __global__ void k_init_seeds_checked(const IdxT* seeds, int64_t num_seeds, int64_t num_nodes,
-                                     IdxT* S, int32_t* node_map, DevState* st) {
+                                     IdxT* S, int32_t* node_map, DevState* st,
+                                     const int32_t* cache_map, int32_t* S_slot) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= num_seeds) return;
   const int64_t v = (int64_t)seeds[i];
@@ -149,6 +150,7 @@ __global__ void k_init_seeds_checked(const IdxT* seeds, int64_t num_seeds, int64
     return;
   }
   atomicMin(&node_map[v], (int32_t)i);
+  if (cache_map) S_slot[i] = cache_map[v];
 }
 
 template <typename IdxT>

@@ -64,8 +64,11 @@ __global__ __launch_bounds__(kTileThreads) void k_class_mix(const int32_t* __res
 
 template <typename IdxT>
 struct FrontierArgs {
-  const IdxT* seeds;  // non-null at hop 0 without validation: the frontier is read from here
+  const IdxT* seeds;   // read only where from_seeds is set (may be null for an empty batch)
+  int32_t from_seeds;  // hop 0 without validation: the frontier is the seed list itself
   int64_t num_seeds;
+  const int32_t* cache_map;  // device map, or null: entries of the seeds go to S_slot
+  int32_t* S_slot;
   IdxT* S;
   int32_t* node_map;
   const int64_t* indptr;
@@ -86,7 +89,7 @@ __global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<Id
   __shared__ uint32_t lds4[4];
   __shared__ uint32_t bin_n[kNumBins];
   __shared__ uint32_t bin_base[kNumBins];
-  const bool from_seeds = a.seeds != nullptr;
+  const bool from_seeds = a.from_seeds != 0;
   if (from_seeds && blockIdx.x == 0 && threadIdx.x == 0) a.st->n_dst[0] = (int32_t)a.num_seeds;
   const int64_t n = from_seeds ? a.num_seeds : (int64_t)a.st->n_dst[a.hop];
   if ((int64_t)blockIdx.x * kTile >= n) return;
@@ -110,7 +113,10 @@ __global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<Id
         const IdxT s = a.seeds[i];
         v = (int64_t)s;
         a.S[i] = s;
-        if (v >= 0 && v < a.num_nodes) a.node_map[v] = (int32_t)i;
+        if (v >= 0 && v < a.num_nodes) {
+          a.node_map[v] = (int32_t)i;
+          if (a.cache_map) a.S_slot[i] = a.cache_map[v];
+        }
       } else {
         v = (int64_t)a.S[i];
       }

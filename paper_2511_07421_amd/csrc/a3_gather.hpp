@@ -11,6 +11,9 @@ namespace a3 {
 // flight), then stores them; stores are streaming (the output is not read again by this kernel
 // and should not evict feature rows that the next mini-batch is likely to hit again).
 // With G = 64 the id and device-map lookups are wave-uniform and go through the scalar unit.
+// `resolved`, if given, holds the device-map entry of ids[i] at position i (the sampler stores it
+// where it first numbers a node): the map itself, a random 4-byte read that costs a whole line per
+// row, is then not touched, and cache_map only says that a map is in use.
 // Rows may be padded: row r of a store starts at r * stride bytes, and vecs_per_row vectors are
 // copied (the host rounds the row up to a whole vector only where every stride has the room).
 // ---------------------------------------------------------------------------
@@ -34,6 +37,7 @@ constexpr unsigned kGatherHostLds = kGatherThreads * kHostScan * (sizeof(int64_t
 template <typename VecT, typename IdxT>
 __device__ __forceinline__ void gather_host_rows(const char* __restrict__ feat_host,
                                                  const int32_t* __restrict__ cache_map,
+                                                 const int32_t* __restrict__ resolved,
                                                  const IdxT* __restrict__ ids, int64_t n_ids, int64_t id_limit,
                                                  uint32_t vecs_per_row, int64_t host_stride, int64_t out_stride,
                                                  int log2_g, uint32_t host_blocks, char* __restrict__ out) {
@@ -67,12 +71,15 @@ __device__ __forceinline__ void gather_host_rows(const char* __restrict__ feat_h
       }
     }
   };
-  auto load_map = [&]() {
+  auto load_map = [&](int64_t base) {  // of the round whose ids are in id_ahead
 #pragma unroll
-    for (int k = 0; k < kHostScan; ++k) c_ahead[k] = id_ahead[k] >= 0 ? cache_map[id_ahead[k]] : 0;
+    for (int k = 0; k < kHostScan; ++k) {
+      c_ahead[k] = 0;
+      if (id_ahead[k] >= 0) c_ahead[k] = resolved ? resolved[base + k * kWave + lane] : cache_map[id_ahead[k]];
+    }
   };
   load_ids(first);
-  load_map();
+  load_map(first);
   load_ids(first + step);
   for (int64_t base = first; base < n_ids; base += step) {  // wave-uniform bounds
     int32_t c[kHostScan];
@@ -89,7 +96,7 @@ __device__ __forceinline__ void gather_host_rows(const char* __restrict__ feat_h
       }
       n_found += (uint32_t)__popcll(mask);
     }
-    load_map();                  // of round base + step, whose ids arrived during the last copies
+    load_map(base + step);       // of round base + step, whose ids arrived during the last copies
     load_ids(base + 2 * step);
     wave_sync();
     for (uint32_t j0 = group * kHostRowsInFlight; j0 < n_found; j0 += n_groups * kHostRowsInFlight) {
@@ -121,6 +128,7 @@ template <typename VecT, typename IdxT, int U, int R, bool kWaveRow>
 __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restrict__ feat_dev,
                                                            const char* __restrict__ feat_host,
                                                            const int32_t* __restrict__ cache_map,
+                                                           const int32_t* __restrict__ resolved,
                                                            const IdxT* __restrict__ ids,
                                                            int64_t n_ids,
                                                            const int32_t* __restrict__ n_ids_dev,
@@ -139,7 +147,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restric
   // host_blocks > 0 (only with a device map and a host store): the first host_blocks workgroups
   // take the rows in host memory, the others the rows in the device store
   if (blockIdx.x < host_blocks) {
-    gather_host_rows<VecT, IdxT>(feat_host, cache_map, ids, n_ids, id_limit, vecs_per_row, host_stride,
+    gather_host_rows<VecT, IdxT>(feat_host, cache_map, resolved, ids, n_ids, id_limit, vecs_per_row, host_stride,
                                  out_stride, log2_g, host_blocks, out);
     return;
   }
@@ -167,7 +175,11 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restric
            (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)id);
     }
     int64_t slot = id;
-    if (cache_map) {
+    if (resolved) {  // the device-map entry of ids[rr], looked up when the id was numbered
+      int32_t c = resolved[rr];
+      if (kWaveRow) c = __builtin_amdgcn_readfirstlane(c);
+      slot = c;
+    } else if (cache_map) {
       int32_t c = cache_map[id];
       if (kWaveRow) c = __builtin_amdgcn_readfirstlane(c);
       slot = c;

@@ -49,7 +49,8 @@ __global__ __launch_bounds__(kTileThreads) void k_flag(const IdxT* gid, const in
 // A first occurrence at edge q gets local id n_dst + (first occurrences before q); every edge
 // reads its id through its first occurrence.  Also clears the hop's scratch counters.  With
 // tile_offs null the workgroup scans k_flag's tile sums itself (few tiles) and workgroup 0
-// publishes the hop's source count.
+// publishes the hop's source count.  With a device map given, a new node's entry is stored beside
+// its id (S_slot), so that the retrieve of the input nodes need not look it up again.
 constexpr int kRelabelPerThread = 4;
 
 template <typename IdxT>
@@ -59,7 +60,9 @@ __global__ __launch_bounds__(kTileThreads) void k_relabel(const IdxT* gid, const
                                                           const int32_t* tile_sums, DevState* st,
                                                           int hop, int64_t num_nodes, int64_t cap_src,
                                                           IdxT* S, int32_t* node_map,
-                                                          int32_t* blk_indices) {
+                                                          int32_t* blk_indices,
+                                                          const int32_t* __restrict__ cache_map,
+                                                          int32_t* __restrict__ S_slot) {
   __shared__ int32_t fused_offs[kFuseTiles];
   __shared__ uint32_t fused_total;
   const int64_t n = st->n_edges[hop];
@@ -100,6 +103,9 @@ __global__ __launch_bounds__(kTileThreads) void k_relabel(const IdxT* gid, const
         if (local >= 0 && (int64_t)local < cap_src && (int64_t)g >= 0 && (int64_t)g < num_nodes) {
           S[local] = g;
           node_map[(int64_t)g] = local;
+          // the node's device-map entry, looked up once where the node is first numbered: the
+          // feature retrieve of the input nodes then reads its slots in sequence
+          if (cache_map) S_slot[local] = cache_map[(int64_t)g];
         } else {
           atomicOr(&st->error, kErrNewNode);
         }

@@ -31,6 +31,8 @@ struct a3_ctx {
 
   // arena (device)
   void* S = nullptr;  // local -> global, 8 bytes per entry reserved
+  int32_t* S_slot = nullptr;  // device-map entry of each local id (calls that were given a map)
+  const int32_t* last_cache_map = nullptr;  // the map whose entries S_slot holds, or null
   int32_t* blk_indptr[A3_MAX_HOPS] = {nullptr};
   int32_t* blk_indices[A3_MAX_HOPS] = {nullptr};
   int64_t* blk_eids[A3_MAX_HOPS] = {nullptr};
@@ -269,7 +271,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
   }
   if (validate) {
     hipLaunchKernelGGL(a3::k_init_seeds_checked<IdxT>, dim3(blocks_for(num_seeds, 256)), dim3(256),
-                       0, st, seeds, num_seeds, num_nodes, S, ctx->node_map, ds);
+                       0, st, seeds, num_seeds, num_nodes, S, ctx->node_map, ds, cache_map, ctx->S_slot);
     hipLaunchKernelGGL(a3::k_check_seeds<IdxT>, dim3(blocks_for(num_seeds, 256)), dim3(256), 0, st,
                        seeds, num_seeds, num_nodes, ctx->node_map, ds);
     hipLaunchKernelGGL(a3::k_set_frontier_size, dim3(1), dim3(64), 0, st, ds, (int32_t)num_seeds);
@@ -281,8 +283,11 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
     const unsigned edge_tiles = blocks_for(bound_edges[h], a3::kTile);
     // a1: degrees -> edge offsets of the block, degree bins
     a3::FrontierArgs<IdxT> fa;
-    fa.seeds = (h == 0 && !validate) ? seeds : nullptr;
+    fa.seeds = seeds;
+    fa.from_seeds = (h == 0 && !validate) ? 1 : 0;
     fa.num_seeds = num_seeds;
+    fa.cache_map = cache_map;
+    fa.S_slot = ctx->S_slot;
     fa.S = S;
     fa.node_map = ctx->node_map;
     fa.indptr = indptr;
@@ -360,7 +365,8 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
                        dim3(blocks_for(bound_edges[h], a3::kTileThreads * a3::kRelabelPerThread)),
                        dim3(a3::kTileThreads), 0, st, gid, ctx->first_pos, ctx->local_rank,
                        fuse_edges ? (const int32_t*)nullptr : ctx->tile_offs2, ctx->tile_sums2, ds, h, num_nodes,
-                       ctx->cap_dst[ctx->max_hops], S, ctx->node_map, ctx->blk_indices[h]);
+                       ctx->cap_dst[ctx->max_hops], S, ctx->node_map, ctx->blk_indices[h], cache_map,
+                       ctx->S_slot);
   }
   // leave the relabel map empty for the next call; the same kernel publishes the counts
   hipLaunchKernelGGL(a3::k_finish_call<IdxT>, dim3(blocks_for(bound_dst[num_hops], 256)), dim3(256),
@@ -374,6 +380,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
   ctx->last_bound_in = bound_dst[num_hops];
   for (int h = 0; h < num_hops; ++h) ctx->last_bound_dst[h] = bound_dst[h];
   ctx->last_num_nodes = num_nodes;
+  ctx->last_cache_map = cache_map;
   return A3_OK;
 }
 
@@ -424,9 +431,12 @@ constexpr unsigned kGatherMaxBlocks = 8192;
 constexpr unsigned kGatherHostBlocksAlone = 0;
 constexpr unsigned kGatherHostBlocksShared = 16;
 
-// strides of a gather: bytes from one row to the next in the device store, the host store, the output
+// layout of a gather: bytes from one row to the next in the device store, the host store, the
+// output; and, for the input nodes of a sampled mini-batch, their device-map entries in input
+// order (null: every id is looked up in the map)
 struct GatherStrides {
   int64_t dev, host, out;
+  const int32_t* resolved = nullptr;
 };
 
 template <typename VecT, typename IdxT, int U, int R, bool kWaveRow>
@@ -442,7 +452,7 @@ void launch_gather_as(a3_ctx* ctx, int log2_g, const void* feat_dev, const void*
   const unsigned host_blocks = (cache_map && feat_host) ? ctx->gather_host_blocks : 0u;
   hipLaunchKernelGGL((a3::k_gather<VecT, IdxT, U, R, kWaveRow>), dim3(dev_blocks + host_blocks),
                      dim3(a3::kGatherThreads), host_blocks ? a3::kGatherHostLds : 0u, ctx->stream, (const char*)feat_dev,
-                     (const char*)feat_host, cache_map, (const IdxT*)ids, n_ids, n_ids_dev, id_limit,
+                     (const char*)feat_host, cache_map, st.resolved, (const IdxT*)ids, n_ids, n_ids_dev, id_limit,
                      vpr, st.dev, st.host, st.out, log2_g, host_blocks, (char*)out);
 }
 
@@ -667,6 +677,7 @@ extern "C" int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t
   int rc = A3_OK;
   auto chk = [&](int r) { if (rc == A3_OK) rc = r; };
   chk(dev_alloc(ctx, (int64_t**)&ctx->S, ctx->cap_dst[max_hops]));
+  chk(dev_alloc(ctx, &ctx->S_slot, ctx->cap_dst[max_hops]));
   chk(dev_alloc(ctx, (int64_t**)&ctx->gid, max_edges));
   chk(dev_alloc(ctx, &ctx->first_pos, max_edges));
   chk(dev_alloc(ctx, &ctx->local_rank, max_edges));
@@ -873,6 +884,8 @@ extern "C" int a3_gather_input_features_strided(a3_ctx* ctx, const void* feat_de
   const int64_t bound = std::min(ctx->last_bound_in, out_rows);
   if (bound == 0) return A3_OK;
   A3_HIP(ctx, hipSetDevice(ctx->device));
+  // the sampling call stored the map's entries of its input nodes if it was given this map
+  if (cache_map && cache_map == ctx->last_cache_map) st.resolved = ctx->S_slot;
   return gather_enqueue(ctx, feat_dev, feat_host, cache_map, ctx->S, ctx->last_idx_bytes, bound,
                         &ctx->d_state->n_src[ctx->last_hops - 1], ctx->last_num_nodes, row_bytes, st,
                         out);

@@ -34,3 +34,18 @@ def _oracle_built():
     """The oracle is a checker: build it once per session so tests can load it."""
     from oracle import build as ob
     ob.build(force=False)
+
+
+@pytest.fixture
+def progress(request):
+    """say(msg): a line on the real stdout, past pytest's capture, so that a long test (a full-size
+    oracle run takes up to two minutes) shows which step it is at while it runs"""
+    capman = request.config.pluginmanager.getplugin("capturemanager")
+
+    def say(msg):
+        if capman is None:
+            print(msg, flush=True)
+            return
+        with capman.global_and_fixture_disabled():
+            print(msg, flush=True)
+    return say

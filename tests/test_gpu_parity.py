@@ -210,6 +210,62 @@ def test_fanout_shapes_and_edge_cases():
     ctx.close()
 
 
+def test_empty_batch_between_batches_on_a_plain_context():
+    """no seeds, on a context without A3_VALIDATE and after a call that left a frontier behind:
+    empty blocks, and the next call is unaffected"""
+    w, g, d_ip, d_ix = _graph("mini_social")
+    ctx = a3.Context(64, [5, 3])
+    cm = degree_ranked_cache(g, None, 0.3).cache_map.numpy()
+    seeds = seed_batch(w.num_nodes, 64, 3, 2)
+    _compare(ctx, w, g, d_ip, d_ix, seeds, [5, 3], cm, 2.0, 5, "before the empty batch")
+    for d_cm in (None, torch.from_numpy(cm).to(DEV)):
+        empty = ctx.sample_blocks(d_ip, d_ix, torch.zeros(0, dtype=torch.int32, device=DEV), [5, 3], d_cm, 2 * Q, 6)
+        assert empty.n_dst == [0, 0] and empty.n_src == [0, 0] and empty.n_edges == [0, 0]
+        assert empty.input_nodes.numel() == 0
+        assert [int(t[0].item()) for t in empty.blk_indptr] == [0, 0]
+    seeds = seed_batch(w.num_nodes, 50, 3, 4)
+    _compare(ctx, w, g, d_ip, d_ix, seeds, [5, 3], cm, 2.0, 7, "after the empty batch")
+    _compare(ctx, w, g, d_ip, d_ix, seeds, [5, 3], None, 1.0, 8, "after the empty batch, no map")
+    ctx.close()
+
+
+@pytest.mark.parametrize("flags", [0, a3.A3_VALIDATE])
+@pytest.mark.parametrize("host_workgroups", [0, 16])
+def test_input_rows_by_stored_map_entries_and_by_lookup_agree(flags, host_workgroups):
+    """The retrieve of a mini-batch's input nodes uses the device-map entries that the sampling call
+    stored (same map given to both calls); given an equal map at another address, or a sampling
+    call without a map, it looks every id up.  All three give the oracle's rows."""
+    w, g, d_ip, d_ix = _graph("mini_copurchase")
+    full = make_features(g.num_nodes, w.feat_dim, w.feat_dtype, feat_seed=6)
+    split = degree_ranked_cache(g, full, 0.25, pin_host=True)
+    d_cm, d_fd = split.cache_map.to(DEV), split.feat_dev.to(DEV)
+    d_cm2 = d_cm.clone()
+    ctx = a3.Context(w.batch, w.fanouts, flags=flags)
+    ctx.set_gather_host_workgroups(host_workgroups)
+    for b, gamma in enumerate((1.0, 4.0)):
+        seeds = seed_batch(w.num_nodes, w.batch, 0, b)
+        d_seeds = torch.from_numpy(seeds).to(DEV)
+        want = oracle.sample_blocks(g.indptr.numpy(), g.indices.numpy(), seeds, w.fanouts,
+                                    split.cache_map.numpy(), int(gamma * Q), b)
+        want_rows = oracle.gather_features(split.feat_dev.numpy(), split.feat_host.numpy(),
+                                           split.cache_map.numpy(), want.input_nodes)
+        n = want.n_src[-1]
+        for tag, sample_map, gather_map in (("stored entries", d_cm, d_cm), ("lookup, other address", d_cm, d_cm2),
+                                            ("lookup, sampled without a map", None, d_cm)):
+            if sample_map is None and gamma != 1.0:
+                continue
+            print(f"[case] input rows: {tag} gamma={gamma} flags={flags} host_workgroups={host_workgroups}", flush=True)
+            out = torch.full((n + 3, w.feat_dim), 7.0, dtype=w.feat_dtype, device=DEV)
+            ctx.sample_blocks_begin(d_ip, d_ix, d_seeds, w.fanouts, sample_map, int(gamma * Q), b)
+            ctx.gather_input_features(d_fd, split.feat_host, gather_map, out)
+            got = ctx.sample_blocks_end().to_host()
+            torch.cuda.synchronize()
+            blocks_equal(got, want)
+            assert out[:n].cpu().numpy().tobytes() == want_rows.tobytes()
+            assert bool((out[n:] == 7.0).all())
+    ctx.close()
+
+
 def test_isolated_nodes_and_no_eids():
     indptr = torch.tensor([0, 0, 1, 2, 2], dtype=torch.int64)
     indices = torch.tensor([2, 1], dtype=torch.int64)
