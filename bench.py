@@ -565,7 +565,7 @@ def run_policies(args):
     """Cache policies on the co-purchase-style graph: hit rate and step time of the static fill
     ranked by degree (the input generators' default), the static fill ranked by access count over
     pre-sampled mini-batches (a3_cache_count_accesses + a3_cache_rank; Sec. IV-C: "most frequently
-    accessed nodes"), and a FIFO dynamic cache that starts empty (a3_cache_fifo_update;
+    accessed nodes"), and a FIFO dynamic cache that starts empty (a3_cache_fifo_update_static;
     Sec. II-B), each under uniform and locality-aware sampling.  Markdown table."""
     import numpy as np
     import torch
@@ -657,7 +657,7 @@ def run_policies(args):
             ids = blk.input_nodes.long()
             hb = int((cm[ids] >= 0).sum().item())   # judged before the update
             ev0.record()
-            ctx.cache_fifo_update(cm, owner, state, cache, rows)
+            ctx.cache_fifo_update(cm, owner, state, cache, rows, static_scratch=True)
             ev1.record()
             torch.cuda.synchronize()
             ms_pol += ev0.elapsed_time(ev1)

@@ -263,6 +263,23 @@ int a3_cache_fifo_update(a3_ctx* ctx, int32_t* cache_map, int64_t num_nodes, int
                          int32_t* fifo_state, int64_t n_slots, void* feat_dev, int64_t row_bytes,
                          const void* ids, int32_t idx_bytes, int64_t n_ids, const void* rows);
 
+/* a3_cache_fifo_update for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results,
+ * same asynchrony; it calls no hipMalloc / hipFree and no allocating library routine.  Its scratch
+ * (one int32 per id, two per 1 024 ids) lives in a static device array of the library, 4 MiB + 8 KiB
+ * that every GPU the library runs on holds until the process ends, so
+ *   n_ids <= A3_FIFO_STATIC_MAX_IDS, A3_ERR_CAPACITY otherwise (with ids == NULL the limit applies
+ *   to the bound on the input nodes of the last sampled mini-batch: seeds x prod(1 + fanout),
+ *   at most num_nodes);
+ * the array's address on a device is looked up once, when the first context is created there.
+ * All calls on one GPU share the array: calls that overlap on one GPU (two streams, two contexts,
+ * two threads) race; calls on one stream, or ordered by events, do not.  Nothing of an earlier
+ * call's scratch contents is read. */
+#define A3_FIFO_STATIC_MAX_IDS (1 << 20)
+int a3_cache_fifo_update_static(a3_ctx* ctx, int32_t* cache_map, int64_t num_nodes, int32_t* slot_owner,
+                                int32_t* fifo_state, int64_t n_slots, void* feat_dev, int64_t row_bytes,
+                                const void* ids, int32_t idx_bytes, int64_t n_ids, const void* rows);
+
 /* Measurement aid (Sec. IV-A reports averages over runs; this gives per-call device times).
  * With A3_PROFILE every a3_sample_blocks (kind 0), a3_gather_features (kind 1) and a3_block_mean
  * (kind 2) brackets its kernels with HIP events on the context's stream.  a3_profile_read waits for the newest event

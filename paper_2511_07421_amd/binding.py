@@ -15,6 +15,7 @@ A3_MAX_FANOUT = 1024
 A3_OK, A3_ERR_INVALID_ARG, A3_ERR_CAPACITY, A3_ERR_HIP, A3_ERR_INPUT = 0, -1, -2, -3, -4
 A3_VALIDATE, A3_NO_EIDS, A3_HOST_ONLY, A3_FORCE_RADIX, A3_PROFILE = 1, 2, 4, 8, 16
 A3_PROFILE_DEPTH = 256
+A3_FIFO_STATIC_MAX_IDS = 1 << 20
 A3_PIPE_SEQUENTIAL, A3_PIPE_MODE1, A3_PIPE_MODE2 = 0, 1, 2
 A3_PIPE_MAX_WORKERS = 8
 A3_F32, A3_F16 = 0, 1
@@ -104,6 +105,8 @@ def lib():
                                            C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                                            C.c_int64, C.c_void_p]
         L.a3_cache_fifo_update.restype = C.c_int
+        L.a3_cache_fifo_update_static.argtypes = L.a3_cache_fifo_update.argtypes
+        L.a3_cache_fifo_update_static.restype = C.c_int
         L.a3_block_mean_strided.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                                             C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_int64]
         L.a3_block_mean_strided.restype = C.c_int
@@ -415,9 +418,11 @@ class Context:
 
     def cache_fifo_update(self, cache_map: torch.Tensor, slot_owner: torch.Tensor,
                           fifo_state: torch.Tensor, feat_dev: torch.Tensor, rows: torch.Tensor,
-                          ids: Optional[torch.Tensor] = None) -> None:
+                          ids: Optional[torch.Tensor] = None, static_scratch: bool = False) -> None:
         """one mini-batch through the FIFO cache, in place; ids = None: the input nodes of the last
-        sampled mini-batch, rows then being what gather_input_features wrote"""
+        sampled mini-batch, rows then being what gather_input_features wrote.  static_scratch:
+        a3_cache_fifo_update_static, the form that allocates nothing (at most
+        A3_FIFO_STATIC_MAX_IDS ids)"""
         for t in (cache_map, slot_owner, fifo_state):
             assert t.dtype == torch.int32 and t.is_contiguous()
         assert fifo_state.shape[0] >= 4
@@ -428,10 +433,11 @@ class Context:
         row_bytes = feat_dev.shape[1] * feat_dev.element_size()
         if ids is not None and ids.shape[0] == 0:
             return  # an empty tensor has no address; a null `ids` would mean "the last input nodes"
-        rc = lib().a3_cache_fifo_update(self._h, _dptr(cache_map), cache_map.shape[0], _dptr(slot_owner),
-                                        _dptr(fifo_state), slot_owner.shape[0], _dptr(feat_dev),
-                                        row_bytes, _dptr(ids), 0 if ids is None else ids.element_size(),
-                                        0 if ids is None else ids.shape[0], _dptr(rows))
+        call = lib().a3_cache_fifo_update_static if static_scratch else lib().a3_cache_fifo_update
+        rc = call(self._h, _dptr(cache_map), cache_map.shape[0], _dptr(slot_owner),
+                  _dptr(fifo_state), slot_owner.shape[0], _dptr(feat_dev),
+                  row_bytes, _dptr(ids), 0 if ids is None else ids.element_size(),
+                  0 if ids is None else ids.shape[0], _dptr(rows))
         self._check(rc)
 
 

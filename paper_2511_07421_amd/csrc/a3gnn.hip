@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -164,6 +165,32 @@ size_t sample_block_lds_bytes(uint32_t lds_per_wave, uint32_t cap, int n_waves) 
   const size_t own = (size_t)lds_per_wave * n_waves;
   const size_t hub = (size_t)a3::kHubRegion * n_waves + cap + 9 + (lds_per_wave - cap);
   return std::max(own, hub) * sizeof(uint64_t);
+}
+
+// Scratch of the FIFO update for callers that cannot allocate: one int32 per id (its rank among
+// the misses of its tile) and two per tile of 1024 ids (tile sums, tile offsets), 4 MiB + 8 KiB.
+// Every GPU the library runs on holds its own copy at its own address until the process ends;
+// host code uses the address that hipGetSymbolAddress returns for the current device, never the
+// array's name.
+constexpr int64_t kFifoStaticTiles = A3_FIFO_STATIC_MAX_IDS / a3::kTile;
+static __device__ __align__(256) int32_t scratch[A3_FIFO_STATIC_MAX_IDS + 2 * kFifoStaticTiles];
+
+constexpr int kMaxDevices = 64;
+int32_t* g_scratch_ptr[kMaxDevices] = {nullptr};
+std::mutex g_scratch_mutex;
+
+// address of `scratch` on the context's device (which the caller has made current)
+int scratch_on_device(a3_ctx* ctx, int32_t** ptr) {
+  if (ctx->device < 0 || ctx->device >= kMaxDevices)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_fifo_update_static: device ordinal above 63");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[ctx->device]) {
+    void* p = nullptr;
+    A3_HIP(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    g_scratch_ptr[ctx->device] = (int32_t*)p;
+  }
+  *ptr = g_scratch_ptr[ctx->device];
+  return A3_OK;
 }
 
 void free_all(a3_ctx* ctx) {
@@ -675,6 +702,12 @@ extern "C" int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t
   const int64_t max_items = std::max(max_edges, ctx->cap_dst[max_hops]);
   ctx->cap_tiles = (max_items + a3::kTile - 1) / a3::kTile + 1;
   int rc = A3_OK;
+  {
+    // set-up, once per device: where this device keeps the static scratch of
+    // a3_cache_fifo_update_static, so that the call itself only reads the stored address
+    int32_t* unused = nullptr;
+    if (hip_device < kMaxDevices) rc = scratch_on_device(ctx, &unused);
+  }
   auto chk = [&](int r) { if (rc == A3_OK) rc = r; };
   chk(dev_alloc(ctx, (int64_t**)&ctx->S, ctx->cap_dst[max_hops]));
   chk(dev_alloc(ctx, &ctx->S_slot, ctx->cap_dst[max_hops]));
@@ -1155,7 +1188,7 @@ extern "C" int a3_cache_rank(a3_ctx* ctx, const uint32_t* counts, int64_t num_no
 namespace {
 template <typename VecT, typename IdxT>
 void launch_fifo_apply(a3_ctx* ctx, const void* ids, int64_t n_ids, const int32_t* n_dev,
-                       const int32_t* tile_offs, const int32_t* state, int64_t n_slots,
+                       const int32_t* rank, const int32_t* tile_offs, const int32_t* state, int64_t n_slots,
                        int64_t num_nodes, int32_t* cache_map, int32_t* slot_owner, const void* rows,
                        void* feat_dev, int64_t row_bytes) {
   const uint32_t vecs = (uint32_t)(row_bytes / (int64_t)sizeof(VecT));
@@ -1163,72 +1196,119 @@ void launch_fifo_apply(a3_ctx* ctx, const void* ids, int64_t n_ids, const int32_
   while ((1u << log2_g) < vecs && log2_g < 6) ++log2_g;
   const unsigned blocks = blocks_for(n_ids << log2_g, a3::kGatherThreads);
   hipLaunchKernelGGL((a3::k_fifo_apply<VecT, IdxT>), dim3(blocks), dim3(a3::kGatherThreads), 0, ctx->stream,
-                     (const IdxT*)ids, n_ids, n_dev, ctx->fifo_rank, tile_offs, state, n_slots, num_nodes,
+                     (const IdxT*)ids, n_ids, n_dev, rank, tile_offs, state, n_slots, num_nodes,
                      cache_map, slot_owner, (const VecT*)rows, (VecT*)feat_dev, vecs, log2_g);
 }
 template <typename IdxT>
 void fifo_apply_by_width(a3_ctx* ctx, int width, const void* ids, int64_t n_ids, const int32_t* n_dev,
-                         const int32_t* tile_offs, const int32_t* state, int64_t n_slots,
+                         const int32_t* rank, const int32_t* tile_offs, const int32_t* state, int64_t n_slots,
                          int64_t num_nodes, int32_t* cache_map, int32_t* slot_owner, const void* rows,
                          void* feat_dev, int64_t row_bytes) {
   switch (width) {
-    case 16: launch_fifo_apply<a3::vec16_t, IdxT>(ctx, ids, n_ids, n_dev, tile_offs, state, n_slots, num_nodes, cache_map, slot_owner, rows, feat_dev, row_bytes); break;
-    case 8: launch_fifo_apply<a3::vec8_t, IdxT>(ctx, ids, n_ids, n_dev, tile_offs, state, n_slots, num_nodes, cache_map, slot_owner, rows, feat_dev, row_bytes); break;
-    case 4: launch_fifo_apply<a3::vec4_t, IdxT>(ctx, ids, n_ids, n_dev, tile_offs, state, n_slots, num_nodes, cache_map, slot_owner, rows, feat_dev, row_bytes); break;
-    default: launch_fifo_apply<a3::vec2_t, IdxT>(ctx, ids, n_ids, n_dev, tile_offs, state, n_slots, num_nodes, cache_map, slot_owner, rows, feat_dev, row_bytes); break;
+    case 16: launch_fifo_apply<a3::vec16_t, IdxT>(ctx, ids, n_ids, n_dev, rank, tile_offs, state, n_slots, num_nodes, cache_map, slot_owner, rows, feat_dev, row_bytes); break;
+    case 8: launch_fifo_apply<a3::vec8_t, IdxT>(ctx, ids, n_ids, n_dev, rank, tile_offs, state, n_slots, num_nodes, cache_map, slot_owner, rows, feat_dev, row_bytes); break;
+    case 4: launch_fifo_apply<a3::vec4_t, IdxT>(ctx, ids, n_ids, n_dev, rank, tile_offs, state, n_slots, num_nodes, cache_map, slot_owner, rows, feat_dev, row_bytes); break;
+    default: launch_fifo_apply<a3::vec2_t, IdxT>(ctx, ids, n_ids, n_dev, rank, tile_offs, state, n_slots, num_nodes, cache_map, slot_owner, rows, feat_dev, row_bytes); break;
   }
 }
+}  // namespace
+
+namespace {
+
+// argument checks shared by the two forms of the FIFO update; on A3_OK with *n_ids > 0 the
+// update can be queued
+int fifo_check(a3_ctx* ctx, const char* who, int32_t* cache_map, int64_t num_nodes, int32_t* slot_owner,
+               int32_t* fifo_state, int64_t n_slots, void* feat_dev, int64_t row_bytes, const void** ids,
+               int32_t* idx_bytes, int64_t* n_ids, const int32_t** n_dev, const void* rows) {
+  const std::string w(who);
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, w + ": ctx is null");
+  if (num_nodes < 0 || num_nodes > 0x7FFFFFFFLL)
+    return fail(ctx, A3_ERR_INVALID_ARG, w + ": num_nodes must be in [0, 2^31-1]");
+  if (n_slots < 1 || n_slots > 0x7FFFFFFFLL)
+    return fail(ctx, A3_ERR_INVALID_ARG, w + ": n_slots must be in [1, 2^31-1]");
+  if (row_bytes <= 0 || (row_bytes & 1) || row_bytes > (1ll << 30))
+    return fail(ctx, A3_ERR_INVALID_ARG, w + ": row_bytes must be positive, even, at most 2^30");
+  if (!cache_map || !slot_owner || !fifo_state || !feat_dev || !rows)
+    return fail(ctx, A3_ERR_INVALID_ARG, w + ": a required pointer is null");
+  const int rc = resolve_ids(ctx, who, ids, idx_bytes, n_ids, n_dev);
+  if (rc != A3_OK) return rc;
+  if (ctx->flags & A3_HOST_ONLY) return fail(ctx, A3_ERR_HIP, w + ": context was created without a device");
+  if (((uintptr_t)feat_dev | (uintptr_t)rows) & 1)
+    return fail(ctx, A3_ERR_INVALID_ARG, w + ": buffers must be 2-byte aligned");
+  if (too_many_threads(*n_ids * 64)) return fail(ctx, A3_ERR_CAPACITY, w + ": more than 2^26 ids in one call");
+  return A3_OK;
+}
+
+// the three launches of one update; rank [n_ids], tile_sums and tile_offs [tiles of 1024 ids]
+int fifo_enqueue(a3_ctx* ctx, int32_t* cache_map, int64_t num_nodes, int32_t* slot_owner, int32_t* fifo_state,
+                 int64_t n_slots, void* feat_dev, int64_t row_bytes, const void* ids, int32_t idx_bytes,
+                 int64_t n_ids, const int32_t* n_dev, const void* rows, int32_t* rank, int32_t* tile_sums,
+                 int32_t* tile_offs) {
+  const int64_t n_tiles = (n_ids + a3::kTile - 1) / a3::kTile;
+  if (idx_bytes == 4)
+    hipLaunchKernelGGL(a3::k_fifo_flag<int32_t>, dim3((unsigned)n_tiles), dim3(a3::kTileThreads), 0, ctx->stream,
+                       (const int32_t*)ids, n_ids, n_dev, cache_map, num_nodes, rank, tile_sums);
+  else
+    hipLaunchKernelGGL(a3::k_fifo_flag<int64_t>, dim3((unsigned)n_tiles), dim3(a3::kTileThreads), 0, ctx->stream,
+                       (const int64_t*)ids, n_ids, n_dev, cache_map, num_nodes, rank, tile_sums);
+  hipLaunchKernelGGL(a3::k_fifo_scan, dim3(1), dim3(a3::kTileThreads), 0, ctx->stream, tile_sums, tile_offs,
+                     n_tiles, fifo_state, n_slots);
+  const uintptr_t align_bits = (uintptr_t)feat_dev | (uintptr_t)rows | (uintptr_t)row_bytes;
+  int width = 16;
+  while (width > 2 && (align_bits & (uintptr_t)(width - 1))) width >>= 1;
+  if (idx_bytes == 4)
+    fifo_apply_by_width<int32_t>(ctx, width, ids, n_ids, n_dev, rank, tile_offs, fifo_state, n_slots, num_nodes,
+                                 cache_map, slot_owner, rows, feat_dev, row_bytes);
+  else
+    fifo_apply_by_width<int64_t>(ctx, width, ids, n_ids, n_dev, rank, tile_offs, fifo_state, n_slots, num_nodes,
+                                 cache_map, slot_owner, rows, feat_dev, row_bytes);
+  A3_HIP(ctx, hipGetLastError());
+  return A3_OK;
+}
+
 }  // namespace
 
 extern "C" int a3_cache_fifo_update(a3_ctx* ctx, int32_t* cache_map, int64_t num_nodes,
                                     int32_t* slot_owner, int32_t* fifo_state, int64_t n_slots,
                                     void* feat_dev, int64_t row_bytes, const void* ids,
                                     int32_t idx_bytes, int64_t n_ids, const void* rows) {
-  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_cache_fifo_update: ctx is null");
-  if (num_nodes < 0 || num_nodes > 0x7FFFFFFFLL)
-    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_fifo_update: num_nodes must be in [0, 2^31-1]");
-  if (n_slots < 1 || n_slots > 0x7FFFFFFFLL)
-    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_fifo_update: n_slots must be in [1, 2^31-1]");
-  if (row_bytes <= 0 || (row_bytes & 1) || row_bytes > (1ll << 30))
-    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_fifo_update: row_bytes must be positive, even, at most 2^30");
-  if (!cache_map || !slot_owner || !fifo_state || !feat_dev || !rows)
-    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_fifo_update: a required pointer is null");
   const int32_t* n_dev = nullptr;
-  int rc = resolve_ids(ctx, "a3_cache_fifo_update", &ids, &idx_bytes, &n_ids, &n_dev);
+  int rc = fifo_check(ctx, "a3_cache_fifo_update", cache_map, num_nodes, slot_owner, fifo_state, n_slots,
+                      feat_dev, row_bytes, &ids, &idx_bytes, &n_ids, &n_dev, rows);
   if (rc != A3_OK) return rc;
-  if (ctx->flags & A3_HOST_ONLY)
-    return fail(ctx, A3_ERR_HIP, "a3_cache_fifo_update: context was created without a device");
-  const uintptr_t align_bits = (uintptr_t)feat_dev | (uintptr_t)rows | (uintptr_t)row_bytes;
-  if (align_bits & 1)
-    return fail(ctx, A3_ERR_INVALID_ARG, "a3_cache_fifo_update: buffers must be 2-byte aligned");
   if (n_ids == 0) return A3_OK;
-  if (too_many_threads(n_ids * 64))
-    return fail(ctx, A3_ERR_CAPACITY, "a3_cache_fifo_update: more than 2^26 ids in one call");
   A3_HIP(ctx, hipSetDevice(ctx->device));
   const int64_t n_tiles = (n_ids + a3::kTile - 1) / a3::kTile;
   rc = ensure_buffer(ctx, &ctx->fifo_rank, &ctx->fifo_rank_cap, n_ids);
   if (rc == A3_OK) rc = ensure_buffer(ctx, &ctx->fifo_tiles, &ctx->fifo_tiles_cap, 2 * n_tiles);
   if (rc != A3_OK) return rc;
-  int32_t* tile_sums = ctx->fifo_tiles;
-  int32_t* tile_offs = ctx->fifo_tiles + n_tiles;
-  if (idx_bytes == 4)
-    hipLaunchKernelGGL(a3::k_fifo_flag<int32_t>, dim3((unsigned)n_tiles), dim3(a3::kTileThreads), 0, ctx->stream,
-                       (const int32_t*)ids, n_ids, n_dev, cache_map, num_nodes, ctx->fifo_rank, tile_sums);
-  else
-    hipLaunchKernelGGL(a3::k_fifo_flag<int64_t>, dim3((unsigned)n_tiles), dim3(a3::kTileThreads), 0, ctx->stream,
-                       (const int64_t*)ids, n_ids, n_dev, cache_map, num_nodes, ctx->fifo_rank, tile_sums);
-  hipLaunchKernelGGL(a3::k_fifo_scan, dim3(1), dim3(a3::kTileThreads), 0, ctx->stream, tile_sums, tile_offs,
-                     n_tiles, fifo_state, n_slots);
-  int width = 16;
-  while (width > 2 && (align_bits & (uintptr_t)(width - 1))) width >>= 1;
-  if (idx_bytes == 4)
-    fifo_apply_by_width<int32_t>(ctx, width, ids, n_ids, n_dev, tile_offs, fifo_state, n_slots, num_nodes,
-                                 cache_map, slot_owner, rows, feat_dev, row_bytes);
-  else
-    fifo_apply_by_width<int64_t>(ctx, width, ids, n_ids, n_dev, tile_offs, fifo_state, n_slots, num_nodes,
-                                 cache_map, slot_owner, rows, feat_dev, row_bytes);
-  A3_HIP(ctx, hipGetLastError());
-  return A3_OK;
+  return fifo_enqueue(ctx, cache_map, num_nodes, slot_owner, fifo_state, n_slots, feat_dev, row_bytes, ids,
+                      idx_bytes, n_ids, n_dev, rows, ctx->fifo_rank, ctx->fifo_tiles, ctx->fifo_tiles + n_tiles);
+}
+
+extern "C" int a3_cache_fifo_update_static(a3_ctx* ctx, int32_t* cache_map, int64_t num_nodes,
+                                           int32_t* slot_owner, int32_t* fifo_state, int64_t n_slots,
+                                           void* feat_dev, int64_t row_bytes, const void* ids,
+                                           int32_t idx_bytes, int64_t n_ids, const void* rows) {
+  const int32_t* n_dev = nullptr;
+  int rc = fifo_check(ctx, "a3_cache_fifo_update_static", cache_map, num_nodes, slot_owner, fifo_state,
+                      n_slots, feat_dev, row_bytes, &ids, &idx_bytes, &n_ids, &n_dev, rows);
+  if (rc != A3_OK) return rc;
+  // with ids == NULL, n_ids is the launch bound of the last sampled mini-batch's input nodes
+  if (n_ids > A3_FIFO_STATIC_MAX_IDS)
+    return fail(ctx, A3_ERR_CAPACITY,
+                "a3_cache_fifo_update_static: more than A3_FIFO_STATIC_MAX_IDS ids (for ids == NULL: the bound "
+                "on the input nodes of the last sampled mini-batch); use a3_cache_fifo_update");
+  if (n_ids == 0) return A3_OK;
+  A3_HIP(ctx, hipSetDevice(ctx->device));
+  int32_t* ptr = nullptr;
+  rc = scratch_on_device(ctx, &ptr);
+  if (rc != A3_OK) return rc;
+  // the kernels write every scratch entry they later read (a rank per id, a sum per launched
+  // tile), so nothing of an earlier call's contents has to be cleared
+  return fifo_enqueue(ctx, cache_map, num_nodes, slot_owner, fifo_state, n_slots, feat_dev, row_bytes, ids,
+                      idx_bytes, n_ids, n_dev, rows, ptr, ptr + A3_FIFO_STATIC_MAX_IDS,
+                      ptr + A3_FIFO_STATIC_MAX_IDS + kFifoStaticTiles);
 }
 
 extern "C" int a3_profile_read(a3_ctx* ctx, int kind, float* ms, int max, int* n) {

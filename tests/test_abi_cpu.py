@@ -196,15 +196,17 @@ def test_cache_policy_argument_errors(L):
     assert L.a3_cache_rank(h, None, 10, 2, p, None) == a3.A3_ERR_INVALID_ARG
     assert L.a3_cache_rank(h, p, 10, 2, p, None) == a3.A3_ERR_HIP
 
-    def fifo(cm=p, n=10, owner=p, st=p, slots=4, feat=p, rb=8, ids=p, ib=4, n_ids=2, rows=p):
-        return L.a3_cache_fifo_update(h, cm, n, owner, st, slots, feat, rb, ids, ib, n_ids, rows)
+    # the allocating form and the one on static scratch check their arguments alike
+    for call in (L.a3_cache_fifo_update, L.a3_cache_fifo_update_static):
+        def fifo(cm=p, n=10, owner=p, st=p, slots=4, feat=p, rb=8, ids=p, ib=4, n_ids=2, rows=p):
+            return call(h, cm, n, owner, st, slots, feat, rb, ids, ib, n_ids, rows)
 
-    assert fifo(cm=None) == a3.A3_ERR_INVALID_ARG
-    assert fifo(slots=0) == a3.A3_ERR_INVALID_ARG
-    assert fifo(rb=7) == a3.A3_ERR_INVALID_ARG
-    assert fifo(rows=None) == a3.A3_ERR_INVALID_ARG
-    assert fifo(ib=3) == a3.A3_ERR_INVALID_ARG
-    assert fifo() == a3.A3_ERR_HIP
+        assert fifo(cm=None) == a3.A3_ERR_INVALID_ARG
+        assert fifo(slots=0) == a3.A3_ERR_INVALID_ARG
+        assert fifo(rb=7) == a3.A3_ERR_INVALID_ARG
+        assert fifo(rows=None) == a3.A3_ERR_INVALID_ARG
+        assert fifo(ib=3) == a3.A3_ERR_INVALID_ARG
+        assert fifo() == a3.A3_ERR_HIP
     assert L.a3_destroy(h) == a3.A3_OK
 
 
