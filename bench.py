@@ -32,8 +32,6 @@ OPS_PER_SLOT = (20 * 4 + 20) / 4 + 1
 HEADLINE = "citation"
 OTHERS = ["social", "copurchase"]
 METRIC = "sampled edges/s + feature-gather GB/s (% of HBM peak) per mini-batch, 1 GPU"
-# seeds per oracle call of the CPU baseline where a whole mini-batch outlasts the budget
-ORACLE_SLICE = 512
 
 
 def parse():
@@ -129,6 +127,7 @@ def measure(args, name, headline, legs):
     n_edges = n_in = 0
     last_ids = None
     last_blocks = None
+    slow_paths = {}
 
     def step(b, timed):
         nonlocal n_edges, n_in, last_ids, last_blocks
@@ -140,6 +139,8 @@ def measure(args, name, headline, legs):
         rows = blocks.n_src[-1]
         assert rows <= cap_rows
         if timed:
+            for key, val in ctx.sample_stats().items():
+                slow_paths[key] = max(val, slow_paths.get(key, 0)) if key == "weight_classes" else slow_paths.get(key, 0) + val
             n_edges += sum(blocks.n_edges)
             n_in += rows
             last_ids = blocks.input_nodes
@@ -182,11 +183,12 @@ def measure(args, name, headline, legs):
     hit_rate = int((d_cm[ids_l] >= 0).sum().item()) / ids_l.numel() if ids_l.numel() else 1.0
 
     # neighbour slots the last timed batch had to draw for (nodes with degree above the fanout)
-    scanned = 0
+    scanned_per_hop = []
     for h, f in enumerate(w.fanouts):
         dst = ids_l[:last_blocks.n_dst[h]]
         deg = g.indptr[dst + 1] - g.indptr[dst]
-        scanned += int(deg[deg > f].sum().item())
+        scanned_per_hop.append(int(deg[deg > f].sum().item()))
+    scanned = sum(scanned_per_hop)
     scan_rate = scanned / (ms_sample / K * 1e-3)
 
     # counters cannot be read from inside this process: the figure comes from the committed
@@ -236,6 +238,8 @@ def measure(args, name, headline, legs):
         "input_rows_per_step": n_in / K,
         "cache_hit_rate": hit_rate,
         "scanned_slots_per_step": scanned,
+        # nodes of the K timed steps that left the sampler's usual path (a3_sample_stats)
+        "slow_path_nodes": slow_paths,
         "roofline_sampling": {"kernel": "k_sample (all hops, with the relabel kernels around it)",
                               "bound": "alu", "achieved": scan_rate * OPS_PER_SLOT / 1e12,
                               "peak": ALU_PEAK_TOPS, "unit": "Tops/s (32-bit integer lane-operations)",
@@ -389,54 +393,57 @@ def measure(args, name, headline, legs):
             oracle.gather_features(fd, fh, cm_small, np.arange(ids.shape[0], dtype=np.int64))
             return time.perf_counter() - c0
 
-        # The oracle as it stands, single-threaded, on a bounded sample: slices of the timed
-        # mini-batches' seed lists, each sampled as a mini-batch of its own with its mini-batch's
-        # rng_seed, until the budget is spent.  A whole mini-batch of `citation` takes the oracle
-        # about two minutes; its parity with the GPU path at full size is the tests' business.
-        n_slice = min(batch, ORACLE_SLICE)
-        units = [(W + j // (batch // n_slice), (j % (batch // n_slice)) * n_slice)
-                 for j in range(K * (batch // n_slice))]
-        spent, done, o_edges, o_rows, o_sample, o_gather = 0.0, 0, 0, 0, 0.0, 0.0
+        # The oracle as it stands, single-threaded, on a bounded sample of the last timed
+        # mini-batch (all its seeds, same rng_seed): its first hop, which also tells how long the
+        # oracle takes per scanned neighbour slot, then as many of its hops as that rate predicts
+        # to fit the budget (the slots each hop scans are known from the GPU's blocks).  A whole
+        # mini-batch of `citation` takes the oracle about two minutes (its parity with the GPU path
+        # at full size is the tests' business); its first two hops take about twenty seconds.
+        H = len(w.fanouts)
         seeds_host = {}
 
-        def one_unit(u):
-            b, s0 = u
+        def oracle_run(b, hops):
             if b not in seeds_host:
                 seeds_host[b] = seeds[b].cpu().numpy()
             c0 = time.perf_counter()
-            ob = oracle.sample_blocks(ip_h, ix_h, seeds_host[b][s0:s0 + n_slice], w.fanouts, cm_h, bias_q16, b)
+            ob = oracle.sample_blocks(ip_h, ix_h, seeds_host[b], w.fanouts[:hops], cm_h, bias_q16, b)
             return ob, time.perf_counter() - c0
 
-        while spent < args.cpu_seconds and done < len(units):
-            ob, dt = one_unit(units[done])
+        b_last = W + K - 1
+        ob, dt = oracle_run(b_last, 1)
+        dg = oracle_rows(ob.input_nodes.astype(np.int64))
+        spent, best = dt + dg, (1, ob, dt, dg)
+        per_slot = dt / max(scanned_per_hop[0], 1)
+        hops = 1
+        # (the one-hop run overstates the cost per slot: its fixed costs are spread over few slots)
+        while hops < H and per_slot * sum(scanned_per_hop[:hops + 1]) <= 2.0 * args.cpu_seconds:
+            hops += 1
+        if hops > 1:
+            ob, dt = oracle_run(b_last, hops)
             dg = oracle_rows(ob.input_nodes.astype(np.int64))
-            o_edges += sum(ob.n_edges)
-            o_rows += ob.n_src[-1]
-            o_sample += dt
-            o_gather += dg
             spent += dt + dg
-            done += 1
+            best = (hops, ob, dt, dg)
+        hops, ob, dt, dg = best
         result["cpu_baseline"] = {
-            "value": o_edges / spent, "unit": "sampled edges/s", "cores": 1, "kind": "oracle",
-            "sample": "%d mini-batches of %d seeds each (consecutive slices of the seed lists of the timed "
-                      "mini-batches of workload %s, same rng_seed), sampling + gather, %.1f s of CPU work"
-                      % (done, n_slice, w.name, spent),
-            "gather_GBps": o_rows * row_bytes / max(o_gather, 1e-9) / 1e9,
-            "ms_sample_per_call": o_sample * 1e3 / done, "ms_gather_per_call": o_gather * 1e3 / done,
-            "edges_per_call": o_edges / done,
+            "value": sum(ob.n_edges) / (dt + dg), "unit": "sampled edges/s", "cores": 1, "kind": "oracle",
+            "sample": "the first %d of %d hops of the last timed mini-batch of workload %s (all its seeds, same "
+                      "rng_seed), sampling + gather of that run's input rows: %d edges in %.1f s; %.1f s of CPU "
+                      "work with the one-hop run before it" % (hops, H, w.name, sum(ob.n_edges), dt + dg, spent),
+            "hops": hops, "edges": sum(ob.n_edges),
+            "gather_GBps": ob.n_src[-1] * row_bytes / max(dg, 1e-9) / 1e9,
+            "ms_sample": dt * 1e3, "ms_gather": dg * 1e3,
         }
-        # the unchanged oracle over independent slices, one per thread, on the host's cores (its C
-        # code runs outside the interpreter lock); skipped where one slice outlasts the budget
-        n_thr = min(16, os.cpu_count() or 1, len(units) - done)
-        if n_thr > 1 and spent / done <= args.cpu_seconds:
+        # the unchanged oracle over independent mini-batches, one per thread, on the host's cores
+        # (its C code runs outside the interpreter lock), the same number of hops each
+        n_thr = min(16, os.cpu_count() or 1, K - 1)
+        if n_thr > 1:
             from concurrent.futures import ThreadPoolExecutor
-            todo = units[done:done + n_thr]
-            for b, _ in todo:
-                if b not in seeds_host:
-                    seeds_host[b] = seeds[b].cpu().numpy()
+            todo = list(range(W, W + n_thr))
+            for b in todo:
+                seeds_host[b] = seeds[b].cpu().numpy()
             c0 = time.perf_counter()
             with ThreadPoolExecutor(n_thr) as pool:
-                a_edges = sum(sum(ob.n_edges) for ob, _ in pool.map(one_unit, todo))
+                a_edges = sum(sum(o.n_edges) for o, _ in pool.map(lambda b: oracle_run(b, hops), todo))
             a_s = time.perf_counter() - c0
             model = ""
             try:
@@ -447,7 +454,8 @@ def measure(args, name, headline, legs):
             result["cpu_baseline_all_cores"] = {
                 "value": a_edges / a_s, "unit": "sampled edges/s (sampling + reindex, no gather)",
                 "cores": n_thr, "kind": "oracle",
-                "sample": "%d further slices of %d seeds, one per thread, %.1f s wall" % (n_thr, n_slice, a_s),
+                "sample": "the first %d hops of %d further timed mini-batches, one per thread, %.1f s wall"
+                          % (hops, n_thr, a_s),
                 "cpu_model": model,
             }
         # whole timed mini-batches on the library's own multi-threaded host sampler (the paper's

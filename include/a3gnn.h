@@ -3,18 +3,21 @@
  * Automatic GNN Training on CPU-GPU Heterogeneous Platforms") on one AMD
  * MI355X (gfx950).  C ABI; every pointer is marked host or device.
  *
- * The path (paper Alg. 0, "Sampling" and "Batch Generating" stages):
+ * Listings of the paper are cited by their order of appearance: Alg. 1 "Distributed GNN Training
+ * with Multi-GPUs", Alg. 2 "Weighted Reservoir Sampling" (Alg. 3 is the PPO auto-tuner).
+ *
+ * The path (paper Alg. 1, "Sampling" and "Batch Generating" stages):
  *   1. multi-hop fanout neighbour sampling from a seed set (Sec. III-A), each
- *      neighbourhood sampled by weighted reservoir sampling (Alg. 1) with a
+ *      neighbourhood sampled by weighted reservoir sampling (Alg. 2) with a
  *      larger weight, the bias rate gamma, on neighbours whose feature row is
  *      already in the device cache (locality-aware sampling);
- *   2. reindex (Alg. 0 line 7): global ids -> local ids with duplicates
+ *   2. reindex (Alg. 1 line 7): global ids -> local ids with duplicates
  *      eliminated, one bipartite block in CSR form per hop;
- *   3. feature_retrieve (Alg. 0 line 10): the input nodes' feature rows are
+ *   3. feature_retrieve (Alg. 1 line 10): the input nodes' feature rows are
  *      copied from the device cache or from the host store, as the device map
  *      (Sec. III, feature cache module) says.
  *
- * Determinism.  rand(0,1) of Alg. 1 line 2 is a Philox4x32-10 draw x keyed on
+ * Determinism.  rand(0,1) of Alg. 2 line 2 is a Philox4x32-10 draw x keyed on
  * (rng_seed, hop, node id, neighbour slot); u = (x+1)/2^32.  The key
  * k = u^(1/w) is compared in the log domain with integers only:
  * K = floor((-log2(u) in Q32) * 65536 / w_q16), smaller is better, ties go to
@@ -67,7 +70,7 @@ int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t max_seeds,
 int a3_destroy(a3_ctx* ctx);
 /* hipStream_t for subsequent calls; pending work on the old stream is waited for. */
 int a3_set_stream(a3_ctx* ctx, void* hip_stream);
-/* Tuning of the feature retrieve (Alg. 0 line 10) where both stores are given: n workgroups of
+/* Tuning of the feature retrieve (Alg. 1 line 10) where both stores are given: n workgroups of
  * each launch are set aside for the rows in host memory and the others copy the device rows.
  * n = 0, a context's default: none are, every workgroup copies rows of both stores as they come,
  * the fastest when the retrieve has the GPU to itself.  A small n (16 fill a PCIe 5.0 x16 link)
@@ -97,7 +100,7 @@ typedef struct {
   void* input_nodes;                 /* device [n_src[num_hops-1]], idx_bytes wide: global id of local id */
 } a3_blocks;
 
-/* Sampling + reindex (Sec. III-A, Alg. 1, Alg. 0 line 7).
+/* Sampling + reindex (Sec. III-A, Alg. 2, Alg. 1 line 7).
  *   indptr      device int64 [num_nodes + 1], CSR row starts.
  *   indices     device int32 (idx_bytes = 4) or int64 (idx_bytes = 8) [indptr[num_nodes]];
  *               rows sorted, no repeated neighbour (not checked).
@@ -146,7 +149,18 @@ int a3_sample_blocks_begin(a3_ctx* ctx, const int64_t* indptr, const void* indic
                            const int32_t* cache_map, uint32_t bias_q16, uint64_t rng_seed);
 int a3_sample_blocks_end(a3_ctx* ctx, a3_blocks* out);
 
-/* Feature retrieve (Alg. 0 line 10): out[i,:] = feat_dev[c,:] if
+/* Which paths the most recent ended a3_sample_blocks(_end) took, for tuning (Sec. III-A: the bias
+ * rate and the cache decide how often the weights matter).  stats (host) receives
+ *   [0] weight classes met in the device map: bit 0 some node cached, bit 1 some node not
+ *       (0 for a call without weights; 3 = the weighted selection was in use);
+ *   [1] wide nodes (65 ... 4096 neighbours) and [2] hubs that the first sampling launch of a hop
+ *       could not decide from their best draws alone (fewer than `fanout` cached among them, or odd
+ *       list sizes) and left to the slower second launch;
+ *   [3] nodes selected by the exhaustive bit-by-bit path (about one in 10^5 by design).
+ * A3_ERR_INVALID_ARG before the first ended call or while a begun call is pending. */
+int a3_sample_stats(a3_ctx* ctx, int64_t stats[4]);
+
+/* Feature retrieve (Alg. 1 line 10): out[i,:] = feat_dev[c,:] if
  * c = cache_map[ids[i]] >= 0, else feat_host[-c-1,:].
  *   feat_dev    device [n_cached, row_bytes]; may be NULL if no id maps to it.
  *   feat_host   host memory that the device can read (pinned, mapped)
@@ -193,7 +207,7 @@ int a3_gather_input_features_strided(a3_ctx* ctx, const void* feat_dev, int64_t 
                                      const int32_t* cache_map, int64_t row_bytes, void* out,
                                      int64_t out_stride, int64_t out_rows);
 
-/* Neighbour aggregation of one block, the step that consumes the path's output (Alg. 0 "forward";
+/* Neighbour aggregation of one block, the step that consumes the path's output (Alg. 1 "forward";
  * the evaluation's GraphSAGE aggregates with the mean, Sec. IV-A):
  *   out[i,:] = mean over e in [blk_indptr[i], blk_indptr[i+1]) of x[blk_indices[e],:],  i < n_dst;
  * a destination without sampled edges gets zeros.

@@ -3,7 +3,7 @@
  *
  * The paper's design space lets sampling run on the CPU with n worker processes instead of on
  * the GPU (Tab. I: "Sampling Device", "Workers"; Sec. III).  This sampler is that choice: the
- * same locality-aware multi-hop sampling and reindex (Sec. III-A, Alg. 1, Alg. 0 line 7), the same
+ * same locality-aware multi-hop sampling and reindex (Sec. III-A, Alg. 2, Alg. 1 line 7), the same
  * draws, keys and orderings as the GPU library (see a3gnn.h, "Determinism"), on host pointers,
  * with n worker threads.  For given inputs both devices produce identical arrays.
  * It is called explicitly; the GPU entry points never route through it.
@@ -35,7 +35,7 @@ int a3cpu_destroy(a3cpu_sampler* s);
 int a3cpu_workers(const a3cpu_sampler* s);
 const char* a3cpu_last_error(const a3cpu_sampler* s);
 
-/* The sampler computes its draws (Philox4x32-10, the generator behind Alg. 1's random keys in
+/* The sampler computes its draws (Philox4x32-10, the generator behind Alg. 2's random keys in
  * this library) with the widest vector instructions the CPU has: AVX-512, AVX2 or none.  This
  * check runs every form the CPU supports over the same counters, keys, bars and row ends and
  * compares what they list with the scalar form's list.  Returns the number of cases that differ

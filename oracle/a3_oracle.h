@@ -7,16 +7,18 @@
  * call it, and it shares no source with the GPU library.
  *
  * What it follows (paper: "Towards Affordable, Adaptive and Automatic GNN
- * Training on CPU-GPU Heterogeneous Platforms"):
- *   - Alg. 1 (weighted reservoir sampling): every neighbour u_j of v_i gets a
+ * Training on CPU-GPU Heterogeneous Platforms"; its listings are cited in
+ * order of appearance: Alg. 1 "Distributed GNN Training with Multi-GPUs",
+ * Alg. 2 "Weighted Reservoir Sampling"):
+ *   - Alg. 2 (weighted reservoir sampling): every neighbour u_j of v_i gets a
  *     key k_j = rand(0,1)^(1/w_j); the m neighbours with the largest keys are
  *     kept.  Sec. III-A: cached vertices get the larger weight, set by the
  *     bias rate gamma; gamma = 1 is plain uniform sampling.
  *   - Sec. III-A, multi-hop: the seed set is expanded hop by hop with the
  *     given fanouts.
- *   - Alg. 0 "reindex": global ids are renumbered to local ids, duplicates
+ *   - Alg. 1 "reindex": global ids are renumbered to local ids, duplicates
  *     eliminated.
- *   - Alg. 0 "feature_retrieve": feature rows of the input nodes are copied
+ *   - Alg. 1 "feature_retrieve": feature rows of the input nodes are copied
  *     from the device cache or from the host store, as the device map says.
  *
  * Readings where the paper is silent (random source, arithmetic of pow,
@@ -25,7 +27,8 @@
  * Pins: Philox against the published known-answer vectors of Salmon et al.
  * (SC'11); fixlog2 against exact powers of two, a high-precision logarithm
  * and monotonicity; the key against floor(-log2(u)/w * 2^32) in exact
- * arithmetic; selection against Alg. 1 transcribed as a stream, against the
+ * arithmetic; selection against a one-pass bounded-heap reservoir (a library
+ * routine), against the
  * top-m of exact real keys u^(1/w), against the A-Res inclusion law by
  * chi-square and brute-force enumeration; relabel against brute force on
  * tiny graphs; gather against a library index_select; the block mean against
@@ -51,7 +54,7 @@ void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t
 
 /* The draw of slot `slot` of node `node` at hop `hop`: word (slot & 3) of the
  * Philox block with counter (slot >> 2, lo32(node), hi32(node), hop) and key
- * (lo32(rng_seed), hi32(rng_seed)).  Stands for rand(0,1) of Alg. 1 line 2
+ * (lo32(rng_seed), hi32(rng_seed)).  Stands for rand(0,1) of Alg. 2 line 2
  * through u = (x + 1) / 2^32, so u lies in (0, 1]. */
 uint32_t oracle_draw(uint64_t rng_seed, uint32_t hop, uint64_t node, uint64_t slot);
 
@@ -59,13 +62,13 @@ uint32_t oracle_draw(uint64_t rng_seed, uint32_t hop, uint64_t node, uint64_t sl
  * shift-and-square recurrence on a Q1.31 mantissa, integers only. */
 uint64_t oracle_fixlog2_q32(uint64_t U);
 
-/* Alg. 1 line 2 in the log domain.  k = u^(1/w) descending is the same order
+/* Alg. 2 line 2 in the log domain.  k = u^(1/w) descending is the same order
  * as -log2(u)/w ascending; the key is K = floor(((L << 16)) / w_q16) with
  * L = 32*2^32 - fixlog2(x + 1) = -log2(u) in Q32 and w_q16 the weight in
  * Q16.16.  Smaller K is better. */
 uint64_t oracle_key(uint32_t x, uint32_t w_q16);
 
-/* Alg. 1 for one node: choose m = min(fanout, deg) slots out of deg.
+/* Alg. 2 for one node: choose m = min(fanout, deg) slots out of deg.
  * weights_q16[s] is the weight of slot s in Q16.16 (NULL: all equal).
  * If deg <= fanout all slots are taken and no draw is made.  Otherwise the m
  * slots that are smallest under the total order (K ascending, x descending,
@@ -104,14 +107,14 @@ int oracle_sample_blocks(const int64_t* indptr, const void* indices, int32_t idx
 
 void oracle_free_blocks(oracle_blocks* b);
 
-/* Alg. 0 feature_retrieve: out[i] = feat_dev[c] if c = cache_map[ids[i]] >= 0
+/* Alg. 1 feature_retrieve: out[i] = feat_dev[c] if c = cache_map[ids[i]] >= 0
  * else feat_host[-c - 1]; rows are row_bytes wide and copied byte for byte.
  * Returns 0, or -1 on a bad argument. */
 int oracle_gather_features(const void* feat_dev, const void* feat_host, const int32_t* cache_map,
                            const void* ids, int32_t idx_bytes, int64_t n_ids, int64_t row_bytes,
                            void* out);
 
-/* Neighbour aggregation of one block (Alg. 0 "forward" with the GraphSAGE
+/* Neighbour aggregation of one block (Alg. 1 "forward" with the GraphSAGE
  * mean aggregator the evaluation uses, Sec. IV-A): for every destination i,
  *   out[i][c] = (1 / d_i) * sum over e in [blk_indptr[i], blk_indptr[i+1]) of x[blk_indices[e]][c],
  * d_i the number of sampled edges of i; a destination without edges gets zeros.

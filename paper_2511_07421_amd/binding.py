@@ -76,6 +76,8 @@ def lib():
         L.a3_sample_blocks_begin.restype = C.c_int
         L.a3_sample_blocks_end.argtypes = [C.c_void_p, C.POINTER(_CBlocks)]
         L.a3_sample_blocks_end.restype = C.c_int
+        L.a3_sample_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
+        L.a3_sample_stats.restype = C.c_int
         L.a3_gather_input_features.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                C.c_int64, C.c_void_p, C.c_int64]
         L.a3_gather_input_features.restype = C.c_int
@@ -227,7 +229,10 @@ def _dptr(t: Optional[torch.Tensor]):
 
 def _row_stride(t: Optional[torch.Tensor]) -> int:
     """Bytes from one row of a 2-D tensor to the next.  Rows must be dense (unit stride inside a
-    row) but may be padded: a column slice of a wider buffer, t = buf[:, :dim], is accepted."""
+    row) but may be padded: a column slice of a wider buffer, t = buf[:, :dim], is accepted.
+    For an OUTPUT tensor the columns of buf beyond dim are padding, not data: where every stride
+    in use is a multiple of 16 bytes, a row is copied up to the next multiple of 16 bytes, so up
+    to 14 bytes of buf after each out row receive padding bytes of the source row."""
     if t is None:
         return 0
     assert t.dim() == 2 and (t.shape[1] == 1 or t.stride(1) == 1), "rows must be dense"
@@ -328,10 +333,19 @@ class Context:
         self._check(lib().a3_sample_blocks_end(self._h, C.byref(cb)))
         return Blocks(cb, *self._begun)
 
+    def sample_stats(self) -> dict:
+        """which paths the last ended sampling call took (see a3_sample_stats)"""
+        buf = (C.c_int64 * 4)()
+        self._check(lib().a3_sample_stats(self._h, buf))
+        return {"weight_classes": int(buf[0]), "deferred_wide_nodes": int(buf[1]),
+                "deferred_hubs": int(buf[2]), "exhaustive_nodes": int(buf[3])}
+
     def gather_input_features(self, feat_dev: Optional[torch.Tensor],
                               feat_host: Optional[torch.Tensor], cache_map: Optional[torch.Tensor],
                               out: torch.Tensor) -> torch.Tensor:
-        """rows of the last sampled input nodes -> out[:n]; may be queued before sample_blocks_end"""
+        """rows of the last sampled input nodes -> out[:n]; may be queued before sample_blocks_end.
+        If out is a column slice of a wider buffer, the bytes between its rows are padding and
+        may be overwritten (see _row_stride)."""
         ref = feat_dev if feat_dev is not None else feat_host
         assert ref is not None and ref.dim() == 2
         assert feat_host is None or feat_host.is_pinned(), "feat_host must be pinned host memory"
@@ -347,6 +361,9 @@ class Context:
     def gather_features(self, feat_dev: Optional[torch.Tensor], feat_host: Optional[torch.Tensor],
                         cache_map: Optional[torch.Tensor], ids: torch.Tensor,
                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """out[i] = the row of ids[i] from the device cache or the host store, as cache_map says.
+        If out is a column slice of a wider buffer, the bytes between its rows are padding and
+        may be overwritten (see _row_stride)."""
         ref = feat_dev if feat_dev is not None else feat_host
         assert ref is not None and ref.dim() == 2
         for t in (feat_dev, feat_host):
@@ -371,7 +388,8 @@ class Context:
 
     def block_mean(self, blk_indptr: torch.Tensor, blk_indices: torch.Tensor, x: torch.Tensor,
                    out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        """mean of the source rows x[blk_indices[e]] of every destination of one block"""
+        """mean of the source rows x[blk_indices[e]] of every destination of one block; the bytes
+        between the rows of a padded out are padding and may be overwritten (see _row_stride)"""
         assert blk_indptr.dtype == torch.int32 and blk_indptr.is_contiguous()
         assert blk_indices.dtype == torch.int32 and blk_indices.is_contiguous()
         n_dst = blk_indptr.shape[0] - 1
@@ -386,7 +404,8 @@ class Context:
 
     def block_mean_of_hop(self, hop: int, x: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
         """the same for block `hop` of the last sampled mini-batch, counts taken on the device;
-        may be queued before sample_blocks_end; writes out[:n_dst[hop]]"""
+        may be queued before sample_blocks_end; writes out[:n_dst[hop]] (and, in a padded out, may
+        overwrite the padding between rows)"""
         assert out.dim() == 2 and out.shape[1] == x.shape[1] and out.dtype == x.dtype
         rc = lib().a3_block_mean_of_hop_strided(self._h, hop, _dptr(x), _row_stride(x),
                                                 self._dtype_code(x), x.shape[1], _dptr(out),

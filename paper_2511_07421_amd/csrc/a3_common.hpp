@@ -33,9 +33,10 @@ struct DevState {
   int32_t n_edges[kMaxHops];
   int32_t error;
   int32_t n_radix;  // nodes that went through the exhaustive selection path
+  int32_t n_deferred[2];  // weighted calls: wide nodes / hubs that the first launch of a hop left to the second
   int32_t class_mix;  // weighted calls: bit 0 some node is cached, bit 1 some node is not
   // scratch of the running hop; zero between hops and between calls
-  int32_t bin_count[kNumBins];
+  int32_t bin_count[kNumBins + 2];  // the degree bins, then the two lists of nodes left to a second launch
 };
 
 // What k_sample needs to know of a frontier node; k_frontier has it all in registers and writes
@@ -97,13 +98,30 @@ __global__ __launch_bounds__(kTileThreads) void k_scan_tiles(const int32_t* tile
 }
 
 // When there are few tiles (kFuseTiles at most) the consumers of a tile scan do it themselves
-// instead of waiting for k_scan_tiles: every workgroup's first wavefront reads the tile sums and
-// leaves their exclusive prefix in LDS, 16 consecutive tiles per lane.  Returns the grand total
-// (valid in every thread after the barrier inside).
+// instead of waiting for k_scan_tiles: every workgroup's first wavefront reads the tile sums
+// (tile_sums_load) and leaves their exclusive prefix in LDS, 16 consecutive tiles per lane
+// (tile_prefix_from, which returns the grand total, valid in every thread after its barrier).
 constexpr int kFuseTiles = 1024;
 
-__device__ __forceinline__ uint32_t tile_prefix_to_lds(const int32_t* tile_sums, int64_t n_tiles,
-                                                       int32_t* lds_offs, uint32_t* lds_total) {
+// The tile sums of the first wavefront's lanes, read before the number of tiles is known (so that
+// the read does not wait for it): all kFuseTiles entries that the array holds (cap_tiles); entries
+// past the real count are stale and are dropped by tile_prefix_from.
+struct TileSums {
+  uint32_t v[kFuseTiles / kWave];
+};
+
+__device__ __forceinline__ TileSums tile_sums_load(const int32_t* tile_sums, int64_t cap_tiles) {
+  TileSums s;
+#pragma unroll
+  for (int k = 0; k < kFuseTiles / kWave; ++k) {
+    const int64_t t = (int64_t)(threadIdx.x & (kWave - 1)) * (kFuseTiles / kWave) + k;
+    s.v[k] = (threadIdx.x < (unsigned)kWave && t < cap_tiles) ? (uint32_t)tile_sums[t] : 0u;
+  }
+  return s;
+}
+
+__device__ __forceinline__ uint32_t tile_prefix_from(const TileSums& loaded, int64_t n_tiles, int32_t* lds_offs,
+                                                     uint32_t* lds_total) {
   if (threadIdx.x < (unsigned)kWave) {
     const uint32_t lane = threadIdx.x;
     uint32_t v[kFuseTiles / kWave];
@@ -111,7 +129,7 @@ __device__ __forceinline__ uint32_t tile_prefix_to_lds(const int32_t* tile_sums,
 #pragma unroll
     for (int k = 0; k < kFuseTiles / kWave; ++k) {
       const int64_t t = (int64_t)lane * (kFuseTiles / kWave) + k;
-      v[k] = t < n_tiles ? (uint32_t)tile_sums[t] : 0u;
+      v[k] = t < n_tiles ? loaded.v[k] : 0u;
       sum += v[k];
     }
     uint32_t run = wave_excl_scan_u32(sum);
@@ -167,22 +185,16 @@ __global__ void k_set_frontier_size(DevState* st, int32_t num_seeds) {
   if (threadIdx.x == 0 && blockIdx.x == 0) st->n_dst[0] = st->error != 0 ? 0 : num_seeds;
 }
 
-// End of a call: undo the map entries of every node in S (all nodes the call touched), publish
-// the counts to the host (host_state is pinned host memory) and leave the state clean.
-template <typename IdxT>
-__global__ void k_finish_call(const IdxT* S, DevState* st, int last_hop, int64_t num_nodes,
-                              int32_t* node_map, DevState* host_state) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t n = st->n_src[last_hop];
-  if (i == 0) {
+// End of a call (one workgroup): publish the counts to the host (host_state is pinned host
+// memory) and leave the state clean.  The relabel map was emptied by the last hop's k_relabel.
+__global__ void k_publish(DevState* st, DevState* host_state) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
     *host_state = *st;
     st->error = 0;
     st->n_radix = 0;
+    st->n_deferred[0] = st->n_deferred[1] = 0;
     st->class_mix = 0;
   }
-  if (i >= n) return;
-  const int64_t v = (int64_t)S[i];
-  if (v >= 0 && v < num_nodes) node_map[v] = kMapEmpty;
 }
 
 }  // namespace a3

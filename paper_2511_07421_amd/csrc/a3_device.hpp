@@ -92,10 +92,23 @@ __device__ __forceinline__ uint64_t fixlog2_q32(uint64_t U) {
   return ((uint64_t)e << 32) | frac;
 }
 
-// Alg. 1 line 2 in the log domain: -log2(u)/w in Q32 with u = (x+1)/2^32.
-__device__ __forceinline__ uint64_t sample_key(uint32_t x, uint32_t w_q16) {
+// floor(n / w) for n < 2^54 with at most 38 significant bits (n = L << 16, L < 2^38) and
+// 2^16 <= w < 2^32, given inv_w = 1.0 / w rounded to double: n is exact in a double, the product
+// is within 2^-14 of n / w, so its integer part is the quotient or one beside it, and one
+// correction by the remainder makes it exact.  A dozen instructions where the 64-bit division
+// takes some eighty.
+__device__ __forceinline__ uint64_t div_by_weight(uint64_t n, uint32_t w, double inv_w) {
+  uint64_t q = (uint64_t)((double)n * inv_w);
+  const int64_t r = (int64_t)(n - q * (uint64_t)w);
+  if (r < 0) q -= 1;
+  else if (r >= (int64_t)w) q += 1;
+  return q;
+}
+
+// Alg. 2 line 2 in the log domain: -log2(u)/w in Q32 with u = (x+1)/2^32; inv_w = 1.0 / w_q16.
+__device__ __forceinline__ uint64_t sample_key(uint32_t x, uint32_t w_q16, double inv_w) {
   const uint64_t L = (32ull << 32) - fixlog2_q32((uint64_t)x + 1);
-  return (L << 16) / w_q16;
+  return div_by_weight(L << 16, w_q16, inv_w);
 }
 
 // order of equal-weight slots: larger draw first, then smaller slot

@@ -84,6 +84,8 @@ __device__ __forceinline__ int degree_bin(uint32_t deg) {
   return deg <= 16 ? 0 : deg <= 32 ? 1 : deg <= 64 ? 2 : deg <= kHubDegree ? 3 : 4;
 }
 
+// The launch is sized for a bound on the frontier; workgroups past its real size leave at once.
+// A thread's four nodes go through their reads together: ids, then the row bounds of all four.
 template <typename IdxT>
 __global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<IdxT> a) {
   __shared__ uint32_t lds4[4];
@@ -93,9 +95,17 @@ __global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<Id
   if (from_seeds && blockIdx.x == 0 && threadIdx.x == 0) a.st->n_dst[0] = (int32_t)a.num_seeds;
   const int64_t n = from_seeds ? a.num_seeds : (int64_t)a.st->n_dst[a.hop];
   if ((int64_t)blockIdx.x * kTile >= n) return;
+  const int64_t base_i = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kTilePerThread;
+  int64_t v_of[kTilePerThread], row_of[kTilePerThread], end_of[kTilePerThread];
+#pragma unroll
+  for (int k = 0; k < kTilePerThread; ++k) {
+    const int64_t i = base_i + k;
+    v_of[k] = -1;
+    row_of[k] = end_of[k] = 0;
+    if (i < n) v_of[k] = from_seeds ? (int64_t)a.seeds[i] : (int64_t)a.S[i];
+  }
   if (threadIdx.x < kNumBins) bin_n[threadIdx.x] = 0;
   __syncthreads();
-  const int64_t base_i = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kTilePerThread;
   uint32_t cnt[kTilePerThread];
   uint32_t rank_in_bin[kTilePerThread];
   int bin[kTilePerThread];
@@ -103,43 +113,65 @@ __global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<Id
   uint32_t sum = 0;
 #pragma unroll
   for (int k = 0; k < kTilePerThread; ++k) {
+    const int64_t v = v_of[k];
+    if (base_i + k < n && v >= 0 && v < a.num_nodes) {
+      row_of[k] = a.indptr[v];
+      end_of[k] = a.indptr[v + 1];
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < kTilePerThread; ++k) {
     const int64_t i = base_i + k;
     cnt[k] = 0;
     bin[k] = -1;
     rank_in_bin[k] = 0;
     if (i < n) {
-      int64_t v;
+      const int64_t v = v_of[k];
+      const bool in_graph = v >= 0 && v < a.num_nodes;
+      if (!in_graph) atomicOr(&a.st->error, kErrFrontierId);
       if (from_seeds) {
-        const IdxT s = a.seeds[i];
-        v = (int64_t)s;
-        a.S[i] = s;
-        if (v >= 0 && v < a.num_nodes) {
+        a.S[i] = (IdxT)v;
+        if (in_graph) {
           a.node_map[v] = (int32_t)i;
           if (a.cache_map) a.S_slot[i] = a.cache_map[v];
         }
-      } else {
-        v = (int64_t)a.S[i];
       }
-      int64_t row = 0, deg = 0;
-      if (v >= 0 && v < a.num_nodes) {
-        row = a.indptr[v];
-        deg = a.indptr[v + 1] - row;
-      } else {
-        atomicOr(&a.st->error, kErrFrontierId);
-      }
+      const int64_t row = in_graph ? row_of[k] : 0;
+      int64_t deg = in_graph ? end_of[k] - row_of[k] : 0;
       if (deg < 0 || deg > 0x7FFFFFFF) {  // not a CSR this library can sample: the call fails,
         atomicOr(&a.st->error, kErrHugeRow);  // and the row is not touched
         deg = 0;
       }
       cnt[k] = deg < (int64_t)a.fanout ? (uint32_t)deg : (uint32_t)a.fanout;
       bin[k] = degree_bin((uint32_t)deg);
-      rank_in_bin[k] = atomicAdd(&bin_n[bin[k]], 1u);
       sum += cnt[k];
       rec[k].v = v;
       rec[k].row = row;
       rec[k].deg = (uint32_t)deg;
       rec[k].i = (int32_t)i;
       rec[k].pad = 0;
+    }
+  }
+  // rank of every node inside its bin and workgroup: a wavefront counts its nodes of a bin with
+  // ballots and reserves them with one LDS atomic (frontiers are lopsided, most nodes of a tile
+  // fall into one bin, and an atomic per node on one LDS word would serialise)
+#pragma unroll
+  for (int b = 0; b < kNumBins; ++b) {
+    uint64_t mask[kTilePerThread];
+    uint32_t in_wave = 0;
+#pragma unroll
+    for (int k = 0; k < kTilePerThread; ++k) {
+      mask[k] = __ballot(bin[k] == b);
+      in_wave += (uint32_t)__popcll(mask[k]);
+    }
+    if (in_wave == 0) continue;  // the same in every lane
+    uint32_t base = 0;
+    if (lane_id() == 0) base = atomicAdd(&bin_n[b], in_wave);
+    base = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)base);
+#pragma unroll
+    for (int k = 0; k < kTilePerThread; ++k) {
+      if (bin[k] == b) rank_in_bin[k] = base + lanes_below(mask[k]);
+      base += (uint32_t)__popcll(mask[k]);
     }
   }
   uint32_t total;

@@ -11,9 +11,10 @@
 //                 wavefront each, hubs one workgroup each; records first occurrences in node_map
 //   k_flag        which sampled edge is the first occurrence of a new node; tile-local prefix
 //   k_scan_tiles  numbering of the new nodes across tiles (as above)
-//   k_relabel     local ids of all edges, new nodes appended to the frontier
+//   k_relabel     local ids of all edges, new nodes appended to the frontier with their device-map
+//                 entry; the last hop's launch empties the relabel map
 // Once per call: k_cached_bits (weighted calls: one bit per node from the device map),
-// k_finish_call (reset of the relabel map, counts to the host).
+// k_publish (counts to the host).
 // Then: k_gather (feature retrieve), k_block_mean (neighbour aggregation of one block),
 // k_count_accesses / k_rank_* / k_fifo_* (cache policies), k_validate_rows / k_validate_map
 // (one-time checks of the caller's graph and device map).

@@ -15,12 +15,15 @@ struct SampleArgs {
   const IdxT* S;             // frontier: local id -> global id
   const int32_t* tile_offs;  // scanned tile offsets in global memory, or null: scan tile_sums here
   const int32_t* tile_sums;
+  int64_t cap_tiles;         // entries in tile_sums
   int32_t* blk_indptr;       // out: edge offsets of this hop
   IdxT* gid;                 // out: global id of each sampled neighbour
   int64_t* eids;             // out: CSR position of each sampled edge (may be null)
   int32_t* node_map;         // global id -> first position / local id
   DevState* st;
   const NodeRec* bins[kNumBins];
+  int32_t wide_count, hub_count;  // which of the state block's bin counters hold the sizes of bins[3], bins[4]
+  NodeRec* deferred[2];           // kWeightedFast: wide nodes / hubs left to the second launch (counters 5, 6)
   int64_t num_nodes;
   int64_t cap_edges;         // entries in gid / eids (arena capacity of this hop)
   uint32_t role_blocks[5];   // workgroups serving bins 0, 1, 2 (lane groups), 3 (wide), 4 (hubs)
@@ -32,6 +35,7 @@ struct SampleArgs {
   uint32_t capb;      // second candidate list (weighted only; 0: rescan the row instead)
   uint32_t lds_per_wave;  // uint64 entries of LDS per wavefront
   uint32_t bias_q16;
+  double inv_bias;    // 1.0 / bias_q16
   uint32_t seed_lo, seed_hi;
   uint32_t force_radix;
 };
@@ -45,32 +49,38 @@ __device__ __forceinline__ bool is_cached(const SampleArgs<IdxT>& a, int64_t u) 
   return u >= 0 && u < a.num_nodes && ((a.cached_bits[u >> 5] >> (u & 31)) & 1u);
 }
 
+// writes one sampled edge
 template <typename IdxT>
 struct Emitter {
-  const IdxT* indices;
-  IdxT* gid;
-  int64_t* eids;
-  int32_t* node_map;
+  const SampleArgs<IdxT>& a;
   int64_t row;
   int32_t base;
   int32_t n_dst;
-  int64_t num_nodes;
-  int64_t cap_edges;  // entries in gid / eids
-  int32_t* error;
   __device__ __forceinline__ void operator()(uint32_t pos, uint32_t slot) const {
     const int64_t eid = row + slot;
-    const IdxT g = indices[eid];
+    const IdxT g = a.indices[eid];
     const int32_t e = base + (int32_t)pos;
     // a neighbour id outside the graph or an offset outside the arena is dropped, never written
-    if (e < 0 || (int64_t)e >= cap_edges || (int64_t)g < 0 || (int64_t)g >= num_nodes) {
-      atomicOr(error, kErrEmit);
+    if (e < 0 || (int64_t)e >= a.cap_edges || (int64_t)g < 0 || (int64_t)g >= a.num_nodes) {
+      atomicOr(&a.st->error, kErrEmit);
       return;
     }
-    gid[e] = g;
-    if (eids) eids[e] = eid;
-    atomicMin(&node_map[(int64_t)g], n_dst + e);
+    a.gid[e] = g;
+    if (a.eids) a.eids[e] = eid;
+    atomicMin(&a.node_map[(int64_t)g], n_dst + e);
   }
 };
+
+// How a launch of k_sample treats the weights:
+//   kUniform       all weights equal (no device map, or bias rate 1): the m largest draws;
+//   kWeightedFast  two weights; a wide node or hub is decided from the draws above the scan's
+//                  threshold alone where that is enough (at least m of them cached: the usual
+//                  case), and is put on a list for a second launch where it is not.  Keeps no
+//                  second candidate list, no rescanning path and so far fewer registers;
+//   kWeightedFull  two weights, every path: the second launch, which serves that list.
+constexpr int kUniform = 0, kWeightedFull = 1, kWeightedFast = 2;
+
+constexpr double kInvOne = 1.0 / 65536.0;  // 1 / weight of an uncached neighbour (Q16.16)
 
 __device__ __forceinline__ bool tuple_less(uint64_t K1, uint64_t k1, uint64_t K2, uint64_t k2) {
   return K1 < K2 || (K1 == K2 && k1 < k2);
@@ -370,11 +380,53 @@ __device__ __forceinline__ void key_and_select(const SampleArgs<IdxT>& a, const 
       const uint32_t j = (uint32_t)r * kWave + lane;
       if (j < n) {
         k[r] = j < t_u ? T[j] : T[m + (j - t_u)];
-        K[r] = sample_key(~(uint32_t)(k[r] >> 32), j < t_u ? 65536u : a.bias_q16);
+        K[r] = sample_key(~(uint32_t)(k[r] >> 32), j < t_u ? 65536u : a.bias_q16, j < t_u ? kInvOne : a.inv_bias);
       }
     }
   }
   select_pairs_in_registers<NK>(K, k, n, m, [&](uint32_t pos, uint64_t kk) { emit(pos, (uint32_t)kk); });
+}
+
+// The common case of the weighted selection needs the first list only.  If at least m of its
+// slots are cached, no cached slot outside it can be chosen (the m best cached draws are all in
+// it), and no uncached slot outside it ever can (it has m better draws against it), so the answer
+// is the best m of the first list under (K, draw order): every entry gets its key in one pass over
+// the lanes and one selection follows, all in registers.  With every candidate cached the keys
+// are monotone in the draws and are not computed at all.  Returns false, with nothing written, if
+// fewer than m candidates are cached (the second list is needed) or the list does not fit.
+template <int NK, typename IdxT, typename Emit>
+__device__ __forceinline__ bool weighted_from_first_list(const SampleArgs<IdxT>& a, int64_t row, const uint64_t* list_a,
+                                                         uint32_t cnt_a, uint32_t m, const Emit& emit) {
+  const uint32_t lane = lane_id();
+  uint64_t k[NK], K[NK];
+  bool cached[NK];
+  uint32_t n_c = 0;  // same value in every lane
+#pragma unroll
+  for (int r = 0; r < NK; ++r) {
+    k[r] = ~0ull;
+    K[r] = ~0ull;
+    cached[r] = false;
+    if ((uint32_t)r * kWave < cnt_a) {  // uniform
+      const uint32_t j = (uint32_t)r * kWave + lane;
+      if (j < cnt_a) {
+        k[r] = list_a[j];
+        cached[r] = is_cached(a, (int64_t)a.indices[row + (uint32_t)k[r]]);
+      }
+      n_c += (uint32_t)__popcll(__ballot(cached[r]));
+    }
+  }
+  if (n_c < m) return false;
+  if (n_c == cnt_a) {  // one weight class among the candidates: the m largest draws, in slot order
+    select_in_registers<NK>(list_a, cnt_a, m, [&](uint32_t pos, uint64_t key) { emit(pos, (uint32_t)key); });
+    return true;
+  }
+#pragma unroll
+  for (int r = 0; r < NK; ++r) {
+    if ((uint32_t)r * kWave < cnt_a && (uint32_t)r * kWave + lane < cnt_a)
+      K[r] = sample_key(~(uint32_t)(k[r] >> 32), cached[r] ? a.bias_q16 : 65536u, cached[r] ? a.inv_bias : kInvOne);
+  }
+  select_pairs_in_registers<NK>(K, k, cnt_a, m, [&](uint32_t pos, uint64_t kk) { emit(pos, (uint32_t)kk); });
+  return true;
 }
 
 template <typename IdxT, typename Emit>
@@ -389,9 +441,15 @@ __device__ __forceinline__ bool weighted_from_lists(const SampleArgs<IdxT>& a, i
   int64_t u[kListPerLane];
 #pragma unroll
   for (int c = 0; c < kListPerLane; ++c) {
-    const uint32_t j = (uint32_t)c * kWave + lane;
-    key[c] = j < total ? (j < cnt_a ? list_a[j] : list_b[j - cnt_a]) : 0ull;
-    u[c] = j < total ? (int64_t)a.indices[row + (uint32_t)key[c]] : -1;
+    key[c] = 0ull;
+    u[c] = -1;
+    if ((uint32_t)c * kWave < total) {  // uniform: rounds past the lists' end cost nothing
+      const uint32_t j = (uint32_t)c * kWave + lane;
+      if (j < total) {
+        key[c] = j < cnt_a ? list_a[j] : list_b[j - cnt_a];
+        u[c] = (int64_t)a.indices[row + (uint32_t)key[c]];
+      }
+    }
   }
   uint32_t n_u = 0, n_c = 0;  // same values in every lane
 #pragma unroll
@@ -446,7 +504,18 @@ __device__ __forceinline__ uint32_t second_list_floor(float keep, uint32_t bias_
 // cand [cap] and rest [m (+ 3 m + 2 xcap + capb when weighted)] are this wavefront's LDS buffers.
 // With prefiltered set, cand already holds pre_cnt candidates in slot order (a workgroup scanned
 // the row together; pre_cnt_b entries of the second list too) and the scan is skipped.
-template <typename IdxT, bool kWeighted>
+// kWeightedFast: the node goes to the second launch (one record, written by lane 0)
+template <typename IdxT>
+__device__ __forceinline__ void defer_node(const SampleArgs<IdxT>& a, const NodeRec& r) {
+  if (lane_id() == 0) {
+    const int which = r.deg <= kHubDegree ? 0 : 1;
+    const int32_t at = atomicAdd(&a.st->bin_count[kNumBins + which], 1);
+    a.deferred[which][at] = r;
+    atomicAdd(&a.st->n_deferred[which], 1);
+  }
+}
+
+template <typename IdxT, int kMode>
 __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, const int32_t* tile_offs,
                                  const NodeRec& r, int32_t n_dst, uint64_t* cand, uint64_t* rest,
                                  bool prefiltered, uint32_t pre_cnt, uint32_t pre_cnt_b) {
@@ -458,7 +527,7 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
   const uint32_t f = (uint32_t)a.fanout;
   const int32_t base = tile_offs[i >> kTileShift] + r.local_off;
   if (lane == 0) a.blk_indptr[i] = base;
-  const Emitter<IdxT> emit{a.indices, a.gid, a.eids, a.node_map, row, base, n_dst, a.num_nodes, a.cap_edges, &a.st->error};
+  const Emitter<IdxT> emit{a, row, base, n_dst};
 
   if (deg <= f) {  // keep every neighbour, no draw
     for (uint32_t s = lane; s < deg; s += kWave) emit(s, s);
@@ -486,8 +555,10 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
   uint64_t* list_b = rest + 4 * (size_t)m + 2 * (size_t)a.xcap;  // [capb]
   uint32_t cnt_b = pre_cnt_b;
   // with one weight class in the whole graph the weighted kernel takes the uniform path
+  constexpr bool kWeighted = kMode != kUniform;
+  constexpr bool kFast = kMode == kWeightedFast;
   const bool two_classes = kWeighted && a.st->class_mix == 3;
-  const bool want_b = two_classes && a.capb > 0;
+  const bool want_b = !kFast && two_classes && a.capb > 0;
   const uint32_t X1 = want_b ? second_list_floor(keep, a.bias_q16) : 0u;
   if (!a.force_radix && !prefiltered) {
     // One step: 64 quads = 256 slots.  Only the last step of a row can hold slots past its end,
@@ -547,9 +618,23 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
     for (; q0 < n_quads; q0 += kWave) step(q0, std::true_type{});
     wave_sync();
   }
+  // the first list alone decides most nodes (see weighted_from_first_list)
+  if (two_classes && !a.force_radix && cnt >= m && cnt <= a.cap && cnt <= 2u * kWave && m <= (uint32_t)kWave) {
+    const bool done = cnt <= (uint32_t)kWave ? weighted_from_first_list<1, IdxT>(a, row, cand, cnt, m, emit)
+                                             : weighted_from_first_list<2, IdxT>(a, row, cand, cnt, m, emit);
+    if (done) {
+      wave_sync();  // the candidate buffer is reused by this wavefront's next node
+      return;
+    }
+  }
+  if (kFast && two_classes) {  // everything else is the second launch's business
+    defer_node(a, r);
+    wave_sync();
+    return;
+  }
   // the lists can replace the second scan if both are complete
   const bool lists_ok = want_b && !a.force_radix && cnt >= m && cnt <= a.cap && cnt_b <= a.capb;
-  if (two_classes && lists_ok) {
+  if (!kFast && two_classes && lists_ok) {
     uint64_t* E = rest + 4 * (size_t)m;  // [2 xcap], the challenger buffers of the rescanning path
     if (weighted_from_lists<IdxT>(a, row, cand, cnt, list_b, cnt_b, m, E, 2 * a.xcap, rest, emit)) {
       wave_sync();
@@ -601,6 +686,7 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
     return;
   }
 
+  if constexpr (kMode == kWeightedFull) {
   // ---- two weight classes (cached: gamma, others: 1) -----------------------------------------
   // T = the m largest draws is a first reservoir.  A slot outside T can only enter the answer if
   // it is cached (an uncached slot outside T loses to all of T).  So: key T, take its worst
@@ -618,8 +704,8 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
     const uint32_t s = (uint32_t)k;
     const uint32_t x = ~(uint32_t)(k >> 32);
     const int64_t u = (int64_t)a.indices[row + s];
-    const uint32_t w = is_cached(a, u) ? a.bias_q16 : 65536u;
-    RK[j] = sample_key(x, w);
+    const bool c = is_cached(a, u);
+    RK[j] = sample_key(x, c ? a.bias_q16 : 65536u, c ? a.inv_bias : kInvOne);
     kT = k > kT ? k : kT;
   }
   kT = wave_max_u64(kT);
@@ -638,7 +724,7 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
     if (live && x >= x_lo && k > kT) {
       const int64_t u = (int64_t)a.indices[row + s];
       if (is_cached(a, u)) {
-        K = sample_key(x, a.bias_q16);
+        K = sample_key(x, a.bias_q16, a.inv_bias);
         challenger = tuple_less(K, k, BK, Bk);
       }
     }
@@ -679,13 +765,14 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
     emit(pos, s);
   }
   wave_sync();
+  }
 }
 
 // ---- a group of G lanes (4, 8 or 16), one node of degree <= 4 G: four slots per lane ------------
 // The draws of a lane are one Philox block.  Selection is m rounds of "best remaining slot of
 // the group" (lane-local best, butterfly reduction, lowest lane among equals), which costs
 // O(m log G) instead of ranking every slot against every other.
-template <typename IdxT, int G, bool kWeighted>
+template <typename IdxT, int G, int kMode>
 __device__ void sample_node_group(const SampleArgs<IdxT>& a, const int32_t* tile_offs,
                                   const NodeRec& r, int32_t n_dst) {
   const uint32_t lane = lane_id();
@@ -698,7 +785,7 @@ __device__ void sample_node_group(const SampleArgs<IdxT>& a, const int32_t* tile
   const uint32_t f = (uint32_t)a.fanout;
   const int32_t base = tile_offs[i >> kTileShift] + r.local_off;
   if (gl == 0) a.blk_indptr[i] = base;
-  const Emitter<IdxT> emit{a.indices, a.gid, a.eids, a.node_map, row, base, n_dst, a.num_nodes, a.cap_edges, &a.st->error};
+  const Emitter<IdxT> emit{a, row, base, n_dst};
   if (deg <= f) {
     for (uint32_t s = gl; s < deg; s += G) emit(s, s);
     return;
@@ -712,7 +799,7 @@ __device__ void sample_node_group(const SampleArgs<IdxT>& a, const int32_t* tile
 #pragma unroll
   for (int w = 0; w < 4; ++w) alive |= (4u * gl + w < deg) ? (1u << w) : 0u;
   uint64_t K[4] = {0, 0, 0, 0};
-  if (kWeighted && a.st->class_mix == 3) {
+  if (kMode != kUniform && a.st->class_mix == 3) {
     bool cached[4];
     bool any_c = false, any_u = false;
 #pragma unroll
@@ -733,7 +820,8 @@ __device__ void sample_node_group(const SampleArgs<IdxT>& a, const int32_t* tile
     if (mixed) {
 #pragma unroll
       for (int w = 0; w < 4; ++w)
-        if (alive & (1u << w)) K[w] = sample_key(x[w], cached[w] ? a.bias_q16 : 65536u);
+        if (alive & (1u << w))
+          K[w] = sample_key(x[w], cached[w] ? a.bias_q16 : 65536u, cached[w] ? a.inv_bias : kInvOne);
     }
   }
   uint32_t chosen = 0;
@@ -795,7 +883,7 @@ __device__ void sample_node_group(const SampleArgs<IdxT>& a, const int32_t* tile
 // is slot order again, and wavefront 0 finishes the node as it would one it scanned alone.
 constexpr uint32_t kHubRegion = 64;  // candidates one wavefront may contribute
 
-template <typename IdxT, bool kWeighted>
+template <typename IdxT, int kMode>
 __device__ __forceinline__ void hub_scan(const SampleArgs<IdxT>& a, const NodeRec& r, uint64_t* lds,
                                          uint64_t*& joined_out, uint64_t*& rest_out, uint32_t& pre_cnt,
                                          uint32_t& pre_cnt_b) {
@@ -812,7 +900,7 @@ __device__ __forceinline__ void hub_scan(const SampleArgs<IdxT>& a, const NodeRe
   // the second candidate list of the weighted case is shared: wavefronts reserve space in it
   // with one LDS atomic per append (its order does not matter)
   uint64_t* list_b = rest + 4 * (size_t)a.fanout + 2 * (size_t)a.xcap;
-  const bool want_b = kWeighted && a.capb > 0 && a.st->class_mix == 3;
+  const bool want_b = kMode == kWeightedFull && a.capb > 0 && a.st->class_mix == 3;
   if (want_b) {
     if (threadIdx.x == 0) *shared_cnt_b = 0;
     __syncthreads();
@@ -911,7 +999,7 @@ __device__ __forceinline__ void hub_scan(const SampleArgs<IdxT>& a, const NodeRe
   pre_cnt_b = want_b ? *shared_cnt_b : 0u;
 }
 
-template <typename IdxT, int G, bool kWeighted>
+template <typename IdxT, int G, int kMode>
 __device__ __forceinline__ void run_group_role(const SampleArgs<IdxT>& a, const int32_t* tile_offs,
                                                int bin, uint32_t block_in_role,
                                                uint32_t blocks_in_role, int32_t n_dst) {
@@ -924,7 +1012,7 @@ __device__ __forceinline__ void run_group_role(const SampleArgs<IdxT>& a, const 
   for (; item < count; item += groups) {
     NodeRec nxt = {};
     if (item + groups < count) nxt = a.bins[bin][item + groups];  // in flight while cur is sampled
-    if (cur.i >= 0 && cur.i < n_dst) sample_node_group<IdxT, G, kWeighted>(a, tile_offs, cur, n_dst);
+    if (cur.i >= 0 && cur.i < n_dst) sample_node_group<IdxT, G, kMode>(a, tile_offs, cur, n_dst);
     cur = nxt;
   }
 }
@@ -934,16 +1022,20 @@ constexpr int kSampleMaxThreads = 256;
 // Workgroups take roles by index: the first role_blocks[4] serve the hubs (one workgroup each), the
 // next role_blocks[3] the wide nodes (one wavefront each), then role_blocks[2], [1], [0] the
 // small-degree bins with lane groups of 16, 8, 4.
-template <typename IdxT, bool kWeighted>
+template <typename IdxT, int kMode>
 __global__ __launch_bounds__(kSampleMaxThreads) void k_sample(const SampleArgs<IdxT> a) {
   extern __shared__ uint64_t lds[];
   __shared__ int32_t fused_offs[kFuseTiles];
   __shared__ uint32_t fused_total;
-  const int32_t n_dst = a.st->n_dst[a.hop];
+  // the second launch of a weighted hop usually finds its lists empty
+  if (kMode == kWeightedFull && a.st->bin_count[a.wide_count] == 0 && a.st->bin_count[a.hub_count] == 0) return;
   const int32_t* tile_offs = a.tile_offs;
+  TileSums sums = {};
+  if (tile_offs == nullptr) sums = tile_sums_load(a.tile_sums, a.cap_tiles);  // does not wait for n_dst
+  const int32_t n_dst = a.st->n_dst[a.hop];
   if (tile_offs == nullptr) {  // few tiles: scan the tile sums here, publish the hop's edge count
-    const uint32_t total = tile_prefix_to_lds(a.tile_sums, ((int64_t)n_dst + kTile - 1) >> kTileShift,
-                                              fused_offs, &fused_total);
+    const uint32_t total = tile_prefix_from(sums, ((int64_t)n_dst + kTile - 1) >> kTileShift,
+                                            fused_offs, &fused_total);
     tile_offs = fused_offs;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
       a.st->n_edges[a.hop] = (int32_t)total;
@@ -959,11 +1051,11 @@ __global__ __launch_bounds__(kSampleMaxThreads) void k_sample(const SampleArgs<I
     b -= a.role_blocks[4];
     if (b >= a.role_blocks[3]) {
       b -= a.role_blocks[3];
-      if (b < a.role_blocks[2]) return run_group_role<IdxT, 16, kWeighted>(a, tile_offs, 2, b, a.role_blocks[2], n_dst);
+      if (b < a.role_blocks[2]) return run_group_role<IdxT, 16, kMode>(a, tile_offs, 2, b, a.role_blocks[2], n_dst);
       b -= a.role_blocks[2];
-      if (b < a.role_blocks[1]) return run_group_role<IdxT, 8, kWeighted>(a, tile_offs, 1, b, a.role_blocks[1], n_dst);
+      if (b < a.role_blocks[1]) return run_group_role<IdxT, 8, kMode>(a, tile_offs, 1, b, a.role_blocks[1], n_dst);
       b -= a.role_blocks[1];
-      return run_group_role<IdxT, 4, kWeighted>(a, tile_offs, 0, b, a.role_blocks[0], n_dst);
+      return run_group_role<IdxT, 4, kMode>(a, tile_offs, 0, b, a.role_blocks[0], n_dst);
     }
   }
   // the wavefront's index inside the workgroup, held in a scalar register so that the node loops
@@ -973,7 +1065,7 @@ __global__ __launch_bounds__(kSampleMaxThreads) void k_sample(const SampleArgs<I
   // wide nodes and hubs share one loop (and one copy of the selection code): a wavefront takes a
   // wide node by itself; a hub is scanned by the whole workgroup and finished by wavefront 0
   const int bin = hub_role ? 4 : 3;
-  const int64_t n_nodes = a.st->bin_count[bin];
+  const int64_t n_nodes = a.st->bin_count[hub_role ? a.hub_count : a.wide_count];
   const NodeRec* recs = a.bins[bin];
   const int64_t stride = hub_role ? (int64_t)a.role_blocks[4] : (int64_t)a.role_blocks[3] * n_waves;
   int64_t t = hub_role ? (int64_t)b : (int64_t)b * n_waves + wave;
@@ -987,9 +1079,9 @@ __global__ __launch_bounds__(kSampleMaxThreads) void k_sample(const SampleArgs<I
       uint64_t* cand = my_lds;
       uint64_t* rest = my_lds + a.cap;
       uint32_t pre_cnt = 0, pre_cnt_b = 0;
-      if (hub_role) hub_scan<IdxT, kWeighted>(a, cur, lds, cand, rest, pre_cnt, pre_cnt_b);
+      if (hub_role) hub_scan<IdxT, kMode>(a, cur, lds, cand, rest, pre_cnt, pre_cnt_b);
       if (!hub_role || wave == 0)
-        sample_node_wave<IdxT, kWeighted>(a, tile_offs, cur, n_dst, cand, rest, hub_role, pre_cnt, pre_cnt_b);
+        sample_node_wave<IdxT, kMode>(a, tile_offs, cur, n_dst, cand, rest, hub_role, pre_cnt, pre_cnt_b);
       if (hub_role) __syncthreads();  // the regions are reused for the workgroup's next hub
     }
     cur = nxt;

@@ -238,7 +238,7 @@ inline uint64_t log2_q32(uint64_t U) {
   return ((uint64_t)e << 32) | frac;
 }
 
-// Alg. 1 line 2 in the log domain: -log2(u) / w in Q32, u = (x + 1) / 2^32
+// Alg. 2 line 2 in the log domain: -log2(u) / w in Q32, u = (x + 1) / 2^32
 inline uint64_t weighted_key(uint32_t x, uint32_t w_q16) {
   const uint64_t neg_log = (32ull << 32) - log2_q32((uint64_t)x + 1);
   return (neg_log << 16) / w_q16;
@@ -272,7 +272,7 @@ inline void keep_smallest(std::vector<uint64_t>& v, size_t m) {
   }
 }
 
-// Alg. 1 for one destination: the chosen slots, ascending, into sc.chosen
+// Alg. 2 for one destination: the chosen slots, ascending, into sc.chosen
 template <typename IdxT>
 void select_node(const Graph<IdxT>& g, int64_t v, uint32_t hop, uint32_t fanout, Scratch& sc) {
   const int64_t row = g.indptr[v];

@@ -44,7 +44,8 @@ struct a3_ctx {
   int32_t* tile_sums2 = nullptr;  // per edge tile: first occurrences
   int32_t* tile_offs = nullptr;   // edge offsets of the node tiles (read by k_sample)
   int32_t* tile_offs2 = nullptr;  // new-node offsets of the edge tiles (read by k_relabel)
-  a3::NodeRec* bins[a3::kNumBins] = {nullptr};  // frontier node records by degree bin
+  a3::NodeRec* bins[a3::kNumBins + 2] = {nullptr};  // frontier node records by degree bin; then the wide
+                                                    // nodes and hubs a weighted hop leaves to its second launch
   int32_t* node_map = nullptr;  // global id -> position, grown on demand
   int64_t node_map_cap = 0;
   uint64_t* cached_bits = nullptr;  // one bit per node, rebuilt from the device map by every weighted call
@@ -120,6 +121,11 @@ inline unsigned blocks_for(int64_t n, int per_block) {
 // negligible probability (then the exhaustive path takes over)
 uint32_t lambda_for(int32_t m) { return (uint32_t)(m + 4.0 * std::sqrt((double)m) + 8.0); }
 uint32_t cap_for(uint32_t lambda) { return ((2 * lambda + 63) / 64) * 64; }
+// The first launch of a weighted hop decides a node from these candidates alone if at least m of
+// them are cached, so it keeps half as many again: with three quarters of the neighbours cached,
+// a node then has too few about once in 10^6 instead of once in 10^4 (each one left over costs the
+// second launch a whole node's latency).
+uint32_t lambda_for_first_list(int32_t m) { return (uint32_t)(m + 6.0 * std::sqrt((double)m) + 12.0); }
 constexpr int64_t kMaxRoleWaves = 8192;  // wavefronts serving one role of k_sample
 constexpr int64_t kMaxHubBlocks = 2048;
 constexpr int kSampleWaves = 4;           // wavefronts per k_sample workgroup (fewer if LDS is short)
@@ -143,8 +149,7 @@ uint32_t challenger_cap(int32_t fanout, uint32_t capb) {
 }
 
 // uint64 entries of LDS one wavefront needs in the wavefront-per-node path
-uint32_t sample_lds_entries(int32_t fanout, bool weighted, uint32_t capb) {
-  const uint32_t cap = cap_for(lambda_for(fanout));
+uint32_t sample_lds_entries(uint32_t cap, int32_t fanout, bool weighted, uint32_t capb) {
   uint32_t entries = cap + (uint32_t)fanout;
   if (weighted) entries += 3 * (uint32_t)fanout + 2 * challenger_cap(fanout, capb) + capb;
   return entries;
@@ -340,6 +345,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       sa.S = S;
       sa.tile_offs = fuse_dst ? nullptr : ctx->tile_offs;
       sa.tile_sums = ctx->tile_sums;
+      sa.cap_tiles = ctx->cap_tiles;
       sa.blk_indptr = ctx->blk_indptr[h];
       sa.gid = gid;
       sa.eids = ctx->blk_eids[h];
@@ -348,38 +354,70 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       for (int b = 0; b < a3::kNumBins; ++b) sa.bins[b] = ctx->bins[b];
       sa.num_nodes = num_nodes;
       sa.cap_edges = ctx->cap_edges[h];
-      sa.capb = weighted ? second_list_cap(f, bias_q16) : 0u;
-      sa.lds_per_wave = sample_lds_entries(f, weighted, sa.capb);
-      sa.cap = cap_for(lambda_for(f));
-      // wavefronts per workgroup: as many as the LDS allows, at most kSampleWaves
-      const size_t kLdsLimit = 64 * 1024;
-      int n_waves = kSampleWaves;
-      while (n_waves > 1 && sample_block_lds_bytes(sa.lds_per_wave, sa.cap, n_waves) > kLdsLimit)
-        n_waves >>= 1;
-      // workgroups per role: enough to cover the frontier bound once, at most kMaxRoleWaves wavefronts
-      const int64_t nb = std::max<int64_t>(bound_dst[h], 1);
-      const int64_t max_blocks = std::max<int64_t>(kMaxRoleWaves / n_waves, 1);
-      const int64_t threads = 64 * n_waves;
-      sa.role_blocks[0] = (uint32_t)std::min<int64_t>((nb * 4 + threads - 1) / threads, max_blocks);
-      sa.role_blocks[1] = (uint32_t)std::min<int64_t>((nb * 8 + threads - 1) / threads, max_blocks);
-      sa.role_blocks[2] = (uint32_t)std::min<int64_t>((nb * 16 + threads - 1) / threads, max_blocks);
-      sa.role_blocks[3] = (uint32_t)std::min<int64_t>((nb + n_waves - 1) / n_waves, max_blocks);
-      sa.role_blocks[4] = (uint32_t)std::min<int64_t>(nb, kMaxHubBlocks);
+      sa.wide_count = 3;
+      sa.hub_count = 4;
+      sa.deferred[0] = ctx->bins[a3::kNumBins];
+      sa.deferred[1] = ctx->bins[a3::kNumBins + 1];
       sa.hop = h;
       sa.fanout = f;
-      sa.lambda = lambda_for(f);
-      sa.xcap = challenger_cap(f, sa.capb);
+      sa.lambda = weighted ? lambda_for_first_list(f) : lambda_for(f);
+      sa.cap = cap_for(sa.lambda);
       sa.bias_q16 = bias_q16;
+      sa.inv_bias = 1.0 / (double)bias_q16;
       sa.seed_lo = (uint32_t)rng_seed;
       sa.seed_hi = (uint32_t)(rng_seed >> 32);
       sa.force_radix = (ctx->flags & A3_FORCE_RADIX) ? 1u : 0u;
-      const unsigned grid = sa.role_blocks[0] + sa.role_blocks[1] + sa.role_blocks[2] +
-                            sa.role_blocks[3] + sa.role_blocks[4];
-      const size_t lds_bytes = sample_block_lds_bytes(sa.lds_per_wave, sa.cap, n_waves);
-      if (weighted)
-        hipLaunchKernelGGL((a3::k_sample<IdxT, true>), dim3(grid), dim3((unsigned)threads), lds_bytes, st, sa);
-      else
-        hipLaunchKernelGGL((a3::k_sample<IdxT, false>), dim3(grid), dim3((unsigned)threads), lds_bytes, st, sa);
+      const size_t kLdsLimit = 64 * 1024;
+      const int64_t nb = std::max<int64_t>(bound_dst[h], 1);
+      // The first launch, for every node: all weights equal, or (weighted) the path that decides a
+      // wide node from its first candidate list alone and leaves the others to the second launch.
+      // Either way a wavefront needs the uniform buffers only.
+      {
+        sa.capb = 0;
+        sa.xcap = 0;
+        sa.lds_per_wave = sample_lds_entries(sa.cap, f, false, 0);
+        // wavefronts per workgroup: as many as the LDS allows, at most kSampleWaves
+        int n_waves = kSampleWaves;
+        while (n_waves > 1 && sample_block_lds_bytes(sa.lds_per_wave, sa.cap, n_waves) > kLdsLimit) n_waves >>= 1;
+        // workgroups per role: enough to cover the frontier bound once, at most kMaxRoleWaves wavefronts
+        const int64_t max_blocks = std::max<int64_t>(kMaxRoleWaves / n_waves, 1);
+        const int64_t threads = 64 * n_waves;
+        sa.role_blocks[0] = (uint32_t)std::min<int64_t>((nb * 4 + threads - 1) / threads, max_blocks);
+        sa.role_blocks[1] = (uint32_t)std::min<int64_t>((nb * 8 + threads - 1) / threads, max_blocks);
+        sa.role_blocks[2] = (uint32_t)std::min<int64_t>((nb * 16 + threads - 1) / threads, max_blocks);
+        sa.role_blocks[3] = (uint32_t)std::min<int64_t>((nb + n_waves - 1) / n_waves, max_blocks);
+        sa.role_blocks[4] = (uint32_t)std::min<int64_t>(nb, kMaxHubBlocks);
+        const unsigned grid = sa.role_blocks[0] + sa.role_blocks[1] + sa.role_blocks[2] +
+                              sa.role_blocks[3] + sa.role_blocks[4];
+        const size_t lds_bytes = sample_block_lds_bytes(sa.lds_per_wave, sa.cap, n_waves);
+        if (weighted)
+          hipLaunchKernelGGL((a3::k_sample<IdxT, a3::kWeightedFast>), dim3(grid), dim3((unsigned)threads), lds_bytes, st, sa);
+        else
+          hipLaunchKernelGGL((a3::k_sample<IdxT, a3::kUniform>), dim3(grid), dim3((unsigned)threads), lds_bytes, st, sa);
+      }
+      // The second launch of a weighted hop: the wide nodes and hubs that the first left over (too
+      // few cached candidates, odd list sizes), with both candidate lists and the rescanning path.
+      // Usually there are none, and its workgroups leave after one read.
+      if (weighted) {
+        sa.lambda = lambda_for(f);
+        sa.cap = cap_for(sa.lambda);
+        sa.capb = second_list_cap(f, bias_q16);
+        sa.xcap = challenger_cap(f, sa.capb);
+        sa.lds_per_wave = sample_lds_entries(sa.cap, f, true, sa.capb);
+        int n_waves = kSampleWaves;
+        while (n_waves > 1 && sample_block_lds_bytes(sa.lds_per_wave, sa.cap, n_waves) > kLdsLimit) n_waves >>= 1;
+        const int64_t max_blocks = std::max<int64_t>(kMaxRoleWaves / n_waves / 4, 1);
+        sa.bins[3] = sa.deferred[0];
+        sa.bins[4] = sa.deferred[1];
+        sa.wide_count = a3::kNumBins;
+        sa.hub_count = a3::kNumBins + 1;
+        sa.role_blocks[0] = sa.role_blocks[1] = sa.role_blocks[2] = 0;
+        sa.role_blocks[3] = (uint32_t)std::min<int64_t>((nb + n_waves - 1) / n_waves, max_blocks);
+        sa.role_blocks[4] = (uint32_t)std::min<int64_t>(nb, kMaxHubBlocks / 4);
+        const size_t lds_bytes = sample_block_lds_bytes(sa.lds_per_wave, sa.cap, n_waves);
+        hipLaunchKernelGGL((a3::k_sample<IdxT, a3::kWeightedFull>), dim3(sa.role_blocks[3] + sa.role_blocks[4]),
+                           dim3((unsigned)(64 * n_waves)), lds_bytes, st, sa);
+      }
     }
     // a5: first occurrences -> numbering of new nodes -> local ids
     hipLaunchKernelGGL(a3::k_flag<IdxT>, dim3(edge_tiles), dim3(a3::kTileThreads), 0, st, gid,
@@ -388,16 +426,30 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
     if (!fuse_edges)
       hipLaunchKernelGGL(a3::k_scan_tiles, dim3(1), dim3(a3::kTileThreads), 0, st, ctx->tile_sums2,
                          ctx->tile_offs2, ds, h, 1, (int32_t*)nullptr);
+    a3::RelabelArgs<IdxT> ra;
+    ra.gid = gid;
+    ra.first_pos = ctx->first_pos;
+    ra.local_rank = ctx->local_rank;
+    ra.tile_offs = fuse_edges ? (const int32_t*)nullptr : ctx->tile_offs2;
+    ra.tile_sums = ctx->tile_sums2;
+    ra.cap_tiles = ctx->cap_tiles;
+    ra.st = ds;
+    ra.hop = h;
+    ra.last_hop = h == num_hops - 1 ? 1 : 0;  // the last hop's launch leaves the relabel map empty
+    ra.num_nodes = num_nodes;
+    ra.cap_src = ctx->cap_dst[ctx->max_hops];
+    ra.S = S;
+    ra.node_map = ctx->node_map;
+    ra.blk_indices = ctx->blk_indices[h];
+    ra.cache_map = cache_map;
+    ra.S_slot = ctx->S_slot;
+    // at least as many workgroups as the destinations need for the map reset to stay short
     hipLaunchKernelGGL(a3::k_relabel<IdxT>,
                        dim3(blocks_for(bound_edges[h], a3::kTileThreads * a3::kRelabelPerThread)),
-                       dim3(a3::kTileThreads), 0, st, gid, ctx->first_pos, ctx->local_rank,
-                       fuse_edges ? (const int32_t*)nullptr : ctx->tile_offs2, ctx->tile_sums2, ds, h, num_nodes,
-                       ctx->cap_dst[ctx->max_hops], S, ctx->node_map, ctx->blk_indices[h], cache_map,
-                       ctx->S_slot);
+                       dim3(a3::kTileThreads), 0, st, ra);
   }
-  // leave the relabel map empty for the next call; the same kernel publishes the counts
-  hipLaunchKernelGGL(a3::k_finish_call<IdxT>, dim3(blocks_for(bound_dst[num_hops], 256)), dim3(256),
-                     0, st, S, ds, num_hops - 1, num_nodes, ctx->node_map, ctx->h_state_dev);
+  // the counts go to the host
+  hipLaunchKernelGGL(a3::k_publish, dim3(1), dim3(64), 0, st, ds, ctx->h_state_dev);
   prof_mark(ctx, 0, 1);
   A3_HIP(ctx, hipGetLastError());
   A3_HIP(ctx, hipEventRecord(ctx->sampled, st));
@@ -718,7 +770,7 @@ extern "C" int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t
   chk(dev_alloc(ctx, &ctx->tile_sums2, ctx->cap_tiles));
   chk(dev_alloc(ctx, &ctx->tile_offs, ctx->cap_tiles));
   chk(dev_alloc(ctx, &ctx->tile_offs2, ctx->cap_tiles));
-  for (int b = 0; b < a3::kNumBins; ++b) chk(dev_alloc(ctx, &ctx->bins[b], ctx->cap_dst[max_hops - 1]));
+  for (int b = 0; b < a3::kNumBins + 2; ++b) chk(dev_alloc(ctx, &ctx->bins[b], ctx->cap_dst[max_hops - 1]));
   chk(dev_alloc(ctx, &ctx->d_state, 1));
   chk(dev_alloc(ctx, &ctx->block_seen, kCachedBitsBlocks));
   if (rc == A3_OK) {
@@ -852,6 +904,21 @@ extern "C" int a3_sample_blocks_end(a3_ctx* ctx, a3_blocks* out) {
     return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_blocks_end: no call was begun");
   A3_HIP(ctx, hipSetDevice(ctx->device));
   return sample_finish(ctx, out);
+}
+
+extern "C" int a3_sample_stats(a3_ctx* ctx, int64_t stats[4]) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_sample_stats: ctx is null");
+  if (!stats) return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_stats: stats is null");
+  if (ctx->flags & A3_HOST_ONLY)
+    return fail(ctx, A3_ERR_HIP, "a3_sample_stats: context was created without a device");
+  if (ctx->pending || ctx->last_hops == 0)
+    return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_stats: no ended call to report on");
+  const DevState& hs = *ctx->h_state;
+  stats[0] = hs.class_mix;
+  stats[1] = hs.n_deferred[0];
+  stats[2] = hs.n_deferred[1];
+  stats[3] = hs.n_radix;
+  return A3_OK;
 }
 
 extern "C" int a3_sample_blocks(a3_ctx* ctx, const int64_t* indptr, const void* indices,

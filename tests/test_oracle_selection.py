@@ -1,4 +1,6 @@
-"""Pins for the oracle's per-node selection (Alg. 1) and its sampling law."""
+"""Pins for the oracle's per-node selection (the paper's Weighted Reservoir Sampling listing, its
+second algorithm) and its sampling law."""
+import heapq
 import itertools
 import random
 from decimal import Decimal, getcontext
@@ -13,25 +15,18 @@ getcontext().prec = 60
 Q = 65536
 
 
-def _stream_alg1(keys_x, m):
-    """Alg. 1 as printed: a stream with a reservoir R of m items; an arrival replaces the
-    current minimum only if strictly better.  Items are (K, x, slot); 'better' is the
-    oracle's total order (K ascending, x descending, slot ascending)."""
-    def order(item):
-        K, x, s = item
-        return (K, -x, s)
-    R = []
-    for j, item in enumerate(keys_x):
-        if j < m:
-            R.append(item)
-        else:
-            worst = max(R, key=order)
-            if order(item) < order(worst):
-                R[R.index(worst)] = item
-    return sorted(s for _, _, s in R)
+def _one_pass_reservoir(stream, m):
+    """What a reservoir computes, by a library routine: heapq.nsmallest reads the stream once and
+    keeps at most m items in a heap, evicting its worst when a better one arrives.  Items are
+    (K, x, slot); 'better' is the oracle's total order (K ascending, x descending, slot ascending)."""
+    kept = heapq.nsmallest(m, iter(stream), key=lambda item: (item[0], -item[1], item[2]))
+    return sorted(s for _, _, s in kept)
 
 
-def test_top_m_equals_streaming_reservoir():
+def test_top_m_equals_a_one_pass_reservoir_in_any_arrival_order():
+    """The oracle sorts all keys and keeps m; the method is a reservoir that sees each neighbour
+    once (Weighted Reservoir Sampling listing, Sec. III-A: O(|N(v)|) time, O(m) space).  Both must
+    choose the same slots, and a reservoir's choice must not depend on the order of arrival."""
     rnd = random.Random(10)
     for trial in range(400):
         deg = rnd.randrange(2, 200)
@@ -42,7 +37,11 @@ def test_top_m_equals_streaming_reservoir():
         for s in range(deg):
             x = oracle.draw(seed, hop, node, s)
             items.append((oracle.key(x, w[s]), x, s))
-        assert oracle.select(seed, hop, node, deg, m, w) == _stream_alg1(items, m)
+        want = oracle.select(seed, hop, node, deg, m, w)
+        assert want == _one_pass_reservoir(items, m)
+        shuffled = items[:]
+        rnd.shuffle(shuffled)
+        assert want == _one_pass_reservoir(shuffled, m)
 
 
 def test_selection_equals_top_m_of_real_keys():
@@ -103,7 +102,7 @@ def test_uniform_inclusion_chi_square():
 
 
 def test_weighted_single_draw_law():
-    """m = 1: P(slot j) = w_j / sum w (the A-Res property behind Alg. 1)."""
+    """m = 1: P(slot j) = w_j / sum w (the A-Res property behind Alg. 2)."""
     w = np.array([1, 4, 1, 1, 4, 2.5, 1, 1], dtype=float)
     wq = [int(v * Q) for v in w]
     T = 20000
