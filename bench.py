@@ -238,6 +238,7 @@ def measure(args, name, headline, legs):
         "input_rows_per_step": n_in / K,
         "cache_hit_rate": hit_rate,
         "scanned_slots_per_step": scanned,
+        "scanned_slots_per_hop": scanned_per_hop,
         # nodes of the K timed steps that left the sampler's usual path (a3_sample_stats)
         "slow_path_nodes": slow_paths,
         "roofline_sampling": {"kernel": "k_sample (all hops, with the relabel kernels around it)",
@@ -394,11 +395,10 @@ def measure(args, name, headline, legs):
             return time.perf_counter() - c0
 
         # The oracle as it stands, single-threaded, on a bounded sample of the last timed
-        # mini-batch (all its seeds, same rng_seed): its first hop, which also tells how long the
-        # oracle takes per scanned neighbour slot, then as many of its hops as that rate predicts
-        # to fit the budget (the slots each hop scans are known from the GPU's blocks).  A whole
-        # mini-batch of `citation` takes the oracle about two minutes (its parity with the GPU path
-        # at full size is the tests' business); its first two hops take about twenty seconds.
+        # mini-batch (all its seeds, same rng_seed): its first hop, then as many of its hops as are
+        # predicted to fit the budget.  A whole mini-batch of `citation` takes the oracle about two
+        # minutes (its parity with the GPU path at full size is the tests' business); its first two
+        # hops take about twenty seconds.
         H = len(w.fanouts)
         seeds_host = {}
 
@@ -413,10 +413,11 @@ def measure(args, name, headline, legs):
         ob, dt = oracle_run(b_last, 1)
         dg = oracle_rows(ob.input_nodes.astype(np.int64))
         spent, best = dt + dg, (1, ob, dt, dg)
-        per_slot = dt / max(scanned_per_hop[0], 1)
+        # the oracle scans five to six million neighbour slots a second on one core, and the slots
+        # that each hop scans are known from the GPU's blocks: as many hops as ten million slots per
+        # second of budget allow (so the run takes up to twice the budget)
         hops = 1
-        # (the one-hop run overstates the cost per slot: its fixed costs are spread over few slots)
-        while hops < H and per_slot * sum(scanned_per_hop[:hops + 1]) <= 2.0 * args.cpu_seconds:
+        while hops < H and sum(scanned_per_hop[:hops + 1]) <= 10e6 * args.cpu_seconds:
             hops += 1
         if hops > 1:
             ob, dt = oracle_run(b_last, hops)

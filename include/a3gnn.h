@@ -52,6 +52,8 @@ extern "C" {
 #define A3_HOST_ONLY 4u      /* no device: calls validate their arguments, then fail with A3_ERR_HIP */
 #define A3_FORCE_RADIX 8u    /* testing: always use the exhaustive selection path */
 #define A3_PROFILE 16u       /* bracket the kernels of every call with HIP events (see a3_profile_read) */
+#define A3_TEST_MAP_RANGE 32u /* testing: the relabel map's value ranges start two calls above the bottom
+                                of int32, so every third call refills the map and values are negative */
 #define A3_PROFILE_DEPTH 256 /* calls remembered per kind */
 
 typedef struct a3_ctx a3_ctx;

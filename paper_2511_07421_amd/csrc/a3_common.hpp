@@ -157,7 +157,7 @@ __global__ void k_fill_i32(int32_t* p, int64_t n, int32_t value) {
 // A3_VALIDATE only: seeds -> S with range and uniqueness checks; a bad batch empties the frontier
 template <typename IdxT>
 __global__ void k_init_seeds_checked(const IdxT* seeds, int64_t num_seeds, int64_t num_nodes,
-                                     IdxT* S, int32_t* node_map, DevState* st,
+                                     IdxT* S, int32_t* node_map, int32_t map_base, DevState* st,
                                      const int32_t* cache_map, int32_t* S_slot) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= num_seeds) return;
@@ -167,18 +167,18 @@ __global__ void k_init_seeds_checked(const IdxT* seeds, int64_t num_seeds, int64
     atomicOr(&st->error, kErrBadSeed);
     return;
   }
-  atomicMin(&node_map[v], (int32_t)i);
+  atomicMin(&node_map[v], map_base + (int32_t)i);
   if (cache_map) S_slot[i] = cache_map[v];
 }
 
 template <typename IdxT>
 __global__ void k_check_seeds(const IdxT* seeds, int64_t num_seeds, int64_t num_nodes,
-                              const int32_t* node_map, DevState* st) {
+                              const int32_t* node_map, int32_t map_base, DevState* st) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= num_seeds) return;
   const int64_t v = (int64_t)seeds[i];
   if (v < 0 || v >= num_nodes) return;
-  if (node_map[v] != (int32_t)i) atomicOr(&st->error, kErrDupSeed);
+  if (node_map[v] != map_base + (int32_t)i) atomicOr(&st->error, kErrDupSeed);
 }
 
 __global__ void k_set_frontier_size(DevState* st, int32_t num_seeds) {
@@ -186,7 +186,8 @@ __global__ void k_set_frontier_size(DevState* st, int32_t num_seeds) {
 }
 
 // End of a call (one workgroup): publish the counts to the host (host_state is pinned host
-// memory) and leave the state clean.  The relabel map was emptied by the last hop's k_relabel.
+// memory) and leave the state clean.  The relabel map is not cleaned: the next call writes values
+// below everything this one wrote (see map_base in a3_relabel.hpp).
 __global__ void k_publish(DevState* st, DevState* host_state) {
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     *host_state = *st;

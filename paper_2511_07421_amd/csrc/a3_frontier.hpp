@@ -71,6 +71,7 @@ struct FrontierArgs {
   int32_t* S_slot;
   IdxT* S;
   int32_t* node_map;
+  int32_t map_base;  // the call's offset into the relabel map's value range
   const int64_t* indptr;
   DevState* st;
   int32_t hop;
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<Id
       if (from_seeds) {
         a.S[i] = (IdxT)v;
         if (in_graph) {
-          a.node_map[v] = (int32_t)i;
+          a.node_map[v] = a.map_base + (int32_t)i;
           if (a.cache_map) a.S_slot[i] = a.cache_map[v];
         }
       }

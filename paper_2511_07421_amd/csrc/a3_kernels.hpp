@@ -12,7 +12,7 @@
 //   k_flag        which sampled edge is the first occurrence of a new node; tile-local prefix
 //   k_scan_tiles  numbering of the new nodes across tiles (as above)
 //   k_relabel     local ids of all edges, new nodes appended to the frontier with their device-map
-//                 entry; the last hop's launch empties the relabel map
+//                 entry (the relabel map is never cleaned: every call uses values below the last)
 // Once per call: k_cached_bits (weighted calls: one bit per node from the device map),
 // k_publish (counts to the host).
 // Then: k_gather (feature retrieve), k_block_mean (neighbour aggregation of one block),

@@ -5,15 +5,23 @@
 namespace a3 {
 
 // ---------------------------------------------------------------------------
-// step a5: dedup + relabel.  node_map[g] now holds, for every sampled global id g, either its
-// local id (< n_dst, g is a destination) or n_dst + (position of g's first occurrence).
+// step a5: dedup + relabel.  node_map[g] now holds, for every sampled global id g, map_base plus
+// either its local id (< n_dst, g is a destination) or n_dst + (position of g's first occurrence).
+//
+// The relabel map is never cleaned between calls.  A call's values lie in [map_base, map_base +
+// span), span being the most positions a call of this context can number, and every call takes
+// the range just below the previous call's: whatever an earlier call left in an entry is larger
+// than anything this call writes, so to the atomicMin that records first occurrences it is as good
+// as empty, and no entry this call reads can hold it (the call wrote there first).  The host
+// refills the map with the largest value when the ranges reach the bottom of int32, once in
+// hundreds to hundreds of thousands of calls.
 // Both kernels issue their reads in batches of independent loads (every edge of a thread at
 // once), so a workgroup goes through two or three memory round trips, not one per step of an
 // edge's chain.  The launches are sized for a bound on the hop's edges that can be several
 // times the real count: workgroups past the count leave before they read anything else.
 // ---------------------------------------------------------------------------
 template <typename IdxT>
-__global__ __launch_bounds__(kTileThreads) void k_flag(const IdxT* gid, const int32_t* node_map,
+__global__ __launch_bounds__(kTileThreads) void k_flag(const IdxT* gid, const int32_t* node_map, int32_t map_base,
                                                        DevState* st, int hop, int64_t num_nodes,
                                                        int32_t* first_pos, int32_t* local_rank,
                                                        int32_t* tile_sums) {
@@ -30,7 +38,10 @@ __global__ __launch_bounds__(kTileThreads) void k_flag(const IdxT* gid, const in
   for (int k = 0; k < kTilePerThread; ++k) {
     const int64_t g = g_of[k];
     p_of[k] = 0;
-    if (base_e + k < n && g >= 0 && g < num_nodes) p_of[k] = node_map[g];
+    if (base_e + k < n && g >= 0 && g < num_nodes) {
+      const int64_t rel = (int64_t)node_map[g] - (int64_t)map_base;  // this call's own value: in [0, span)
+      p_of[k] = rel >= 0 && rel <= 0x7FFFFFFFll ? (int32_t)rel : -1;
+    }
   }
   uint32_t flag[kTilePerThread];
   uint32_t sum = 0;
@@ -61,9 +72,8 @@ __global__ __launch_bounds__(kTileThreads) void k_flag(const IdxT* gid, const in
 // tile_offs null the workgroup scans k_flag's tile sums itself (few tiles) and workgroup 0
 // publishes the hop's source count.
 // Where a node is first numbered its device-map entry is looked up, once (S_slot: the retrieve
-// of the input nodes then reads its slots in sequence).  In the last hop the relabel map is
-// emptied instead of completed: a new node's entry is reset rather than set, and the entries of
-// the hop's destinations (every node numbered before) are reset by a loop over them.
+// of the input nodes then reads its slots in sequence), and its relabel-map entry becomes its
+// local id, for the hops that follow; the last hop, which nothing follows, leaves the map alone.
 constexpr int kRelabelPerThread = 4;
 
 template <typename IdxT>
@@ -81,6 +91,7 @@ struct RelabelArgs {
   int64_t cap_src;           // entries in S, S_slot
   IdxT* S;
   int32_t* node_map;
+  int32_t map_base;
   int32_t* blk_indices;
   const int32_t* cache_map;  // or null
   int32_t* S_slot;
@@ -97,10 +108,9 @@ __global__ __launch_bounds__(kTileThreads) void k_relabel(const RelabelArgs<IdxT
   const int32_t n_dst = a.st->n_dst[a.hop];
   if (blockIdx.x == 0 && threadIdx.x == 0)
     for (int b = 0; b < kNumBins + 2; ++b) a.st->bin_count[b] = 0;
-  // a workgroup past the hop's edges has only its share of the map reset to do (last hop);
-  // workgroup 0 stays in any case: it publishes the hop's source count
-  const bool idle = blockIdx.x != 0 && (int64_t)blockIdx.x * kRelabelPerThread * kTileThreads >= n;
-  if (idle && !(a.last_hop && (int64_t)blockIdx.x * kTileThreads < (int64_t)n_dst)) return;
+  // a workgroup past the hop's edges leaves; workgroup 0 stays in any case: it publishes the
+  // hop's source count
+  if (blockIdx.x != 0 && (int64_t)blockIdx.x * kRelabelPerThread * kTileThreads >= n) return;
   int64_t e_of[kRelabelPerThread];
   int32_t p_of[kRelabelPerThread];
   IdxT g_of[kRelabelPerThread];
@@ -119,13 +129,6 @@ __global__ __launch_bounds__(kTileThreads) void k_relabel(const RelabelArgs<IdxT
       const int32_t n_src = n_dst + (int32_t)total;
       a.st->n_src[a.hop] = n_src;
       a.st->n_dst[a.hop + 1] = n_src;
-    }
-  }
-  if (a.last_hop) {  // empty the relabel map: the destinations here, the new nodes below
-    const int64_t stride = (int64_t)gridDim.x * kTileThreads;
-    for (int64_t i = (int64_t)blockIdx.x * kTileThreads + threadIdx.x; i < (int64_t)n_dst; i += stride) {
-      const int64_t v = (int64_t)a.S[i];
-      if (v >= 0 && v < a.num_nodes) a.node_map[v] = kMapEmpty;
     }
   }
   // second batch of reads: the rank of every edge's first occurrence; for a first occurrence
@@ -172,7 +175,7 @@ __global__ __launch_bounds__(kTileThreads) void k_relabel(const RelabelArgs<IdxT
         if (is_new[k] && local >= 0 && (int64_t)local < a.cap_src) {
           const int64_t g = (int64_t)g_of[k];
           a.S[local] = g_of[k];
-          a.node_map[g] = a.last_hop ? kMapEmpty : local;
+          if (!a.last_hop) a.node_map[g] = a.map_base + local;
           if (a.cache_map) a.S_slot[local] = slot_of[k];
         } else {
           atomicOr(&a.st->error, kErrNewNode);

@@ -19,7 +19,8 @@ struct SampleArgs {
   int32_t* blk_indptr;       // out: edge offsets of this hop
   IdxT* gid;                 // out: global id of each sampled neighbour
   int64_t* eids;             // out: CSR position of each sampled edge (may be null)
-  int32_t* node_map;         // global id -> first position / local id
+  int32_t* node_map;         // global id -> map_base + (first position / local id)
+  int32_t map_base;
   DevState* st;
   const NodeRec* bins[kNumBins];
   int32_t wide_count, hub_count;  // which of the state block's bin counters hold the sizes of bins[3], bins[4]
@@ -67,7 +68,7 @@ struct Emitter {
     }
     a.gid[e] = g;
     if (a.eids) a.eids[e] = eid;
-    atomicMin(&a.node_map[(int64_t)g], n_dst + e);
+    atomicMin(&a.node_map[(int64_t)g], a.map_base + n_dst + e);
   }
 };
 

@@ -33,6 +33,7 @@ struct a3_ctx {
   // arena (device)
   void* S = nullptr;  // local -> global, 8 bytes per entry reserved
   int32_t* S_slot = nullptr;  // device-map entry of each local id (calls that were given a map)
+  int32_t* block_seen = nullptr;  // per workgroup of k_cached_bits: which weight classes it met
   const int32_t* last_cache_map = nullptr;  // the map whose entries S_slot holds, or null
   int32_t* blk_indptr[A3_MAX_HOPS] = {nullptr};
   int32_t* blk_indices[A3_MAX_HOPS] = {nullptr};
@@ -46,12 +47,12 @@ struct a3_ctx {
   int32_t* tile_offs2 = nullptr;  // new-node offsets of the edge tiles (read by k_relabel)
   a3::NodeRec* bins[a3::kNumBins + 2] = {nullptr};  // frontier node records by degree bin; then the wide
                                                     // nodes and hubs a weighted hop leaves to its second launch
-  int32_t* node_map = nullptr;  // global id -> position, grown on demand
+  int32_t* node_map = nullptr;  // global id -> map_base + position, grown on demand
   int64_t node_map_cap = 0;
+  int64_t map_floor = 0;        // the lowest value any call has written into node_map so far
+  int32_t map_base = 0;         // the running call's offset (its values: [map_base, map_base + span))
   uint64_t* cached_bits = nullptr;  // one bit per node, rebuilt from the device map by every weighted call
   int64_t cached_bits_words = 0;
-  int32_t* block_seen = nullptr;  // per workgroup of k_cached_bits: which weight classes it met
-  bool node_map_dirty = false;
   int32_t* fifo_rank = nullptr;   // FIFO update: per id, rank among its tile's misses (grown on demand)
   int64_t fifo_rank_cap = 0;
   int32_t* fifo_tiles = nullptr;  // FIFO update: tile sums, then tile offsets
@@ -219,7 +220,12 @@ void free_all(a3_ctx* ctx) {
   ctx->sampled = nullptr;
 }
 
+// The relabel map for a call on num_nodes nodes, and the call's value range in it: just below the
+// previous call's, so that nothing has to be cleaned between calls (see a3_relabel.hpp).  The map
+// is refilled with the largest value when it is first made or enlarged, and when the ranges have
+// reached the bottom of int32.
 int ensure_node_map(a3_ctx* ctx, int64_t num_nodes) {
+  bool refill = false;
   if (num_nodes > ctx->node_map_cap) {
     if (ctx->node_map) {
       A3_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -231,14 +237,18 @@ int ensure_node_map(a3_ctx* ctx, int64_t num_nodes) {
     A3_HIP(ctx, hipMalloc(&q, (size_t)std::max<int64_t>(num_nodes, 1) * sizeof(int32_t)));
     ctx->node_map = (int32_t*)q;
     ctx->node_map_cap = num_nodes;
-    ctx->node_map_dirty = true;
+    refill = true;
   }
-  if (ctx->node_map_dirty) {
+  const int64_t span = std::max<int64_t>(ctx->cap_dst[ctx->max_hops], 1);  // positions a call can number
+  if (ctx->map_floor - span < (int64_t)INT32_MIN) refill = true;
+  if (refill) {
     hipLaunchKernelGGL(a3::k_fill_i32, dim3(std::min(blocks_for(ctx->node_map_cap, 256), 1u << 20)), dim3(256), 0,
                        ctx->stream, ctx->node_map, ctx->node_map_cap, a3::kMapEmpty);
     A3_HIP(ctx, hipGetLastError());
-    ctx->node_map_dirty = false;
+    ctx->map_floor = (ctx->flags & A3_TEST_MAP_RANGE) ? (int64_t)INT32_MIN + 2 * span + 5 : (int64_t)a3::kMapEmpty;
   }
+  ctx->map_floor -= span;
+  ctx->map_base = (int32_t)ctx->map_floor;
   return A3_OK;
 }
 
@@ -294,7 +304,6 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
 
   int rc = ensure_node_map(ctx, num_nodes);
   if (rc != A3_OK) return rc;
-  ctx->node_map_dirty = true;  // until the call has cleaned up after itself
 
   prof_mark(ctx, 0, 0);
   if (weighted) {
@@ -303,9 +312,10 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
   }
   if (validate) {
     hipLaunchKernelGGL(a3::k_init_seeds_checked<IdxT>, dim3(blocks_for(num_seeds, 256)), dim3(256),
-                       0, st, seeds, num_seeds, num_nodes, S, ctx->node_map, ds, cache_map, ctx->S_slot);
+                       0, st, seeds, num_seeds, num_nodes, S, ctx->node_map, ctx->map_base, ds, cache_map,
+                       ctx->S_slot);
     hipLaunchKernelGGL(a3::k_check_seeds<IdxT>, dim3(blocks_for(num_seeds, 256)), dim3(256), 0, st,
-                       seeds, num_seeds, num_nodes, ctx->node_map, ds);
+                       seeds, num_seeds, num_nodes, ctx->node_map, ctx->map_base, ds);
     hipLaunchKernelGGL(a3::k_set_frontier_size, dim3(1), dim3(64), 0, st, ds, (int32_t)num_seeds);
   }
 
@@ -322,6 +332,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
     fa.S_slot = ctx->S_slot;
     fa.S = S;
     fa.node_map = ctx->node_map;
+    fa.map_base = ctx->map_base;
     fa.indptr = indptr;
     fa.st = ds;
     fa.hop = h;
@@ -350,6 +361,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       sa.gid = gid;
       sa.eids = ctx->blk_eids[h];
       sa.node_map = ctx->node_map;
+      sa.map_base = ctx->map_base;
       sa.st = ds;
       for (int b = 0; b < a3::kNumBins; ++b) sa.bins[b] = ctx->bins[b];
       sa.num_nodes = num_nodes;
@@ -421,7 +433,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
     }
     // a5: first occurrences -> numbering of new nodes -> local ids
     hipLaunchKernelGGL(a3::k_flag<IdxT>, dim3(edge_tiles), dim3(a3::kTileThreads), 0, st, gid,
-                       ctx->node_map, ds, h, num_nodes, ctx->first_pos, ctx->local_rank,
+                       ctx->node_map, ctx->map_base, ds, h, num_nodes, ctx->first_pos, ctx->local_rank,
                        ctx->tile_sums2);
     if (!fuse_edges)
       hipLaunchKernelGGL(a3::k_scan_tiles, dim3(1), dim3(a3::kTileThreads), 0, st, ctx->tile_sums2,
@@ -435,11 +447,12 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
     ra.cap_tiles = ctx->cap_tiles;
     ra.st = ds;
     ra.hop = h;
-    ra.last_hop = h == num_hops - 1 ? 1 : 0;  // the last hop's launch leaves the relabel map empty
+    ra.last_hop = h == num_hops - 1 ? 1 : 0;  // nothing follows: the relabel map needs no local ids
     ra.num_nodes = num_nodes;
     ra.cap_src = ctx->cap_dst[ctx->max_hops];
     ra.S = S;
     ra.node_map = ctx->node_map;
+    ra.map_base = ctx->map_base;
     ra.blk_indices = ctx->blk_indices[h];
     ra.cache_map = cache_map;
     ra.S_slot = ctx->S_slot;
@@ -480,8 +493,6 @@ int sample_finish(a3_ctx* ctx, a3_blocks* out) {
                 "a3_sample_blocks: an index left its array (ids in indices/seeds outside the "
                 "graph, or an internal error; guard bits " + std::to_string(hs.error) +
                     "); outputs are invalid");
-  ctx->node_map_dirty = false;
-
   const int num_hops = ctx->last_hops;
   std::memset(out, 0, sizeof(*out));
   out->num_hops = num_hops;

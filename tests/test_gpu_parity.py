@@ -266,6 +266,25 @@ def test_input_rows_by_stored_map_entries_and_by_lookup_agree(flags, host_workgr
     ctx.close()
 
 
+@pytest.mark.parametrize("flags", [a3.A3_TEST_MAP_RANGE, a3.A3_TEST_MAP_RANGE | a3.A3_VALIDATE])
+def test_relabel_map_ranges_down_to_the_bottom_of_int32_and_refills(flags):
+    """The relabel map is never cleaned: each call writes values below the previous call's.  With
+    the testing flag the ranges start just above the bottom of int32 (negative values) and every
+    third call refills the map; a run of calls with different seeds, fanouts and an input error in
+    between must equal the oracle call by call."""
+    w, g, d_ip, d_ix = _graph("mini_copurchase")
+    cm = degree_ranked_cache(g, None, 0.3).cache_map.numpy()
+    ctx = a3.Context(200, [15, 10, 5], flags=flags)
+    for b in range(8):
+        seeds = seed_batch(w.num_nodes, 200 - 20 * b, 5, b)
+        fan = [[15, 10, 5], [3, 2], [15]][b % 3]
+        _compare(ctx, w, g, d_ip, d_ix, seeds, fan, cm if b % 2 else None, 4.0 if b % 2 else 1.0, b, "map ranges")
+        if b == 4 and (flags & a3.A3_VALIDATE):
+            with pytest.raises(a3.A3Error):
+                ctx.sample_blocks(d_ip, d_ix, torch.tensor([7, 9, 7], dtype=torch.int32, device=DEV), [2])
+    ctx.close()
+
+
 def test_isolated_nodes_and_no_eids():
     indptr = torch.tensor([0, 0, 1, 2, 2], dtype=torch.int64)
     indices = torch.tensor([2, 1], dtype=torch.int64)
