@@ -414,10 +414,11 @@ def measure(args, name, headline, legs):
         dg = oracle_rows(ob.input_nodes.astype(np.int64))
         spent, best = dt + dg, (1, ob, dt, dg)
         # the oracle scans five to six million neighbour slots a second on one core, and the slots
-        # that each hop scans are known from the GPU's blocks: as many hops as ten million slots per
-        # second of budget allow (so the run takes up to twice the budget)
+        # that each hop scans are known from the GPU's blocks: as many hops as twelve million slots
+        # per second of budget allow (so the run takes up to about twice the budget; the default
+        # budget of 20 s admits the first two hops of `citation`, 204 M slots, and all of the others)
         hops = 1
-        while hops < H and sum(scanned_per_hop[:hops + 1]) <= 10e6 * args.cpu_seconds:
+        while hops < H and sum(scanned_per_hop[:hops + 1]) <= 12e6 * args.cpu_seconds:
             hops += 1
         if hops > 1:
             ob, dt = oracle_run(b_last, hops)
@@ -604,30 +605,41 @@ def run_policies(args):
             host[r0:r0 + step] = full[order_rest[r0:r0 + step].long()].cpu()
         return host
 
+    def second_launch_nodes(ctx, blk):
+        """frontier nodes of a weighted call that its fast sampling launches could not decide, as a
+        share of all its frontier nodes (under the single-launch plan: all of them)"""
+        st = ctx.sample_stats()
+        if st["launch_plan"] == 0:
+            return 0.0
+        if st["launch_plan"] == 2:
+            return 1.0
+        return (st["deferred_wide_nodes"] + st["deferred_hubs"]) / max(sum(blk.n_dst), 1)
+
     def run_static(cache_map, feat_dev, feat_host, gamma):
         q = int(gamma * 65536)
-        hits = n_in = 0
+        hits = n_in = left = 0
         ctx.profile_read(0), ctx.profile_read(1)
         for b in range(args.presample, args.presample + K):
             ctx.sample_blocks_begin(g.indptr, g.indices, seeds[b], w.fanouts, cache_map, q, b)
             ctx.gather_input_features(feat_dev, feat_host, cache_map, rows)
             blk = ctx.sample_blocks_end()
+            left += second_launch_nodes(ctx, blk)
             ids = blk.input_nodes.long()
             hits += int((cache_map[ids] >= 0).sum().item())
             n_in += ids.numel()
         torch.cuda.synchronize()
-        return hits / n_in, n_in / K, sum(ctx.profile_read(0)) / K, sum(ctx.profile_read(1)) / K
+        return hits / n_in, n_in / K, sum(ctx.profile_read(0)) / K, sum(ctx.profile_read(1)) / K, left / K
 
     print(f"# cache policies on `{w.name}`: N={N:,}, {w.row_bytes}-B rows, cache {cache_frac:.0%} = {n_cached:,} rows, "
           f"batch {w.batch}, fanouts {w.fanouts}, {K} mini-batches per row (device times from HIP events)")
-    print("| policy | gamma | hit rate | input rows | ms sample | ms gather | ms policy | ms total |")
-    print("|---|---|---|---|---|---|---|---|")
+    print("| policy | gamma | hit rate | input rows | nodes sampled by the slow launch | ms sample | ms gather | ms policy | ms total |")
+    print("|---|---|---|---|---|---|---|---|---|")
     gammas = [float(x) for x in (args.gammas or "1,4").split(",")]
     # 1. degree-ranked static fill
     split = degree_ranked_cache(g, full, cache_frac, pin_host=True)
     for gamma in gammas:
-        h, n, ms_s, ms_g = run_static(split.cache_map, split.feat_dev, split.feat_host, gamma)
-        print(f"| static, by degree | {gamma:g} | {h:.3f} | {n:.0f} | {ms_s:.3f} | {ms_g:.3f} | - | {ms_s + ms_g:.3f} |", flush=True)
+        h, n, ms_s, ms_g, left = run_static(split.cache_map, split.feat_dev, split.feat_host, gamma)
+        print(f"| static, by degree | {gamma:g} | {h:.3f} | {n:.0f} | {left:.1%} | {ms_s:.3f} | {ms_g:.3f} | - | {ms_s + ms_g:.3f} |", flush=True)
     del split
     # 2. access-count-ranked static fill: pre-sample, count, rank, build the two stores by gathers
     counts = torch.zeros(N, dtype=torch.int32, device=dev)
@@ -643,9 +655,9 @@ def run_policies(args):
     setup_ms = ev0.elapsed_time(ev1)
     feat_host = host_rows(order[n_cached:])
     for gamma in gammas:
-        h, n, ms_s, ms_g = run_static(cache_map, feat_dev, feat_host, gamma)
+        h, n, ms_s, ms_g, left = run_static(cache_map, feat_dev, feat_host, gamma)
         print(f"| static, by access count ({args.presample} pre-sampled batches, set-up {setup_ms:.1f} ms on the GPU) | {gamma:g} | "
-              f"{h:.3f} | {n:.0f} | {ms_s:.3f} | {ms_g:.3f} | - | {ms_s + ms_g:.3f} |", flush=True)
+              f"{h:.3f} | {n:.0f} | {left:.1%} | {ms_s:.3f} | {ms_g:.3f} | - | {ms_s + ms_g:.3f} |", flush=True)
     del feat_dev, feat_host, cache_map, order
     # 3. FIFO dynamic cache from empty; the host store holds every row
     host_all = host_rows(torch.arange(N, device=dev))
@@ -656,13 +668,14 @@ def run_policies(args):
         state = torch.zeros(4, dtype=torch.int32, device=dev)
         cache = torch.zeros((n_cached, w.feat_dim), dtype=w.feat_dtype, device=dev)
         ctx.profile_read(0), ctx.profile_read(1)
-        hits = n_in = 0
+        hits = n_in = left = 0
         first_hit = last_hit = 0.0
         ms_pol = 0.0
         for b in range(args.presample, args.presample + K):
             ctx.sample_blocks_begin(g.indptr, g.indices, seeds[b], w.fanouts, cm, q, b)
             ctx.gather_input_features(cache, host_all, cm, rows)
             blk = ctx.sample_blocks_end()
+            left += second_launch_nodes(ctx, blk)
             ids = blk.input_nodes.long()
             hb = int((cm[ids] >= 0).sum().item())   # judged before the update
             ev0.record()
@@ -677,7 +690,7 @@ def run_policies(args):
             last_hit = hb / ids.numel()
         ms_s, ms_g = sum(ctx.profile_read(0)) / K, sum(ctx.profile_read(1)) / K
         print(f"| FIFO, from empty (hit rate of batch 2: {first_hit:.3f}, of the last: {last_hit:.3f}) | {gamma:g} | "
-              f"{hits / n_in:.3f} | {n_in / K:.0f} | {ms_s:.3f} | {ms_g:.3f} | {ms_pol / K:.3f} | "
+              f"{hits / n_in:.3f} | {n_in / K:.0f} | {left / K:.1%} | {ms_s:.3f} | {ms_g:.3f} | {ms_pol / K:.3f} | "
               f"{ms_s + ms_g + ms_pol / K:.3f} |", flush=True)
     ctx.close()
 

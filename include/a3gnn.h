@@ -158,9 +158,13 @@ int a3_sample_blocks_end(a3_ctx* ctx, a3_blocks* out);
  *   [1] wide nodes (65 ... 4096 neighbours) and [2] hubs that the first sampling launch of a hop
  *       could not decide from their best draws alone (fewer than `fanout` cached among them, or odd
  *       list sizes) and left to the slower second launch;
- *   [3] nodes selected by the exhaustive bit-by-bit path (about one in 10^5 by design).
+ *   [3] nodes selected by the exhaustive bit-by-bit path (about one in 10^5 by design);
+ *   [4] the launch plan of that call: 0 no weights, 1 two launches per hop (the fast one, then
+ *       the one for what it left over), 2 one full launch per hop.  A context switches to plan 2
+ *       for its next 16 weighted calls when [1] + [2] exceeds a fifth of the call's frontier
+ *       nodes, then tries plan 1 again; the blocks are the same under either plan.
  * A3_ERR_INVALID_ARG before the first ended call or while a begun call is pending. */
-int a3_sample_stats(a3_ctx* ctx, int64_t stats[4]);
+int a3_sample_stats(a3_ctx* ctx, int64_t stats[5]);
 
 /* Feature retrieve (Alg. 1 line 10): out[i,:] = feat_dev[c,:] if
  * c = cache_map[ids[i]] >= 0, else feat_host[-c-1,:].
@@ -282,7 +286,7 @@ int a3_cache_fifo_update(a3_ctx* ctx, int32_t* cache_map, int64_t num_nodes, int
 /* a3_cache_fifo_update for callers that cannot allocate device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results,
  * same asynchrony; it calls no hipMalloc / hipFree and no allocating library routine.  Its scratch
- * (one int32 per id, two per 1 024 ids) lives in a static device array of the library, 4 MiB + 8 KiB
+ * (one int32 per id, two per 1 024 ids) lives in a static device array of the library, 16 MiB + 32 KiB
  * that every GPU the library runs on holds until the process ends, so
  *   n_ids <= A3_FIFO_STATIC_MAX_IDS, A3_ERR_CAPACITY otherwise (with ids == NULL the limit applies
  *   to the bound on the input nodes of the last sampled mini-batch: seeds x prod(1 + fanout),
@@ -291,7 +295,7 @@ int a3_cache_fifo_update(a3_ctx* ctx, int32_t* cache_map, int64_t num_nodes, int
  * All calls on one GPU share the array: calls that overlap on one GPU (two streams, two contexts,
  * two threads) race; calls on one stream, or ordered by events, do not.  Nothing of an earlier
  * call's scratch contents is read. */
-#define A3_FIFO_STATIC_MAX_IDS (1 << 20)
+#define A3_FIFO_STATIC_MAX_IDS (1 << 22)
 int a3_cache_fifo_update_static(a3_ctx* ctx, int32_t* cache_map, int64_t num_nodes, int32_t* slot_owner,
                                 int32_t* fifo_state, int64_t n_slots, void* feat_dev, int64_t row_bytes,
                                 const void* ids, int32_t idx_bytes, int64_t n_ids, const void* rows);

@@ -15,7 +15,7 @@ A3_MAX_FANOUT = 1024
 A3_OK, A3_ERR_INVALID_ARG, A3_ERR_CAPACITY, A3_ERR_HIP, A3_ERR_INPUT = 0, -1, -2, -3, -4
 A3_VALIDATE, A3_NO_EIDS, A3_HOST_ONLY, A3_FORCE_RADIX, A3_PROFILE, A3_TEST_MAP_RANGE = 1, 2, 4, 8, 16, 32
 A3_PROFILE_DEPTH = 256
-A3_FIFO_STATIC_MAX_IDS = 1 << 20
+A3_FIFO_STATIC_MAX_IDS = 1 << 22
 A3_PIPE_SEQUENTIAL, A3_PIPE_MODE1, A3_PIPE_MODE2 = 0, 1, 2
 A3_PIPE_MAX_WORKERS = 8
 A3_F32, A3_F16 = 0, 1
@@ -335,10 +335,11 @@ class Context:
 
     def sample_stats(self) -> dict:
         """which paths the last ended sampling call took (see a3_sample_stats)"""
-        buf = (C.c_int64 * 4)()
+        buf = (C.c_int64 * 5)()
         self._check(lib().a3_sample_stats(self._h, buf))
         return {"weight_classes": int(buf[0]), "deferred_wide_nodes": int(buf[1]),
-                "deferred_hubs": int(buf[2]), "exhaustive_nodes": int(buf[3])}
+                "deferred_hubs": int(buf[2]), "exhaustive_nodes": int(buf[3]),
+                "launch_plan": int(buf[4])}
 
     def gather_input_features(self, feat_dev: Optional[torch.Tensor],
                               feat_host: Optional[torch.Tensor], cache_map: Optional[torch.Tensor],

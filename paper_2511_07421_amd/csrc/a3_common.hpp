@@ -36,7 +36,7 @@ struct DevState {
   int32_t n_deferred[2];  // weighted calls: wide nodes / hubs that the first launch of a hop left to the second
   int32_t class_mix;  // weighted calls: bit 0 some node is cached, bit 1 some node is not
   // scratch of the running hop; zero between hops and between calls
-  int32_t bin_count[kNumBins + 2];  // the degree bins, then the two lists of nodes left to a second launch
+  int32_t bin_count[kNumBins];  // the degree bins
 };
 
 // What k_sample needs to know of a frontier node; k_frontier has it all in registers and writes
@@ -48,7 +48,7 @@ struct NodeRec {
   uint32_t deg;       // degree (0 for a row that k_frontier refused)
   int32_t i;          // position in the frontier (destination id of the block)
   int32_t local_off;  // edges of earlier nodes of the same scan tile
-  int32_t pad;
+  int32_t left;       // set by the first sampling launch of a weighted hop: the second launch samples this node
 };
 
 // ---------------------------------------------------------------------------

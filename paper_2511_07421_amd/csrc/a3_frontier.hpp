@@ -150,7 +150,7 @@ __global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<Id
       rec[k].row = row;
       rec[k].deg = (uint32_t)deg;
       rec[k].i = (int32_t)i;
-      rec[k].pad = 0;
+      rec[k].left = 0;
     }
   }
   // rank of every node inside its bin and workgroup: a wavefront counts its nodes of a bin with

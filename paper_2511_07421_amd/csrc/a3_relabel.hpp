@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kTileThreads) void k_relabel(const RelabelArgs<IdxT
   const int64_t n = a.st->n_edges[a.hop];
   const int32_t n_dst = a.st->n_dst[a.hop];
   if (blockIdx.x == 0 && threadIdx.x == 0)
-    for (int b = 0; b < kNumBins + 2; ++b) a.st->bin_count[b] = 0;
+    for (int b = 0; b < kNumBins; ++b) a.st->bin_count[b] = 0;
   // a workgroup past the hop's edges leaves; workgroup 0 stays in any case: it publishes the
   // hop's source count
   if (blockIdx.x != 0 && (int64_t)blockIdx.x * kRelabelPerThread * kTileThreads >= n) return;

@@ -22,9 +22,8 @@ struct SampleArgs {
   int32_t* node_map;         // global id -> map_base + (first position / local id)
   int32_t map_base;
   DevState* st;
-  const NodeRec* bins[kNumBins];
-  int32_t wide_count, hub_count;  // which of the state block's bin counters hold the sizes of bins[3], bins[4]
-  NodeRec* deferred[2];           // kWeightedFast: wide nodes / hubs left to the second launch (counters 5, 6)
+  NodeRec* bins[kNumBins];   // kWeightedFast sets `left` in the records of bins 3, 4 that it leaves to the second launch
+  uint32_t left_only;        // kWeightedFull as a second launch: only the records with `left` set
   int64_t num_nodes;
   int64_t cap_edges;         // entries in gid / eids (arena capacity of this hop)
   uint32_t role_blocks[5];   // workgroups serving bins 0, 1, 2 (lane groups), 3 (wide), 4 (hubs)
@@ -505,21 +504,18 @@ __device__ __forceinline__ uint32_t second_list_floor(float keep, uint32_t bias_
 // cand [cap] and rest [m (+ 3 m + 2 xcap + capb when weighted)] are this wavefront's LDS buffers.
 // With prefiltered set, cand already holds pre_cnt candidates in slot order (a workgroup scanned
 // the row together; pre_cnt_b entries of the second list too) and the scan is skipped.
-// kWeightedFast: the node goes to the second launch (one record, written by lane 0)
-template <typename IdxT>
-__device__ __forceinline__ void defer_node(const SampleArgs<IdxT>& a, const NodeRec& r) {
-  if (lane_id() == 0) {
-    const int which = r.deg <= kHubDegree ? 0 : 1;
-    const int32_t at = atomicAdd(&a.st->bin_count[kNumBins + which], 1);
-    a.deferred[which][at] = r;
-    atomicAdd(&a.st->n_deferred[which], 1);
-  }
+// kWeightedFast: the node goes to the second launch.  A mark in its own record and no shared
+// list: a list needs a counter, and thousands of atomics on one word stall every wavefront
+// that touches the counter's cache line (0.2 ms per hop with a few thousand nodes left over).
+__device__ __forceinline__ void defer_node(int32_t* left) {
+  if (lane_id() == 0) *left = 1;
 }
 
 template <typename IdxT, int kMode>
 __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, const int32_t* tile_offs,
                                  const NodeRec& r, int32_t n_dst, uint64_t* cand, uint64_t* rest,
-                                 bool prefiltered, uint32_t pre_cnt, uint32_t pre_cnt_b) {
+                                 bool prefiltered, uint32_t pre_cnt, uint32_t pre_cnt_b,
+                                 bool both_classes, int32_t* left) {
   const uint32_t lane = lane_id();
   const int64_t v = r.v;
   const int64_t row = r.row;
@@ -558,7 +554,7 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
   // with one weight class in the whole graph the weighted kernel takes the uniform path
   constexpr bool kWeighted = kMode != kUniform;
   constexpr bool kFast = kMode == kWeightedFast;
-  const bool two_classes = kWeighted && a.st->class_mix == 3;
+  const bool two_classes = kWeighted && both_classes;
   const bool want_b = !kFast && two_classes && a.capb > 0;
   const uint32_t X1 = want_b ? second_list_floor(keep, a.bias_q16) : 0u;
   if (!a.force_radix && !prefiltered) {
@@ -629,7 +625,7 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
     }
   }
   if (kFast && two_classes) {  // everything else is the second launch's business
-    defer_node(a, r);
+    defer_node(left);
     wave_sync();
     return;
   }
@@ -775,7 +771,7 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
 // O(m log G) instead of ranking every slot against every other.
 template <typename IdxT, int G, int kMode>
 __device__ void sample_node_group(const SampleArgs<IdxT>& a, const int32_t* tile_offs,
-                                  const NodeRec& r, int32_t n_dst) {
+                                  const NodeRec& r, int32_t n_dst, bool both_classes) {
   const uint32_t lane = lane_id();
   const uint32_t gl = lane & (G - 1);       // lane inside the group
   const uint32_t gshift = lane & ~(G - 1);  // first lane of the group inside the wavefront
@@ -800,7 +796,7 @@ __device__ void sample_node_group(const SampleArgs<IdxT>& a, const int32_t* tile
 #pragma unroll
   for (int w = 0; w < 4; ++w) alive |= (4u * gl + w < deg) ? (1u << w) : 0u;
   uint64_t K[4] = {0, 0, 0, 0};
-  if (kMode != kUniform && a.st->class_mix == 3) {
+  if (kMode != kUniform && both_classes) {
     bool cached[4];
     bool any_c = false, any_u = false;
 #pragma unroll
@@ -887,7 +883,7 @@ constexpr uint32_t kHubRegion = 64;  // candidates one wavefront may contribute
 template <typename IdxT, int kMode>
 __device__ __forceinline__ void hub_scan(const SampleArgs<IdxT>& a, const NodeRec& r, uint64_t* lds,
                                          uint64_t*& joined_out, uint64_t*& rest_out, uint32_t& pre_cnt,
-                                         uint32_t& pre_cnt_b) {
+                                         uint32_t& pre_cnt_b, bool both_classes) {
   const uint32_t lane = lane_id();
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(threadIdx.x >> 6));
   const uint32_t n_waves = blockDim.x >> 6;
@@ -901,7 +897,7 @@ __device__ __forceinline__ void hub_scan(const SampleArgs<IdxT>& a, const NodeRe
   // the second candidate list of the weighted case is shared: wavefronts reserve space in it
   // with one LDS atomic per append (its order does not matter)
   uint64_t* list_b = rest + 4 * (size_t)a.fanout + 2 * (size_t)a.xcap;
-  const bool want_b = kMode == kWeightedFull && a.capb > 0 && a.st->class_mix == 3;
+  const bool want_b = kMode == kWeightedFull && a.capb > 0 && both_classes;
   if (want_b) {
     if (threadIdx.x == 0) *shared_cnt_b = 0;
     __syncthreads();
@@ -1003,7 +999,7 @@ __device__ __forceinline__ void hub_scan(const SampleArgs<IdxT>& a, const NodeRe
 template <typename IdxT, int G, int kMode>
 __device__ __forceinline__ void run_group_role(const SampleArgs<IdxT>& a, const int32_t* tile_offs,
                                                int bin, uint32_t block_in_role,
-                                               uint32_t blocks_in_role, int32_t n_dst) {
+                                               uint32_t blocks_in_role, int32_t n_dst, bool both_classes) {
   const int64_t count = a.st->bin_count[bin];
   const uint32_t per_block = blockDim.x / G;
   const int64_t groups = (int64_t)blocks_in_role * per_block;
@@ -1013,7 +1009,7 @@ __device__ __forceinline__ void run_group_role(const SampleArgs<IdxT>& a, const 
   for (; item < count; item += groups) {
     NodeRec nxt = {};
     if (item + groups < count) nxt = a.bins[bin][item + groups];  // in flight while cur is sampled
-    if (cur.i >= 0 && cur.i < n_dst) sample_node_group<IdxT, G, kMode>(a, tile_offs, cur, n_dst);
+    if (cur.i >= 0 && cur.i < n_dst) sample_node_group<IdxT, G, kMode>(a, tile_offs, cur, n_dst, both_classes);
     cur = nxt;
   }
 }
@@ -1028,12 +1024,60 @@ __global__ __launch_bounds__(kSampleMaxThreads) void k_sample(const SampleArgs<I
   extern __shared__ uint64_t lds[];
   __shared__ int32_t fused_offs[kFuseTiles];
   __shared__ uint32_t fused_total;
-  // the second launch of a weighted hop usually finds its lists empty
-  if (kMode == kWeightedFull && a.st->bin_count[a.wide_count] == 0 && a.st->bin_count[a.hub_count] == 0) return;
+  __shared__ uint32_t block_left;
+  // Workgroups start in index order, so the roles with the longest-running workgroups come
+  // first (hubs, then wide nodes) and the short ones of the small-degree bins fill the end of the
+  // launch; the other way round the hubs would start last and the launch end with their tail.
+  uint32_t b = blockIdx.x;
+  const bool hub_role = b < a.role_blocks[4];  // the same for the whole workgroup
+  int group_bin = -1;
+  if (!hub_role) {
+    b -= a.role_blocks[4];
+    if (b >= a.role_blocks[3]) {
+      b -= a.role_blocks[3];
+      group_bin = 2;
+      if (b >= a.role_blocks[2]) {
+        b -= a.role_blocks[2];
+        group_bin = 1;
+        if (b >= a.role_blocks[1]) {
+          b -= a.role_blocks[1];
+          group_bin = 0;
+        }
+      }
+    }
+  }
+  // the wavefront's index inside the workgroup, held in a scalar register so that the node loops
+  // below are uniform control flow for the whole wavefront
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(threadIdx.x >> 6));
+  const uint32_t n_waves = blockDim.x >> 6;
+  const uint32_t lane = lane_id();
+  // wide nodes and hubs share one loop (and one copy of the selection code): a wavefront takes a
+  // wide node by itself; a hub is scanned by the whole workgroup and finished by wavefront 0
+  const int bin = hub_role ? 4 : 3;
+  NodeRec* recs = a.bins[bin];
+  const int64_t stride = hub_role ? (int64_t)a.role_blocks[4] : (int64_t)a.role_blocks[3] * n_waves;
+  const int64_t first = hub_role ? (int64_t)b : (int64_t)b * n_waves + wave;
+  int64_t n_nodes = 0;
+  // kWeightedFull walks its list 64 records at a time, one per lane: as a second launch it takes
+  // only the marked ones, and most workgroups find none and leave here, before anything else
+  uint64_t round0 = 0;
+  uint32_t n_left = 0;
+  if constexpr (kMode == kWeightedFull) {
+    if (group_bin < 0) {
+      n_nodes = a.st->bin_count[bin];
+      const int64_t tl = first + (int64_t)lane * stride;
+      round0 = __ballot(tl < n_nodes && (!a.left_only || recs[tl].left != 0));
+    }
+    if (a.left_only) {
+      if (threadIdx.x == 0) block_left = 0;
+      if (!__syncthreads_or(round0 != 0 || first + 64 * stride < n_nodes)) return;
+    }
+  }
   const int32_t* tile_offs = a.tile_offs;
   TileSums sums = {};
   if (tile_offs == nullptr) sums = tile_sums_load(a.tile_sums, a.cap_tiles);  // does not wait for n_dst
   const int32_t n_dst = a.st->n_dst[a.hop];
+  const bool both_classes = kMode != kUniform && a.st->class_mix == 3;  // read once, not per node
   if (tile_offs == nullptr) {  // few tiles: scan the tile sums here, publish the hop's edge count
     const uint32_t total = tile_prefix_from(sums, ((int64_t)n_dst + kTile - 1) >> kTileShift,
                                             fused_offs, &fused_total);
@@ -1043,49 +1087,56 @@ __global__ __launch_bounds__(kSampleMaxThreads) void k_sample(const SampleArgs<I
       a.blk_indptr[n_dst] = (int32_t)total;
     }
   }
-  // Workgroups start in index order, so the roles with the longest-running workgroups come
-  // first (hubs, then wide nodes) and the short ones of the small-degree bins fill the end of the
-  // launch; the other way round the hubs would start last and the launch end with their tail.
-  uint32_t b = blockIdx.x;
-  const bool hub_role = b < a.role_blocks[4];  // the same for the whole workgroup
-  if (!hub_role) {
-    b -= a.role_blocks[4];
-    if (b >= a.role_blocks[3]) {
-      b -= a.role_blocks[3];
-      if (b < a.role_blocks[2]) return run_group_role<IdxT, 16, kMode>(a, tile_offs, 2, b, a.role_blocks[2], n_dst);
-      b -= a.role_blocks[2];
-      if (b < a.role_blocks[1]) return run_group_role<IdxT, 8, kMode>(a, tile_offs, 1, b, a.role_blocks[1], n_dst);
-      b -= a.role_blocks[1];
-      return run_group_role<IdxT, 4, kMode>(a, tile_offs, 0, b, a.role_blocks[0], n_dst);
-    }
-  }
-  // the wavefront's index inside the workgroup, held in a scalar register so that the node loops
-  // below are uniform control flow for the whole wavefront
-  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(threadIdx.x >> 6));
-  const uint32_t n_waves = blockDim.x >> 6;
-  // wide nodes and hubs share one loop (and one copy of the selection code): a wavefront takes a
-  // wide node by itself; a hub is scanned by the whole workgroup and finished by wavefront 0
-  const int bin = hub_role ? 4 : 3;
-  const int64_t n_nodes = a.st->bin_count[hub_role ? a.hub_count : a.wide_count];
-  const NodeRec* recs = a.bins[bin];
-  const int64_t stride = hub_role ? (int64_t)a.role_blocks[4] : (int64_t)a.role_blocks[3] * n_waves;
-  int64_t t = hub_role ? (int64_t)b : (int64_t)b * n_waves + wave;
+  if (group_bin == 2) return run_group_role<IdxT, 16, kMode>(a, tile_offs, 2, b, a.role_blocks[2], n_dst, both_classes);
+  if (group_bin == 1) return run_group_role<IdxT, 8, kMode>(a, tile_offs, 1, b, a.role_blocks[1], n_dst, both_classes);
+  if (group_bin == 0) return run_group_role<IdxT, 4, kMode>(a, tile_offs, 0, b, a.role_blocks[0], n_dst, both_classes);
   uint64_t* my_lds = lds + (size_t)wave * a.lds_per_wave;
-  NodeRec cur = {};
-  if (t < n_nodes) cur = recs[t];
-  for (; t < n_nodes; t += stride) {
-    NodeRec nxt = {};
-    if (t + stride < n_nodes) nxt = recs[t + stride];  // in flight while cur is sampled
+  auto sample_one = [&](const NodeRec& cur, int32_t* left) {
     if (cur.i >= 0 && cur.i < n_dst) {
       uint64_t* cand = my_lds;
       uint64_t* rest = my_lds + a.cap;
       uint32_t pre_cnt = 0, pre_cnt_b = 0;
-      if (hub_role) hub_scan<IdxT, kMode>(a, cur, lds, cand, rest, pre_cnt, pre_cnt_b);
+      if (hub_role) hub_scan<IdxT, kMode>(a, cur, lds, cand, rest, pre_cnt, pre_cnt_b, both_classes);
       if (!hub_role || wave == 0)
-        sample_node_wave<IdxT, kMode>(a, tile_offs, cur, n_dst, cand, rest, hub_role, pre_cnt, pre_cnt_b);
+        sample_node_wave<IdxT, kMode>(a, tile_offs, cur, n_dst, cand, rest, hub_role, pre_cnt, pre_cnt_b,
+                                      both_classes, left);
       if (hub_role) __syncthreads();  // the regions are reused for the workgroup's next hub
     }
-    cur = nxt;
+  };
+  if constexpr (kMode == kWeightedFull) {
+    for (int64_t t0 = first; t0 < n_nodes; t0 += 64 * stride) {
+      uint64_t todo = round0;
+      if (t0 != first) {
+        const int64_t tl = t0 + (int64_t)lane * stride;
+        todo = __ballot(tl < n_nodes && (!a.left_only || recs[tl].left != 0));
+      }
+      n_left += (uint32_t)__popcll(todo);
+      NodeRec cur = {};
+      if (todo) cur = recs[t0 + (int64_t)__builtin_ctzll(todo) * stride];
+      while (todo) {
+        todo &= todo - 1;
+        NodeRec nxt = {};
+        if (todo) nxt = recs[t0 + (int64_t)__builtin_ctzll(todo) * stride];  // in flight while cur is sampled
+        sample_one(cur, nullptr);
+        cur = nxt;
+      }
+    }
+    if (a.left_only) {  // the call's count of nodes that needed this launch: one atomic per workgroup
+      if (lane == 0 && n_left != 0 && (!hub_role || wave == 0)) atomicAdd(&block_left, n_left);
+      __syncthreads();
+      if (threadIdx.x == 0 && block_left != 0) atomicAdd(&a.st->n_deferred[hub_role ? 1 : 0], (int32_t)block_left);
+    }
+  } else {
+    n_nodes = a.st->bin_count[bin];
+    int64_t t = first;
+    NodeRec cur = {};
+    if (t < n_nodes) cur = recs[t];
+    for (; t < n_nodes; t += stride) {
+      NodeRec nxt = {};
+      if (t + stride < n_nodes) nxt = recs[t + stride];  // in flight while cur is sampled
+      sample_one(cur, &recs[t].left);
+      cur = nxt;
+    }
   }
 }
 

@@ -45,12 +45,14 @@ struct a3_ctx {
   int32_t* tile_sums2 = nullptr;  // per edge tile: first occurrences
   int32_t* tile_offs = nullptr;   // edge offsets of the node tiles (read by k_sample)
   int32_t* tile_offs2 = nullptr;  // new-node offsets of the edge tiles (read by k_relabel)
-  a3::NodeRec* bins[a3::kNumBins + 2] = {nullptr};  // frontier node records by degree bin; then the wide
-                                                    // nodes and hubs a weighted hop leaves to its second launch
+  a3::NodeRec* bins[a3::kNumBins] = {nullptr};  // frontier node records by degree bin
   int32_t* node_map = nullptr;  // global id -> map_base + position, grown on demand
   int64_t node_map_cap = 0;
   int64_t map_floor = 0;        // the lowest value any call has written into node_map so far
   int32_t map_base = 0;         // the running call's offset (its values: [map_base, map_base + span))
+  int full_only_left = 0;       // weighted calls still to run with one full launch per hop
+  bool last_weighted = false;   // the launch plan of the last sampling call
+  bool last_full_only = false;
   uint64_t* cached_bits = nullptr;  // one bit per node, rebuilt from the device map by every weighted call
   int64_t cached_bits_words = 0;
   int32_t* fifo_rank = nullptr;   // FIFO update: per id, rank among its tile's misses (grown on demand)
@@ -126,6 +128,12 @@ uint32_t cap_for(uint32_t lambda) { return ((2 * lambda + 63) / 64) * 64; }
 // them are cached, so it keeps half as many again: with three quarters of the neighbours cached,
 // a node then has too few about once in 10^6 instead of once in 10^4 (each one left over costs the
 // second launch a whole node's latency).
+// A weighted call whose first launches leave more than one node in kFullOnlyShare to the second
+// switches the next kFullOnlyCalls weighted calls of its context to a single full launch per
+// hop; after them the two-launch plan is tried again.  At that share the two plans cost about
+// the same (the first launch costs about three quarters of a full one on the same nodes).
+constexpr int64_t kFullOnlyShare = 5;
+constexpr int kFullOnlyCalls = 16;
 uint32_t lambda_for_first_list(int32_t m) { return (uint32_t)(m + 6.0 * std::sqrt((double)m) + 12.0); }
 constexpr int64_t kMaxRoleWaves = 8192;  // wavefronts serving one role of k_sample
 constexpr int64_t kMaxHubBlocks = 2048;
@@ -174,7 +182,7 @@ size_t sample_block_lds_bytes(uint32_t lds_per_wave, uint32_t cap, int n_waves) 
 }
 
 // Scratch of the FIFO update for callers that cannot allocate: one int32 per id (its rank among
-// the misses of its tile) and two per tile of 1024 ids (tile sums, tile offsets), 4 MiB + 8 KiB.
+// the misses of its tile) and two per tile of 1024 ids (tile sums, tile offsets), 16 MiB + 32 KiB.
 // Every GPU the library runs on holds its own copy at its own address until the process ends;
 // host code uses the address that hipGetSymbolAddress returns for the current device, never the
 // array's name.
@@ -290,6 +298,12 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
   IdxT* gid = (IdxT*)ctx->gid;
   DevState* ds = ctx->d_state;
   const bool weighted = cache_map != nullptr && bias_q16 > 65536u;
+  // A weighted hop normally runs two launches (see below).  While the first of them keeps leaving
+  // a large share of the nodes to the second (few neighbours cached), its work is mostly wasted:
+  // the hop then runs the second kind alone over every node.  The blocks come out the same.
+  const bool full_only = weighted && ctx->full_only_left > 0;
+  ctx->last_weighted = weighted;
+  ctx->last_full_only = full_only;
   const int validate = (ctx->flags & A3_VALIDATE) ? 1 : 0;
 
   // launch bounds per hop for this call: never more than the arena holds, never more than the
@@ -366,10 +380,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       for (int b = 0; b < a3::kNumBins; ++b) sa.bins[b] = ctx->bins[b];
       sa.num_nodes = num_nodes;
       sa.cap_edges = ctx->cap_edges[h];
-      sa.wide_count = 3;
-      sa.hub_count = 4;
-      sa.deferred[0] = ctx->bins[a3::kNumBins];
-      sa.deferred[1] = ctx->bins[a3::kNumBins + 1];
+      sa.left_only = 0;
       sa.hop = h;
       sa.fanout = f;
       sa.lambda = weighted ? lambda_for_first_list(f) : lambda_for(f);
@@ -384,7 +395,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       // The first launch, for every node: all weights equal, or (weighted) the path that decides a
       // wide node from its first candidate list alone and leaves the others to the second launch.
       // Either way a wavefront needs the uniform buffers only.
-      {
+      if (!full_only) {
         sa.capb = 0;
         sa.xcap = 0;
         sa.lds_per_wave = sample_lds_entries(sa.cap, f, false, 0);
@@ -418,17 +429,30 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
         sa.lds_per_wave = sample_lds_entries(sa.cap, f, true, sa.capb);
         int n_waves = kSampleWaves;
         while (n_waves > 1 && sample_block_lds_bytes(sa.lds_per_wave, sa.cap, n_waves) > kLdsLimit) n_waves >>= 1;
-        const int64_t max_blocks = std::max<int64_t>(kMaxRoleWaves / n_waves / 4, 1);
-        sa.bins[3] = sa.deferred[0];
-        sa.bins[4] = sa.deferred[1];
-        sa.wide_count = a3::kNumBins;
-        sa.hub_count = a3::kNumBins + 1;
-        sa.role_blocks[0] = sa.role_blocks[1] = sa.role_blocks[2] = 0;
-        sa.role_blocks[3] = (uint32_t)std::min<int64_t>((nb + n_waves - 1) / n_waves, max_blocks);
-        sa.role_blocks[4] = (uint32_t)std::min<int64_t>(nb, kMaxHubBlocks / 4);
+        const int64_t threads = 64 * n_waves;
+        if (full_only) {
+          // the only launch of the hop: every node, from the frontier's own lists
+          const int64_t max_blocks = std::max<int64_t>(kMaxRoleWaves / n_waves, 1);
+          sa.role_blocks[0] = (uint32_t)std::min<int64_t>((nb * 4 + threads - 1) / threads, max_blocks);
+          sa.role_blocks[1] = (uint32_t)std::min<int64_t>((nb * 8 + threads - 1) / threads, max_blocks);
+          sa.role_blocks[2] = (uint32_t)std::min<int64_t>((nb * 16 + threads - 1) / threads, max_blocks);
+          sa.role_blocks[3] = (uint32_t)std::min<int64_t>((nb + n_waves - 1) / n_waves, max_blocks);
+          sa.role_blocks[4] = (uint32_t)std::min<int64_t>(nb, kMaxHubBlocks);
+        } else {
+          // A wavefront (a workgroup, for the hubs) looks at the marks of 64 records per round,
+          // the records a whole launch apart: the marked ones spread over one chip's worth of
+          // wavefronts however few they are.
+          const int64_t max_blocks = std::max<int64_t>(kMaxRoleWaves / n_waves / 2, 1);
+          sa.left_only = 1;
+          sa.role_blocks[0] = sa.role_blocks[1] = sa.role_blocks[2] = 0;
+          sa.role_blocks[3] = (uint32_t)std::min<int64_t>((nb + n_waves - 1) / n_waves, max_blocks);
+          sa.role_blocks[4] = (uint32_t)std::min<int64_t>(nb, kMaxHubBlocks / 4);
+        }
+        const unsigned grid = sa.role_blocks[0] + sa.role_blocks[1] + sa.role_blocks[2] +
+                              sa.role_blocks[3] + sa.role_blocks[4];
         const size_t lds_bytes = sample_block_lds_bytes(sa.lds_per_wave, sa.cap, n_waves);
-        hipLaunchKernelGGL((a3::k_sample<IdxT, a3::kWeightedFull>), dim3(sa.role_blocks[3] + sa.role_blocks[4]),
-                           dim3((unsigned)(64 * n_waves)), lds_bytes, st, sa);
+        hipLaunchKernelGGL((a3::k_sample<IdxT, a3::kWeightedFull>), dim3(grid), dim3((unsigned)threads),
+                           lds_bytes, st, sa);
       }
     }
     // a5: first occurrences -> numbering of new nodes -> local ids
@@ -494,6 +518,17 @@ int sample_finish(a3_ctx* ctx, a3_blocks* out) {
                 "graph, or an internal error; guard bits " + std::to_string(hs.error) +
                     "); outputs are invalid");
   const int num_hops = ctx->last_hops;
+  if (ctx->last_weighted) {
+    // the launch plan of the next weighted calls, from how this one went
+    int64_t nodes = 0;
+    for (int h = 0; h < num_hops; ++h) nodes += hs.n_dst[h];
+    const int64_t left_over = (int64_t)hs.n_deferred[0] + hs.n_deferred[1];
+    if (ctx->last_full_only) {
+      if (ctx->full_only_left > 0) --ctx->full_only_left;
+    } else if (left_over * kFullOnlyShare > nodes) {
+      ctx->full_only_left = kFullOnlyCalls;
+    }
+  }
   std::memset(out, 0, sizeof(*out));
   out->num_hops = num_hops;
   for (int h = 0; h < num_hops; ++h) {
@@ -781,7 +816,7 @@ extern "C" int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t
   chk(dev_alloc(ctx, &ctx->tile_sums2, ctx->cap_tiles));
   chk(dev_alloc(ctx, &ctx->tile_offs, ctx->cap_tiles));
   chk(dev_alloc(ctx, &ctx->tile_offs2, ctx->cap_tiles));
-  for (int b = 0; b < a3::kNumBins + 2; ++b) chk(dev_alloc(ctx, &ctx->bins[b], ctx->cap_dst[max_hops - 1]));
+  for (int b = 0; b < a3::kNumBins; ++b) chk(dev_alloc(ctx, &ctx->bins[b], ctx->cap_dst[max_hops - 1]));
   chk(dev_alloc(ctx, &ctx->d_state, 1));
   chk(dev_alloc(ctx, &ctx->block_seen, kCachedBitsBlocks));
   if (rc == A3_OK) {
@@ -917,7 +952,7 @@ extern "C" int a3_sample_blocks_end(a3_ctx* ctx, a3_blocks* out) {
   return sample_finish(ctx, out);
 }
 
-extern "C" int a3_sample_stats(a3_ctx* ctx, int64_t stats[4]) {
+extern "C" int a3_sample_stats(a3_ctx* ctx, int64_t stats[5]) {
   if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_sample_stats: ctx is null");
   if (!stats) return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_stats: stats is null");
   if (ctx->flags & A3_HOST_ONLY)
@@ -929,6 +964,7 @@ extern "C" int a3_sample_stats(a3_ctx* ctx, int64_t stats[4]) {
   stats[1] = hs.n_deferred[0];
   stats[2] = hs.n_deferred[1];
   stats[3] = hs.n_radix;
+  stats[4] = !ctx->last_weighted ? 0 : ctx->last_full_only ? 2 : 1;
   return A3_OK;
 }
 

@@ -285,6 +285,39 @@ def test_relabel_map_ranges_down_to_the_bottom_of_int32_and_refills(flags):
     ctx.close()
 
 
+def test_weighted_launch_plan_follows_the_cache_and_keeps_the_blocks():
+    """With few neighbours cached the first launch of a weighted hop decides almost no wide node;
+    the context then runs its next 16 weighted calls with the single full launch per hop, tries
+    the two-launch plan again, and stays with it once the cache holds enough.  The blocks equal
+    the oracle's under either plan; calls without weights do not count."""
+    w, g, d_ip, d_ix = _graph("mini_social")
+    sparse = degree_ranked_cache(g, None, 0.01).cache_map.numpy()
+    dense = degree_ranked_cache(g, None, 0.6).cache_map.numpy()
+    ctx = a3.Context(64, [25, 10])
+    plans = []
+    for b in range(19):
+        seeds = seed_batch(w.num_nodes, 64 - b, 3, b)
+        _compare(ctx, w, g, d_ip, d_ix, seeds, [25, 10], sparse, 4.0, b, "launch plan")
+        st = ctx.sample_stats()
+        plans.append(st["launch_plan"])
+        if st["launch_plan"] == 2:
+            assert st["deferred_wide_nodes"] == 0 and st["deferred_hubs"] == 0
+        if b == 5:
+            _compare(ctx, w, g, d_ip, d_ix, seeds, [25, 10], None, 1.0, b, "launch plan, no weights")
+            assert ctx.sample_stats()["launch_plan"] == 0
+    assert plans == [1] + [2] * 16 + [1, 2]
+    for b in range(19, 19 + 18):
+        seeds = seed_batch(w.num_nodes, 64, 3, b)
+        if b in (19, 35, 36):
+            _compare(ctx, w, g, d_ip, d_ix, seeds, [25, 10], dense, 4.0, b, "launch plan, dense cache")
+        else:
+            d_cm = torch.from_numpy(dense).to(DEV)
+            ctx.sample_blocks(d_ip, d_ix, torch.from_numpy(seeds).to(DEV), [25, 10], d_cm, 4 * Q, b)
+        plans.append(ctx.sample_stats()["launch_plan"])
+    assert plans[19:] == [2] * 15 + [1, 1, 1]
+    ctx.close()
+
+
 def test_isolated_nodes_and_no_eids():
     indptr = torch.tensor([0, 0, 1, 2, 2], dtype=torch.int64)
     indices = torch.tensor([2, 1], dtype=torch.int64)
