@@ -140,7 +140,8 @@ def measure(args, name, headline, legs):
         assert rows <= cap_rows
         if timed:
             for key, val in ctx.sample_stats().items():
-                slow_paths[key] = max(val, slow_paths.get(key, 0)) if key == "weight_classes" else slow_paths.get(key, 0) + val
+                keep_max = key in ("weight_classes", "launch_plan")
+                slow_paths[key] = max(val, slow_paths.get(key, 0)) if keep_max else slow_paths.get(key, 0) + val
             n_edges += sum(blocks.n_edges)
             n_in += rows
             last_ids = blocks.input_nodes

@@ -556,8 +556,10 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
   constexpr bool kFast = kMode == kWeightedFast;
   const bool two_classes = kWeighted && both_classes;
   const bool want_b = !kFast && two_classes && a.capb > 0;
-  const uint32_t X1 = want_b ? second_list_floor(keep, a.bias_q16) : 0u;
-  if (!a.force_radix && !prefiltered) {
+  uint32_t X1 = want_b ? second_list_floor(keep, a.bias_q16) : 0u;
+  bool scan = !prefiltered;
+  for (int attempt = 0;; ++attempt) {
+  if (!a.force_radix && scan) {
     // One step: 64 quads = 256 slots.  Only the last step of a row can hold slots past its end,
     // so the steps before it run without the range test (tail = false): a lane's condition is
     // then one comparison, which is also its ballot.
@@ -614,6 +616,22 @@ __device__ __forceinline__ void sample_node_wave(const SampleArgs<IdxT>& a, cons
     for (; q0 < whole_steps_end; q0 += kWave) step(q0, std::false_type{});
     for (; q0 < n_quads; q0 += kWave) step(q0, std::true_type{});
     wave_sync();
+  }
+  if (attempt == 1 || a.force_radix || cnt >= m) break;
+  // Fewer than m draws cleared the threshold (about one node in 10^5).  The exhaustive path
+  // would scan the row 34 times; one more scan by this wavefront, with a threshold that keeps
+  // a number midway between m and the buffer's size, settles all but one in 10^10.
+  const uint32_t more = (m + a.cap) >> 1;
+  keep = 4294967296.0f;
+  X0 = 0;
+  if (deg > more) {
+    keep = __fdividef((float)more, (float)deg) * 4294967296.0f;
+    X0 = 0u - (uint32_t)keep;
+  }
+  X1 = want_b ? second_list_floor(keep, a.bias_q16) : 0u;
+  cnt = 0;
+  cnt_b = 0;
+  scan = true;
   }
   // the first list alone decides most nodes (see weighted_from_first_list)
   if (two_classes && !a.force_radix && cnt >= m && cnt <= a.cap && cnt <= 2u * kWave && m <= (uint32_t)kWave) {
@@ -1020,7 +1038,7 @@ constexpr int kSampleMaxThreads = 256;
 // next role_blocks[3] the wide nodes (one wavefront each), then role_blocks[2], [1], [0] the
 // small-degree bins with lane groups of 16, 8, 4.
 template <typename IdxT, int kMode>
-__global__ __launch_bounds__(kSampleMaxThreads) void k_sample(const SampleArgs<IdxT> a) {
+__global__ __launch_bounds__(kSampleMaxThreads) __attribute__((amdgpu_waves_per_eu(4))) void k_sample(const SampleArgs<IdxT> a) {
   extern __shared__ uint64_t lds[];
   __shared__ int32_t fused_offs[kFuseTiles];
   __shared__ uint32_t fused_total;
