@@ -383,8 +383,10 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       sa.left_only = 0;
       sa.hop = h;
       sa.fanout = f;
+      const bool few_draws = (ctx->flags & A3_TEST_FEW_DRAWS) != 0;
       sa.lambda = weighted ? lambda_for_first_list(f) : lambda_for(f);
       sa.cap = cap_for(sa.lambda);
+      if (few_draws) sa.lambda = std::max<uint32_t>(1u, (uint32_t)f / 2u);
       sa.bias_q16 = bias_q16;
       sa.inv_bias = 1.0 / (double)bias_q16;
       sa.seed_lo = (uint32_t)rng_seed;
@@ -424,6 +426,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       if (weighted) {
         sa.lambda = lambda_for(f);
         sa.cap = cap_for(sa.lambda);
+        if (few_draws) sa.lambda = std::max<uint32_t>(1u, (uint32_t)f / 2u);
         sa.capb = second_list_cap(f, bias_q16);
         sa.xcap = challenger_cap(f, sa.capb);
         sa.lds_per_wave = sample_lds_entries(sa.cap, f, true, sa.capb);

@@ -64,17 +64,43 @@ def test_weighted_selection_matches_oracle(gamma):
     ctx.close()
 
 
+def _hub_graph():
+    """wide rows and hubs; seeds: the largest rows, middling ones and the smallest"""
+    if "hubs" not in _graphs:
+        g = make_graph(20_000, 700.0, 40, 12_000, 2.1, True, 5, torch.int32)
+        deg = (g.indptr[1:] - g.indptr[:-1]).numpy()
+        assert deg.max() > 4096 and (deg > 64).sum() > 1000
+        order = np.argsort(-deg, kind="stable")
+        seeds = np.concatenate([order[:24], order[2000:2040], order[-16:]]).astype(np.int32)
+        _graphs["hubs"] = (get_config("mini_social"), g, g.indptr.to(DEV), g.indices.to(DEV), seeds)
+    return _graphs["hubs"]
+
+
+def test_too_few_draws_above_the_threshold_take_one_more_scan():
+    """About one node in 10^5 keeps fewer candidates than its fanout and scans its row once more
+    with a lower threshold.  With the testing flag the first threshold keeps about fanout / 2, so
+    nearly every wide node and hub goes that way (and, weighted, through the second launch)."""
+    w, g, d_ip, d_ix, seeds = _hub_graph()
+    ctx = a3.Context(len(seeds), [15, 3], flags=a3.A3_TEST_FEW_DRAWS)
+    for frac, gamma, fan in [(0.5, 1.0, [15, 3]), (0.5, 4.0, [15, 3]), (0.1, 2.0, [10, 3]), (0.9, 8.0, [5]),
+                             (1.0, 4.0, [15, 2]), (0.3, 64.0, [15])]:
+        cm = degree_ranked_cache(g, None, frac).cache_map.numpy()
+        _compare(ctx, w, g, d_ip, d_ix, seeds, fan, cm, gamma, 31, f"few draws frac={frac}")
+        assert ctx.sample_stats()["exhaustive_nodes"] <= 2
+    ctx.close()
+    w, g, d_ip, d_ix = _graph("mini_social")
+    ctx = a3.Context(128, [25, 10], flags=a3.A3_TEST_FEW_DRAWS)
+    cm = degree_ranked_cache(g, None, 0.3).cache_map.numpy()
+    for b, gamma in enumerate([1.0, 1.5, 4.0]):
+        _compare(ctx, w, g, d_ip, d_ix, seed_batch(w.num_nodes, 128, 1, b), [25, 10], cm, gamma, b, "few draws")
+    ctx.close()
+
+
 def test_weighted_candidate_lists_of_every_size():
     """Wide rows and hubs with many cached neighbours: the two candidate lists of the weighted
     path hold from a few to several hundred slots (every register count of the selection, and
     past its limit, where the row is scanned a second time instead)."""
-    g = make_graph(20_000, 700.0, 40, 12_000, 2.1, True, 5, torch.int32)
-    deg = (g.indptr[1:] - g.indptr[:-1]).numpy()
-    assert deg.max() > 4096 and (deg > 64).sum() > 1000
-    d_ip, d_ix = g.indptr.to(DEV), g.indices.to(DEV)
-    w = get_config("mini_social")
-    order = np.argsort(-deg, kind="stable")
-    seeds = np.concatenate([order[:24], order[2000:2040], order[-16:]]).astype(np.int32)
+    w, g, d_ip, d_ix, seeds = _hub_graph()
     ctx = a3.Context(len(seeds), [15, 3])
     for frac in [0.1, 0.5, 0.9]:
         cm = degree_ranked_cache(g, None, frac).cache_map.numpy()
