@@ -99,47 +99,76 @@ __global__ __launch_bounds__(kTileThreads) void k_scan_tiles(const int32_t* tile
 
 // When there are few tiles (kFuseTiles at most) the consumers of a tile scan do it themselves
 // instead of waiting for k_scan_tiles: every workgroup's first wavefront reads the tile sums
-// (tile_sums_load) and leaves their exclusive prefix in LDS, 16 consecutive tiles per lane
+// (tile_sums_load) and leaves their exclusive prefix in LDS
 // (tile_prefix_from, which returns the grand total, valid in every thread after its barrier).
 constexpr int kFuseTiles = 1024;
 
 // The tile sums of the first wavefront's lanes, read before the number of tiles is known (so that
-// the read does not wait for it): all kFuseTiles entries that the array holds (cap_tiles); entries
+// the read does not wait for it): all entries up to the launch's bound (cap_tiles); entries
 // past the real count are stale and are dropped by tile_prefix_from.
 struct TileSums {
   uint32_t v[kFuseTiles / kWave];
 };
 
-__device__ __forceinline__ TileSums tile_sums_load(const int32_t* tile_sums, int64_t cap_tiles) {
-  TileSums s;
+// cap_tiles: the launch's bound on the number of tiles.  A lane of the first wavefront holds 1, 4
+// or 16 consecutive tiles, whichever covers the bound; the other wavefronts skip all of it (a
+// scalar branch).
+__device__ __forceinline__ bool first_wavefront() {
+  return __builtin_amdgcn_readfirstlane((int32_t)threadIdx.x) < kWave;
+}
+
+template <int P>
+__device__ __forceinline__ void tile_sums_load_p(const int32_t* tile_sums, int64_t cap_tiles, TileSums& s) {
 #pragma unroll
-  for (int k = 0; k < kFuseTiles / kWave; ++k) {
-    const int64_t t = (int64_t)(threadIdx.x & (kWave - 1)) * (kFuseTiles / kWave) + k;
-    s.v[k] = (threadIdx.x < (unsigned)kWave && t < cap_tiles) ? (uint32_t)tile_sums[t] : 0u;
+  for (int k = 0; k < P; ++k) {
+    const int64_t t = (int64_t)threadIdx.x * P + k;
+    s.v[k] = t < cap_tiles ? (uint32_t)tile_sums[t] : 0u;
   }
+}
+
+__device__ __forceinline__ TileSums tile_sums_load(const int32_t* tile_sums, int64_t cap_tiles) {
+  TileSums s = {};
+  if (!first_wavefront()) return s;
+  if (cap_tiles <= kWave)
+    tile_sums_load_p<1>(tile_sums, cap_tiles, s);
+  else if (cap_tiles <= 4 * kWave)
+    tile_sums_load_p<4>(tile_sums, cap_tiles, s);
+  else
+    tile_sums_load_p<kFuseTiles / kWave>(tile_sums, cap_tiles, s);
   return s;
 }
 
-__device__ __forceinline__ uint32_t tile_prefix_from(const TileSums& loaded, int64_t n_tiles, int32_t* lds_offs,
-                                                     uint32_t* lds_total) {
-  if (threadIdx.x < (unsigned)kWave) {
-    const uint32_t lane = threadIdx.x;
-    uint32_t v[kFuseTiles / kWave];
-    uint32_t sum = 0;
+template <int P>
+__device__ __forceinline__ void tile_prefix_p(const TileSums& loaded, int64_t n_tiles, int32_t* lds_offs,
+                                              uint32_t* lds_total) {
+  const uint32_t lane = threadIdx.x;
+  uint32_t v[P];
+  uint32_t sum = 0;
 #pragma unroll
-    for (int k = 0; k < kFuseTiles / kWave; ++k) {
-      const int64_t t = (int64_t)lane * (kFuseTiles / kWave) + k;
-      v[k] = t < n_tiles ? loaded.v[k] : 0u;
-      sum += v[k];
-    }
-    uint32_t run = wave_excl_scan_u32(sum);
+  for (int k = 0; k < P; ++k) {
+    const int64_t t = (int64_t)lane * P + k;
+    v[k] = t < n_tiles ? loaded.v[k] : 0u;
+    sum += v[k];
+  }
+  uint32_t run = wave_excl_scan_u32(sum);
 #pragma unroll
-    for (int k = 0; k < kFuseTiles / kWave; ++k) {
-      const int64_t t = (int64_t)lane * (kFuseTiles / kWave) + k;
-      if (t < n_tiles) lds_offs[t] = (int32_t)run;
-      run += v[k];
-    }
-    if (lane == kWave - 1) *lds_total = run;
+  for (int k = 0; k < P; ++k) {
+    const int64_t t = (int64_t)lane * P + k;
+    if (t < n_tiles) lds_offs[t] = (int32_t)run;
+    run += v[k];
+  }
+  if (lane == kWave - 1) *lds_total = run;
+}
+
+__device__ __forceinline__ uint32_t tile_prefix_from(const TileSums& loaded, int64_t cap_tiles, int64_t n_tiles,
+                                                     int32_t* lds_offs, uint32_t* lds_total) {
+  if (first_wavefront()) {
+    if (cap_tiles <= kWave)
+      tile_prefix_p<1>(loaded, n_tiles, lds_offs, lds_total);
+    else if (cap_tiles <= 4 * kWave)
+      tile_prefix_p<4>(loaded, n_tiles, lds_offs, lds_total);
+    else
+      tile_prefix_p<kFuseTiles / kWave>(loaded, n_tiles, lds_offs, lds_total);
   }
   __syncthreads();
   return *lds_total;

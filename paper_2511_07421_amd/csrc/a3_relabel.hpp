@@ -83,7 +83,7 @@ struct RelabelArgs {
   const int32_t* local_rank;
   const int32_t* tile_offs;  // scanned tile offsets, or null: scan tile_sums here
   const int32_t* tile_sums;
-  int64_t cap_tiles;         // entries in tile_sums
+  int64_t cap_tiles;         // the launch's bound on the tiles in use (at most the entries of tile_sums)
   DevState* st;
   int32_t hop;
   int32_t last_hop;          // this hop ends the call
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(kTileThreads) void k_relabel(const RelabelArgs<IdxT
   }
   const int32_t* tile_offs = a.tile_offs;
   if (fuse) {
-    const uint32_t total = tile_prefix_from(sums, (n + kTile - 1) >> kTileShift, fused_offs, &fused_total);
+    const uint32_t total = tile_prefix_from(sums, a.cap_tiles, (n + kTile - 1) >> kTileShift, fused_offs, &fused_total);
     tile_offs = fused_offs;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
       const int32_t n_src = n_dst + (int32_t)total;

@@ -15,7 +15,7 @@ struct SampleArgs {
   const IdxT* S;             // frontier: local id -> global id
   const int32_t* tile_offs;  // scanned tile offsets in global memory, or null: scan tile_sums here
   const int32_t* tile_sums;
-  int64_t cap_tiles;         // entries in tile_sums
+  int64_t cap_tiles;         // the launch's bound on the tiles in use (at most the entries of tile_sums)
   int32_t* blk_indptr;       // out: edge offsets of this hop
   IdxT* gid;                 // out: global id of each sampled neighbour
   int64_t* eids;             // out: CSR position of each sampled edge (may be null)
@@ -1097,7 +1097,7 @@ __global__ __launch_bounds__(kSampleMaxThreads) __attribute__((amdgpu_waves_per_
   const int32_t n_dst = a.st->n_dst[a.hop];
   const bool both_classes = kMode != kUniform && a.st->class_mix == 3;  // read once, not per node
   if (tile_offs == nullptr) {  // few tiles: scan the tile sums here, publish the hop's edge count
-    const uint32_t total = tile_prefix_from(sums, ((int64_t)n_dst + kTile - 1) >> kTileShift,
+    const uint32_t total = tile_prefix_from(sums, a.cap_tiles, ((int64_t)n_dst + kTile - 1) >> kTileShift,
                                             fused_offs, &fused_total);
     tile_offs = fused_offs;
     if (blockIdx.x == 0 && threadIdx.x == 0) {

@@ -370,7 +370,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
       sa.S = S;
       sa.tile_offs = fuse_dst ? nullptr : ctx->tile_offs;
       sa.tile_sums = ctx->tile_sums;
-      sa.cap_tiles = ctx->cap_tiles;
+      sa.cap_tiles = std::min<int64_t>(ctx->cap_tiles, dst_tiles);
       sa.blk_indptr = ctx->blk_indptr[h];
       sa.gid = gid;
       sa.eids = ctx->blk_eids[h];
@@ -471,7 +471,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
     ra.local_rank = ctx->local_rank;
     ra.tile_offs = fuse_edges ? (const int32_t*)nullptr : ctx->tile_offs2;
     ra.tile_sums = ctx->tile_sums2;
-    ra.cap_tiles = ctx->cap_tiles;
+    ra.cap_tiles = std::min<int64_t>(ctx->cap_tiles, edge_tiles);
     ra.st = ds;
     ra.hop = h;
     ra.last_hop = h == num_hops - 1 ? 1 : 0;  // nothing follows: the relabel map needs no local ids
