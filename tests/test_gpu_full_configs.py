@@ -3,8 +3,8 @@ graphs are generated on the GPU, mini-batches go through the HIP library and thr
 oracle, and every output array is compared (bit-exact / byte-exact).  Covers the dense social
 graph, the co-purchase graph with its batch x cache x bias-rate sweep at the corner cells, the
 citation-scale graph with 8-byte ids (all three hops against the full oracle), one full-size
-mini-batch through a stream pipeline and the block mean, and the multi-threaded host sampler
-in the vector form the GPU machine's CPU picks."""
+mini-batch through a stream pipeline and the block mean, the cache policies on the co-purchase
+graph, and the multi-threaded host sampler in the vector form the GPU machine's CPU picks."""
 import time
 
 import numpy as np
@@ -195,6 +195,75 @@ def test_copurchase_sweep_corner_cells(progress, batch, frac, gamma):
     instead of being scanned by their consumers) with the smallest cache and the largest bias rate,
     the smallest batch, and a full cache (one weight class: the bias rate must not matter)"""
     _run(progress, "copurchase", [(batch, frac, gamma, 1)], check_rows=300_000)
+
+
+def test_copurchase_full_size_fifo_cache_and_access_counts(progress):
+    """Cache policies at full size: a FIFO ring of 2.5 % of the nodes that starts empty (every
+    mini-batch brings more misses than it has slots) and three mini-batches of locality-aware
+    sampling that read it: the first meets one weight class, the second finds few neighbours
+    cached and leaves half of its wide nodes to the second sampling launch, so the third runs the
+    single full launch per hop.  The update goes through both entry points; the access counts of
+    the same mini-batches and the ranked fill are compared too.  Blocks, rows, map, owners, ring
+    head and counts equal the oracle's after every step."""
+    world = _world("copurchase", progress)
+    w, g = world.w, world.g
+    N, batch = w.num_nodes, 1024
+    n_slots = N // 40
+    full_h = world.full.cpu()
+    host_all = full_h.pin_memory()
+    full_np = full_h.numpy()
+    ctx = a3.Context(batch, w.fanouts)
+    cm = -torch.arange(N, dtype=torch.int32, device=DEV) - 1
+    owner = torch.full((n_slots,), -1, dtype=torch.int32, device=DEV)
+    state = torch.zeros(4, dtype=torch.int32, device=DEV)
+    cache = torch.zeros((n_slots, w.feat_dim), dtype=w.feat_dtype, device=DEV)
+    rows = torch.zeros((_cap_rows(w, batch), w.feat_dim), dtype=w.feat_dtype, device=DEV)
+    counts = torch.zeros(N, dtype=torch.int32, device=DEV)
+    o_cm = (-np.arange(N) - 1).astype(np.int32)
+    o_owner = np.full(n_slots, -1, dtype=np.int32)
+    o_head = np.zeros(1, dtype=np.int32)
+    o_cache = np.zeros((n_slots, w.feat_dim), dtype=np.float32)
+    o_counts = np.zeros(N, dtype=np.uint32)
+    plans = []
+    for b in range(3):
+        seeds = seed_batch(N, batch, 0, 40 + b, dtype=np.int32)
+        ctx.sample_blocks_begin(g.indptr, g.indices, torch.from_numpy(seeds).to(DEV), w.fanouts, cm, 4 * Q, b)
+        ctx.gather_input_features(cache, host_all, cm, rows)
+        ctx.cache_count_accesses(counts)
+        ctx.cache_fifo_update(cm, owner, state, cache, rows, static_scratch=(b == 1))
+        blk = ctx.sample_blocks_end()
+        st = ctx.sample_stats()
+        plans.append((st["launch_plan"], st["deferred_wide_nodes"] + st["deferred_hubs"]))
+        progress(f"[case] copurchase fifo step {b}: edges={blk.n_edges} n_src={blk.n_src} stats={st}; oracle running")
+        ob = oracle.sample_blocks(world.ip_h, world.ix_h, seeds, w.fanouts, o_cm, 4 * Q, b)
+        blocks_equal(blk.to_host(), ob)
+        ids = ob.input_nodes.astype(np.int32)
+        # the oracle reads host arrays: hand it the rows it will touch, renumbered (the cache's rows
+        # first, then the host store's)
+        c = o_cm[ids]
+        dev_rows, host_rows = np.unique(c[c >= 0]), np.unique(-c[c < 0] - 1)
+        cm_small = np.where(c >= 0, np.searchsorted(dev_rows, np.maximum(c, 0)),
+                            -np.searchsorted(host_rows, np.maximum(-c - 1, 0)) - 1).astype(np.int32)
+        o_rows = oracle.gather_features(o_cache[dev_rows] if dev_rows.size else None,
+                                        full_np[host_rows] if host_rows.size else None, cm_small,
+                                        np.arange(ids.shape[0], dtype=np.int64))
+        oracle.count_accesses(ids, o_counts)
+        misses = oracle.cache_fifo_update(o_cm, o_owner, o_head, o_cache, ids, o_rows)
+        torch.cuda.synchronize()
+        assert rows[: blk.n_src[-1]].cpu().numpy().tobytes() == o_rows.tobytes()
+        sv = state.cpu().numpy()
+        assert sv[0] == o_head[0] and sv[1] == misses
+        assert np.array_equal(cm.cpu().numpy(), o_cm)
+        assert np.array_equal(owner.cpu().numpy(), o_owner)
+        filled = o_owner >= 0
+        assert np.array_equal(cache.cpu().numpy()[filled], o_cache[filled])
+    assert plans[0] == (1, 0) and plans[1][0] == 1 and plans[1][1] > 10_000 and plans[2] == (2, 0)
+    assert np.array_equal(counts.cpu().numpy().view(np.uint32), o_counts)
+    got_cm, got_order = ctx.cache_rank(counts, n_slots)
+    want_cm, want_order = oracle.rank_cache(o_counts, n_slots)
+    assert np.array_equal(got_cm.cpu().numpy(), want_cm)
+    assert np.array_equal(got_order.cpu().numpy(), want_order)
+    ctx.close()
 
 
 def test_citation_full_size(progress):
