@@ -75,6 +75,11 @@ int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t max_seeds,
 int a3_destroy(a3_ctx* ctx);
 /* hipStream_t for subsequent calls; pending work on the old stream is waited for. */
 int a3_set_stream(a3_ctx* ctx, void* hip_stream);
+/* Optional: allocates now what depends on the graph's size (the relabel map, 4 bytes per node, and
+ * the bitmap of cached nodes, 1 bit per node; Alg. 1 line 7 and Sec. III-A), so that no later
+ * sampling call on a graph of at most num_nodes nodes allocates device memory; without it the
+ * first such call does.  A3_ERR_INVALID_ARG while a begun sampling call is pending. */
+int a3_reserve(a3_ctx* ctx, int64_t num_nodes);
 /* Tuning of the feature retrieve (Alg. 1 line 10) where both stores are given: n workgroups of
  * each launch are set aside for the rows in host memory and the others copy the device rows.
  * n = 0, a context's default: none are, every workgroup copies rows of both stores as they come,
@@ -337,6 +342,8 @@ typedef struct a3_pipeline a3_pipeline;
 int a3_pipeline_create(a3_pipeline** out, int hip_device, int mode, int n_workers, int64_t max_seeds,
                        int32_t max_hops, const int32_t* max_fanouts, uint32_t flags);
 int a3_pipeline_destroy(a3_pipeline* p);
+/* a3_reserve on every worker's context: no mini-batch of the pipeline allocates afterwards */
+int a3_pipeline_reserve(a3_pipeline* p, int64_t num_nodes);
 const char* a3_pipeline_last_error(const a3_pipeline* p);
 /* Workers actually created, and device bytes their arenas hold (relabel maps included); the
  * caller's output buffers come on top (Eq. 3, Eq. 5). */

@@ -63,6 +63,10 @@ def lib():
         L.a3_validate_cache_map.restype = C.c_int
         L.a3_set_gather_host_workgroups.argtypes = [C.c_void_p, C.c_int32]
         L.a3_set_gather_host_workgroups.restype = C.c_int
+        L.a3_reserve.argtypes = [C.c_void_p, C.c_int64]
+        L.a3_reserve.restype = C.c_int
+        L.a3_pipeline_reserve.argtypes = [C.c_void_p, C.c_int64]
+        L.a3_pipeline_reserve.restype = C.c_int
         L.a3_last_error.argtypes = [C.c_void_p]
         L.a3_last_error.restype = C.c_char_p
         L.a3_sample_blocks.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,
@@ -276,6 +280,10 @@ class Context:
 
     def set_gather_host_workgroups(self, n: int):
         self._check(lib().a3_set_gather_host_workgroups(self._h, n))
+
+    def reserve(self, num_nodes: int):
+        """allocate now what depends on the graph's size, so that no later sampling call does"""
+        self._check(lib().a3_reserve(self._h, num_nodes))
 
     def validate_graph(self, indptr: torch.Tensor, indices: torch.Tensor):
         """raises A3Error (A3_ERR_INPUT) unless (indptr, indices) is a CSR with sorted, repeat-free rows"""
@@ -493,6 +501,10 @@ class Pipeline:
     def _check(self, rc: int):
         if rc != A3_OK:
             raise A3Error(rc, (lib().a3_pipeline_last_error(self._h) or b"").decode())
+
+    def reserve(self, num_nodes: int):
+        """Context.reserve on every worker: no mini-batch of the pipeline allocates afterwards"""
+        self._check(lib().a3_pipeline_reserve(self._h, num_nodes))
 
     @property
     def workspace_bytes(self) -> int:

@@ -232,29 +232,36 @@ void free_all(a3_ctx* ctx) {
 // previous call's, so that nothing has to be cleaned between calls (see a3_relabel.hpp).  The map
 // is refilled with the largest value when it is first made or enlarged, and when the ranges have
 // reached the bottom of int32.
-int ensure_node_map(a3_ctx* ctx, int64_t num_nodes) {
-  bool refill = false;
-  if (num_nodes > ctx->node_map_cap) {
-    if (ctx->node_map) {
-      A3_HIP(ctx, hipStreamSynchronize(ctx->stream));
-      A3_HIP(ctx, hipFree(ctx->node_map));
-      ctx->node_map = nullptr;
-      ctx->node_map_cap = 0;
-    }
-    void* q = nullptr;
-    A3_HIP(ctx, hipMalloc(&q, (size_t)std::max<int64_t>(num_nodes, 1) * sizeof(int32_t)));
-    ctx->node_map = (int32_t*)q;
-    ctx->node_map_cap = num_nodes;
-    refill = true;
-  }
+int fill_node_map(a3_ctx* ctx) {
   const int64_t span = std::max<int64_t>(ctx->cap_dst[ctx->max_hops], 1);  // positions a call can number
-  if (ctx->map_floor - span < (int64_t)INT32_MIN) refill = true;
-  if (refill) {
-    hipLaunchKernelGGL(a3::k_fill_i32, dim3(std::min(blocks_for(ctx->node_map_cap, 256), 1u << 20)), dim3(256), 0,
-                       ctx->stream, ctx->node_map, ctx->node_map_cap, a3::kMapEmpty);
-    A3_HIP(ctx, hipGetLastError());
-    ctx->map_floor = (ctx->flags & A3_TEST_MAP_RANGE) ? (int64_t)INT32_MIN + 2 * span + 5 : (int64_t)a3::kMapEmpty;
+  hipLaunchKernelGGL(a3::k_fill_i32, dim3(std::min(blocks_for(ctx->node_map_cap, 256), 1u << 20)), dim3(256), 0,
+                     ctx->stream, ctx->node_map, ctx->node_map_cap, a3::kMapEmpty);
+  A3_HIP(ctx, hipGetLastError());
+  ctx->map_floor = (ctx->flags & A3_TEST_MAP_RANGE) ? (int64_t)INT32_MIN + 2 * span + 5 : (int64_t)a3::kMapEmpty;
+  return A3_OK;
+}
+
+// a map for graphs of up to num_nodes nodes (made, or enlarged, and filled)
+int reserve_node_map(a3_ctx* ctx, int64_t num_nodes) {
+  if (num_nodes <= ctx->node_map_cap) return A3_OK;
+  if (ctx->node_map) {
+    A3_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    A3_HIP(ctx, hipFree(ctx->node_map));
+    ctx->node_map = nullptr;
+    ctx->node_map_cap = 0;
   }
+  void* q = nullptr;
+  A3_HIP(ctx, hipMalloc(&q, (size_t)std::max<int64_t>(num_nodes, 1) * sizeof(int32_t)));
+  ctx->node_map = (int32_t*)q;
+  ctx->node_map_cap = num_nodes;
+  return fill_node_map(ctx);
+}
+
+int ensure_node_map(a3_ctx* ctx, int64_t num_nodes) {
+  if (int rc = reserve_node_map(ctx, num_nodes)) return rc;
+  const int64_t span = std::max<int64_t>(ctx->cap_dst[ctx->max_hops], 1);
+  if (ctx->map_floor - span < (int64_t)INT32_MIN)
+    if (int rc = fill_node_map(ctx)) return rc;
   ctx->map_floor -= span;
   ctx->map_base = (int32_t)ctx->map_floor;
   return A3_OK;
@@ -264,20 +271,25 @@ constexpr int64_t kCachedBitsBlocks = 2048;
 
 // The bitmap of cached nodes that the weighted kernels look up, rebuilt from the caller's device
 // map on every call (one streaming pass over 4 bytes per node; the map may have changed).
+int reserve_cached_bits(a3_ctx* ctx, int64_t num_nodes) {
+  const int64_t words = (num_nodes + 63) / 64;
+  if (words <= ctx->cached_bits_words) return A3_OK;
+  if (ctx->cached_bits) {
+    A3_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    A3_HIP(ctx, hipFree(ctx->cached_bits));
+    ctx->cached_bits = nullptr;
+    ctx->cached_bits_words = 0;
+  }
+  void* q = nullptr;
+  A3_HIP(ctx, hipMalloc(&q, (size_t)words * sizeof(uint64_t)));
+  ctx->cached_bits = (uint64_t*)q;
+  ctx->cached_bits_words = words;
+  return A3_OK;
+}
+
 int build_cached_bits(a3_ctx* ctx, const int32_t* cache_map, int64_t num_nodes) {
   const int64_t words = (num_nodes + 63) / 64;
-  if (words > ctx->cached_bits_words) {
-    if (ctx->cached_bits) {
-      A3_HIP(ctx, hipStreamSynchronize(ctx->stream));
-      A3_HIP(ctx, hipFree(ctx->cached_bits));
-      ctx->cached_bits = nullptr;
-      ctx->cached_bits_words = 0;
-    }
-    void* q = nullptr;
-    A3_HIP(ctx, hipMalloc(&q, (size_t)words * sizeof(uint64_t)));
-    ctx->cached_bits = (uint64_t*)q;
-    ctx->cached_bits_words = words;
-  }
+  if (int rc = reserve_cached_bits(ctx, num_nodes)) return rc;
   if (words == 0) return A3_OK;
   // a wavefront makes four words per round; 2048 workgroups at most
   const unsigned blocks = (unsigned)std::min<int64_t>((words + 15) / 16, kCachedBitsBlocks);
@@ -955,6 +967,16 @@ extern "C" int a3_sample_blocks_end(a3_ctx* ctx, a3_blocks* out) {
   return sample_finish(ctx, out);
 }
 
+extern "C" int a3_reserve(a3_ctx* ctx, int64_t num_nodes) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_reserve: ctx is null");
+  if (num_nodes < 0) return fail(ctx, A3_ERR_INVALID_ARG, "a3_reserve: num_nodes is negative");
+  if (ctx->flags & A3_HOST_ONLY) return fail(ctx, A3_ERR_HIP, "a3_reserve: context was created without a device");
+  if (ctx->pending) return fail(ctx, A3_ERR_INVALID_ARG, "a3_reserve: a begun sampling call is pending");
+  A3_HIP(ctx, hipSetDevice(ctx->device));
+  if (int rc = reserve_node_map(ctx, num_nodes)) return rc;
+  return reserve_cached_bits(ctx, num_nodes);
+}
+
 extern "C" int a3_sample_stats(a3_ctx* ctx, int64_t stats[5]) {
   if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_sample_stats: ctx is null");
   if (!stats) return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_stats: stats is null");
@@ -1493,6 +1515,15 @@ void pipeline_free(a3_pipeline* p) {
 
 extern "C" const char* a3_pipeline_last_error(const a3_pipeline* p) {
   return p ? p->err.c_str() : g_pipe_err.c_str();
+}
+
+extern "C" int a3_pipeline_reserve(a3_pipeline* p, int64_t num_nodes) {
+  if (!p) return pfail(nullptr, A3_ERR_INVALID_ARG, "a3_pipeline_reserve: pipeline is null");
+  for (int w = 0; w < p->n; ++w) {
+    const int rc = a3_reserve(p->ctx[w], num_nodes);
+    if (rc != A3_OK) return pfail(p, rc, std::string("a3_pipeline_reserve: ") + a3_last_error(p->ctx[w]));
+  }
+  return A3_OK;
 }
 
 extern "C" int a3_pipeline_create(a3_pipeline** out, int hip_device, int mode, int n_workers,

@@ -250,4 +250,8 @@ def test_validate_argument_errors(L):
     assert L.a3_validate_cache_map(h, p, 3, 1, 2) == a3.A3_ERR_HIP
     assert L.a3_set_gather_host_workgroups(h, 16) == a3.A3_OK
     assert L.a3_set_gather_host_workgroups(h, -1) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_reserve(None, 10) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_reserve(h, -1) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_reserve(h, 10) == a3.A3_ERR_HIP                                   # valid, but no device
+    assert L.a3_pipeline_reserve(None, 10) == a3.A3_ERR_INVALID_ARG
     assert L.a3_destroy(h) == a3.A3_OK

@@ -344,6 +344,22 @@ def test_weighted_launch_plan_follows_the_cache_and_keeps_the_blocks():
     ctx.close()
 
 
+def test_reserve_before_the_first_call_changes_no_result():
+    """a3_reserve makes the relabel map and the cached-node bitmap ahead of the first call (the
+    pipeline test checks the bytes); a larger graph later enlarges them as before"""
+    w, g, d_ip, d_ix = _graph("mini_copurchase")
+    cm = degree_ranked_cache(g, None, 0.3).cache_map.numpy()
+    ctx = a3.Context(64, [15, 10, 5])
+    ctx.reserve(w.num_nodes)
+    for b in range(3):
+        _compare(ctx, w, g, d_ip, d_ix, seed_batch(w.num_nodes, 64, 9, b), [15, 10, 5], cm, 4.0, b, "reserved")
+    ctx.reserve(10)                                               # smaller: nothing to do
+    w2, g2, d_ip2, d_ix2 = _graph("mini_citation")                # larger graph on the same context
+    _compare(ctx, w2, g2, d_ip2, d_ix2, seed_batch(w2.num_nodes, 64, 9, 0, dtype=np.int64), [15, 10, 5], None, 1.0, 0,
+             "after growing")
+    ctx.close()
+
+
 def test_isolated_nodes_and_no_eids():
     indptr = torch.tensor([0, 0, 1, 2, 2], dtype=torch.int64)
     indices = torch.tensor([2, 1], dtype=torch.int64)

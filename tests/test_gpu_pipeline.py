@@ -48,6 +48,11 @@ def test_pipeline_batches_match_oracle(setup, mode, n_workers):
     pipe = a3.Pipeline(mode, n_workers, 256, w.fanouts)
     n = pipe.n_workers
     assert pipe.workspace_bytes > 0
+    # what depends on the graph's size is allocated here, not by the workers' first mini-batches
+    arenas = pipe.workspace_bytes
+    pipe.reserve(w.num_nodes)
+    reserved = pipe.workspace_bytes
+    assert reserved >= arenas + n * (4 * w.num_nodes + w.num_nodes // 8)
     cap_rows = 256
     for f in w.fanouts:
         cap_rows *= 1 + f
@@ -78,6 +83,7 @@ def test_pipeline_batches_match_oracle(setup, mode, n_workers):
     with pytest.raises(a3.A3Error) as ei:
         pipe.wait()
     assert ei.value.code == a3.A3_ERR_INVALID_ARG
+    assert pipe.workspace_bytes == reserved
     pipe.close()
 
 
