@@ -363,9 +363,11 @@ def measure(args, name, headline, legs):
                                 split.feat_dev, split.feat_host, outs[j % n_w])
             torch.cuda.synchronize()
             p_s = time.perf_counter() - t_start
-            # the same mini-batches, the same edges (the full-size parity tests compare a pipeline's
+            # the same mini-batches, the same edges, and the last of them with the input nodes of the
+            # main leg's last one, in the same order (the full-size parity tests compare a pipeline's
             # blocks and rows with the oracle element by element)
             assert p_edges == n_edges
+            assert torch.equal(blk.input_nodes.long(), ids_l)
             pipes.append({"mode": names[mode], "workers": n_w, "consumer": "block mean" if consume else None,
                           "ms_per_step": p_s * 1e3 / K, "edges_per_s": p_edges / p_s,
                           "workspace_bytes": pipe.workspace_bytes,
