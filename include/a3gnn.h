@@ -54,6 +54,8 @@ extern "C" {
 #define A3_PROFILE 16u       /* bracket the kernels of every call with HIP events (see a3_profile_read) */
 #define A3_TEST_MAP_RANGE 32u /* testing: the relabel map's value ranges start two calls above the bottom
                                 of int32, so every third call refills the map and values are negative */
+#define A3_TEST_SMALL_GRID 128u /* testing: every role of the sampling kernels gets at most two workgroups,
+                                so that each wavefront walks its list of nodes in many rounds */
 #define A3_TEST_FEW_DRAWS 64u /* testing: the draw threshold keeps about fanout / 2 candidates per node at
                                 first, so most nodes take the path for too few candidates (one more scan
                                 with a lower threshold; the exhaustive selection after that) */

@@ -424,6 +424,8 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
         sa.role_blocks[2] = (uint32_t)std::min<int64_t>((nb * 16 + threads - 1) / threads, max_blocks);
         sa.role_blocks[3] = (uint32_t)std::min<int64_t>((nb + n_waves - 1) / n_waves, max_blocks);
         sa.role_blocks[4] = (uint32_t)std::min<int64_t>(nb, kMaxHubBlocks);
+        if (ctx->flags & A3_TEST_SMALL_GRID)
+          for (uint32_t& rb : sa.role_blocks) rb = std::min(rb, 2u);
         const unsigned grid = sa.role_blocks[0] + sa.role_blocks[1] + sa.role_blocks[2] +
                               sa.role_blocks[3] + sa.role_blocks[4];
         const size_t lds_bytes = sample_block_lds_bytes(sa.lds_per_wave, sa.cap, n_waves);
@@ -463,6 +465,8 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
           sa.role_blocks[3] = (uint32_t)std::min<int64_t>((nb + n_waves - 1) / n_waves, max_blocks);
           sa.role_blocks[4] = (uint32_t)std::min<int64_t>(nb, kMaxHubBlocks / 4);
         }
+        if (ctx->flags & A3_TEST_SMALL_GRID)
+          for (uint32_t& rb : sa.role_blocks) rb = std::min(rb, 2u);
         const unsigned grid = sa.role_blocks[0] + sa.role_blocks[1] + sa.role_blocks[2] +
                               sa.role_blocks[3] + sa.role_blocks[4];
         const size_t lds_bytes = sample_block_lds_bytes(sa.lds_per_wave, sa.cap, n_waves);

@@ -360,6 +360,32 @@ def test_reserve_before_the_first_call_changes_no_result():
     ctx.close()
 
 
+@pytest.mark.parametrize("flags", [a3.A3_TEST_SMALL_GRID, a3.A3_TEST_SMALL_GRID | a3.A3_TEST_FEW_DRAWS])
+def test_two_workgroups_per_role_walk_the_node_lists_in_many_rounds(flags):
+    """At the benchmark's sizes a wavefront of the sampling kernels serves many nodes in turn, and
+    the second launch of a weighted hop reads the marks of its list in several rounds of 64; small
+    tests give every node a wavefront of its own.  With the testing flag every role has two
+    workgroups: the same loops, many rounds each, in all three kernels and both launch plans."""
+    w, g, d_ip, d_ix, seeds = _hub_graph()
+    sparse = degree_ranked_cache(g, None, 0.02).cache_map.numpy()
+    half = degree_ranked_cache(g, None, 0.5).cache_map.numpy()
+    ctx = a3.Context(len(seeds), [15, 3], flags=flags)
+    _compare(ctx, w, g, d_ip, d_ix, seeds, [15, 3], None, 1.0, 41, "small grid, uniform")
+    _compare(ctx, w, g, d_ip, d_ix, seeds, [15, 3], half, 4.0, 42, "small grid, weighted")
+    plans = []
+    for b in range(3):     # few neighbours cached: most nodes are left to the second launch, then plan 2
+        _compare(ctx, w, g, d_ip, d_ix, seeds, [10, 3], sparse, 8.0, 43 + b, "small grid, sparse cache")
+        plans.append(ctx.sample_stats()["launch_plan"])
+    assert plans == [1, 2, 2]
+    ctx.close()
+    w, g, d_ip, d_ix = _graph("mini_copurchase")
+    cm = degree_ranked_cache(g, None, 0.2).cache_map.numpy()
+    ctx = a3.Context(256, [15, 10, 5], flags=flags)
+    for b, gamma in enumerate([1.0, 4.0]):
+        _compare(ctx, w, g, d_ip, d_ix, seed_batch(w.num_nodes, 256, 2, b), [15, 10, 5], cm, gamma, b, "small grid")
+    ctx.close()
+
+
 def test_isolated_nodes_and_no_eids():
     indptr = torch.tensor([0, 0, 1, 2, 2], dtype=torch.int64)
     indices = torch.tensor([2, 1], dtype=torch.int64)
