@@ -180,7 +180,7 @@ def measure(args, name, headline, legs):
     ms_sample = sum(ms_s) * K / len(ms_s)
     ms_gather = sum(ms_g) * K / len(ms_g)
     # hit rate of the last timed batch (outside the timed region)
-    ids_l = last_ids.long()
+    ids_l = last_ids.to(torch.int64, copy=True)   # a copy: last_ids is a view of the context's own memory
     hit_rate = int((d_cm[ids_l] >= 0).sum().item()) / ids_l.numel() if ids_l.numel() else 1.0
 
     # neighbour slots the last timed batch had to draw for (nodes with degree above the fanout)
