@@ -57,6 +57,10 @@ def parse():
     p.add_argument("--pmc-calibration", action="store_true",
                    help="also run plain device copies of 256 MiB (a known size) so that a rocprofv3 "
                         "--pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
+    p.add_argument("--separate-retrieve", action="store_true",
+                   help="main leg as a3_sample_blocks_begin + a3_gather_input_features instead of "
+                        "a3_sample_gather_begin (which, where rows sit in host memory, retrieves the rows "
+                        "of earlier hops on a second stream while later hops are sampled)")
     p.add_argument("--sweep", action="store_true", help="config 4: batch x cache x bias-rate table")
     p.add_argument("--policies", action="store_true", help="cache policies table")
     p.add_argument("--batches", default="256,1024,4096,16384", help="--sweep: batch sizes")
@@ -124,17 +128,24 @@ def measure(args, name, headline, legs):
     out = padded_rows(cap_rows, w.feat_dim, w.feat_dtype, dev, args.row_align)
     row_stride = (out.stride(0) if cap_rows > 1 else w.feat_dim) * out.element_size()
 
-    n_edges = n_in = 0
+    n_edges = n_in = n_in_last = 0
+    # a3_sample_gather_begin sends rows ahead only where some may sit in host memory
+    parts_ahead = (not args.separate_retrieve and split.feat_host is not None and d_cm is not None
+                   and len(w.fanouts) > 1)
     last_ids = None
     last_blocks = None
     slow_paths = {}
 
     def step(b, timed):
-        nonlocal n_edges, n_in, last_ids, last_blocks
+        nonlocal n_edges, n_in, n_in_last, last_ids, last_blocks
         # queue sampling, then the gather of its input nodes (row count taken on the device),
         # then wait for the sampling counts: the host never stalls the GPU between the two
-        ctx.sample_blocks_begin(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b)
-        ctx.gather_input_features(split.feat_dev, split.feat_host, d_cm, out)
+        if not args.separate_retrieve:
+            ctx.sample_gather_begin(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b,
+                                    split.feat_dev, split.feat_host, out)
+        else:
+            ctx.sample_blocks_begin(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b)
+            ctx.gather_input_features(split.feat_dev, split.feat_host, d_cm, out)
         blocks = ctx.sample_blocks_end()
         rows = blocks.n_src[-1]
         assert rows <= cap_rows
@@ -144,6 +155,7 @@ def measure(args, name, headline, legs):
                 slow_paths[key] = max(val, slow_paths.get(key, 0)) if keep_max else slow_paths.get(key, 0) + val
             n_edges += sum(blocks.n_edges)
             n_in += rows
+            n_in_last += rows - blocks.n_src[-2] if parts_ahead else rows   # rows of the launch behind the sampling
             last_ids = blocks.input_nodes
             last_blocks = blocks
         return blocks
@@ -199,9 +211,9 @@ def measure(args, name, headline, legs):
             and args.row_align == 128):
         traffic = recorded_traffic(w.name)
 
-    gather_payload_gbps = n_in * row_bytes / (ms_gather * 1e-3) / 1e9
+    gather_payload_gbps = n_in_last * row_bytes / (ms_gather * 1e-3) / 1e9
     # per input row: its id, its device-map entry, the row read and the row written
-    algo_bytes_per_launch = (n_in / K) * (2 * row_bytes + ib + 4)
+    algo_bytes_per_launch = (n_in_last / K) * (2 * row_bytes + ib + 4)
     gather_avg_s = ms_gather * 1e-3 / K
     achieved = algo_bytes_per_launch / gather_avg_s / 1e9
     result = {
@@ -233,7 +245,13 @@ def measure(args, name, headline, legs):
         "ms_sample_median_min": [sorted(ms_s)[len(ms_s) // 2], min(ms_s)],
         "ms_gather_median_min": [sorted(ms_g)[len(ms_g) // 2], min(ms_g)],
         # rows that are not in the HBM cache cross PCIe (zero-copy reads of pinned host memory)
-        "pcie_GBps": (n_in / K) * (1.0 - hit_rate) * row_bytes / gather_avg_s / 1e9 if hit_rate < 1.0 else 0.0,
+        # (with rows sent ahead the link works during the sampling too: the rate is over the whole step)
+        "pcie_GBps": ((n_in / K) * (1.0 - hit_rate) * row_bytes / (total_s / K if parts_ahead else gather_avg_s) / 1e9
+                      if hit_rate < 1.0 else 0.0),
+        "retrieve": ("rows of earlier hops on a second stream beside the sampling of later hops; ms_gather and "
+                     "roofline are the last part's, pcie_GBps is over the whole step" if parts_ahead
+                     else "one launch behind the sampling"),
+        "rows_behind_sampling_per_step": n_in_last / K,
         "hbm_traffic_GBps": traffic / gather_avg_s / 1e9 if traffic else None,
         "edges_per_step": n_edges / K,
         "input_rows_per_step": n_in / K,
@@ -492,8 +510,10 @@ def run_sweep(args):
     locality-aware sampling pays off (Sec. II-B Motivation 2, Sec. IV-C ablation): for every batch
     size x HBM cache fraction x bias rate it reports the cache hit rate of the input nodes, the
     number of input rows, the device time of sampling and of the feature gather (HBM rows +
-    pinned-host rows over PCIe), and the wall time per mini-batch with two mini-batches in flight
-    (parallel mode 2: sampling beside the previous retrieve).  Markdown table; one graph."""
+    pinned-host rows over PCIe) as separate calls, the wall time per mini-batch as one unit
+    (a3_sample_gather_begin: rows of earlier hops cross the link during the sampling of later
+    hops), and with two mini-batches in flight (parallel mode 2: sampling beside the previous
+    retrieve).  Markdown table; one graph."""
     import numpy as np
     import torch
     import paper_2511_07421_amd as a3
@@ -513,8 +533,8 @@ def run_sweep(args):
     print(f"# sweep on `{w.name}`: N={st['num_nodes']:,}, nnz={st['nnz']:,}, fanouts {w.fanouts}, "
           f"{w.row_bytes}-B rows, {K} timed mini-batches per cell (device times from HIP events)")
     print("| batch | cache | gamma | hit rate | input rows | ms sample | ms gather | ms total | "
-          "vs gamma=1 | PCIe GB/s | ms per step, 2 in flight | vs gamma=1 |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|---|")
+          "vs gamma=1 | PCIe GB/s | ms per step, one unit | ms per step, 2 in flight | vs gamma=1 |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
     for frac in fracs:
         split = degree_ranked_cache(g, full, frac, pin_host=True, row_align=args.row_align)
         for batch in batches:
@@ -548,6 +568,18 @@ def run_sweep(args):
                     base_total = total
                 miss_bytes = (rows - hits) / K * w.row_bytes
                 pcie = miss_bytes / (ms_g * 1e-3) / 1e9 if rows > hits else 0.0
+                # the same mini-batches through a3_sample_gather_begin (where rows sit in host memory,
+                # those of earlier hops cross the link while later hops are sampled): wall time
+                for b in range(K + W):
+                    if b == W:
+                        torch.cuda.synchronize()
+                        t0 = time.perf_counter()
+                    ctx.sample_gather_begin(g.indptr, g.indices, seeds[b], w.fanouts, split.cache_map, q, b,
+                                            split.feat_dev, split.feat_host, out)
+                    ctx.sample_blocks_end()
+                torch.cuda.synchronize()
+                unit = (time.perf_counter() - t0) * 1e3 / K
+                ctx.profile_read(0), ctx.profile_read(1)
                 # the same mini-batches with two in flight (Sec. III-B, parallel mode 2: the next
                 # mini-batch is sampled beside this one's retrieve, retrieves one at a time): wall time
                 outs = (out, out2)
@@ -567,7 +599,7 @@ def run_sweep(args):
                     base_piped = piped
                 print(f"| {batch} | {frac:.0%} | {gamma:g} | {hits / max(rows, 1):.3f} | {rows // K} | "
                       f"{ms_s:.3f} | {ms_g:.3f} | {total:.3f} | {base_total / total:.2f}x | {pcie:.1f} | "
-                      f"{piped:.3f} | {base_piped / piped:.2f}x |", flush=True)
+                      f"{unit:.3f} | {piped:.3f} | {base_piped / piped:.2f}x |", flush=True)
             pipe.close()
             ctx.close()
             del out, out2

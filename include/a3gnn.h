@@ -223,6 +223,28 @@ int a3_gather_input_features_strided(a3_ctx* ctx, const void* feat_dev, int64_t 
                                      const int32_t* cache_map, int64_t row_bytes, void* out,
                                      int64_t out_stride, int64_t out_rows);
 
+/* a3_sample_blocks_begin and a3_gather_input_features_strided as one queued unit (Alg. 1 lines 7
+ * and 10; Sec. III-B: sampling and batch generation use different resources and can overlap).
+ * The input nodes of a mini-batch are numbered hop by hop.  Where rows may sit in host memory
+ * (feat_host and cache_map given), the rows of the nodes a hop has numbered are retrieved on a
+ * second stream of the context while the next hop is sampled, so that they cross the host link
+ * while the GPU computes; only the rows of the last hop's new nodes are retrieved behind the
+ * sampling, on the context's own stream, which then waits for the second one.  With every row in
+ * device memory the retrieve is one launch behind the sampling (beside it, it would slow the
+ * sampling by as much as it saves).  Blocks and rows are exactly those of the two separate calls; `out` is whole for any work queued on the context's stream after this call (and
+ * after a synchronisation of that stream).  The call is ended with a3_sample_blocks_end, which
+ * waits for the sampling only, as ever.
+ *   cache_map    serves both as the sampler's weights (with bias_q16) and as the retrieve's map
+ *   out_rows     rows `out` can hold; min(n_input_nodes, out_rows) rows are written
+ * The second stream has the default priority and is the context's own (made on first use).
+ * Arguments, layout and errors otherwise as the two calls. */
+int a3_sample_gather_begin(a3_ctx* ctx, const int64_t* indptr, const void* indices, int32_t idx_bytes,
+                           int64_t num_nodes, const void* seeds, int64_t num_seeds,
+                           const int32_t* fanouts, int32_t num_hops, const int32_t* cache_map,
+                           uint32_t bias_q16, uint64_t rng_seed, const void* feat_dev,
+                           int64_t dev_stride, const void* feat_host, int64_t host_stride,
+                           int64_t row_bytes, void* out, int64_t out_stride, int64_t out_rows);
+
 /* Neighbour aggregation of one block, the step that consumes the path's output (Alg. 1 "forward";
  * the evaluation's GraphSAGE aggregates with the mean, Sec. IV-A):
  *   out[i,:] = mean over e in [blk_indptr[i], blk_indptr[i+1]) of x[blk_indices[e],:],  i < n_dst;

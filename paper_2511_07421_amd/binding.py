@@ -80,6 +80,11 @@ def lib():
         L.a3_sample_blocks_begin.restype = C.c_int
         L.a3_sample_blocks_end.argtypes = [C.c_void_p, C.POINTER(_CBlocks)]
         L.a3_sample_blocks_end.restype = C.c_int
+        L.a3_sample_gather_begin.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,
+                                             C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_int32,
+                                             C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p, C.c_int64,
+                                             C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_int64]
+        L.a3_sample_gather_begin.restype = C.c_int
         L.a3_sample_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
         L.a3_sample_stats.restype = C.c_int
         L.a3_gather_input_features.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -333,6 +338,31 @@ class Context:
                                           indices.element_size(), indptr.shape[0] - 1, _dptr(seeds),
                                           seeds.shape[0], fan, len(fanouts), _dptr(cache_map),
                                           bias_q16, rng_seed)
+        self._check(rc)
+        self._begun = (indices.dtype, indices.device)
+
+    def sample_gather_begin(self, indptr: torch.Tensor, indices: torch.Tensor, seeds: torch.Tensor,
+                            fanouts: Sequence[int], cache_map: Optional[torch.Tensor], bias_q16: int,
+                            rng_seed: int, feat_dev: Optional[torch.Tensor],
+                            feat_host: Optional[torch.Tensor], out: torch.Tensor) -> None:
+        """sample_blocks_begin and gather_input_features as one queued unit: the rows of the nodes a
+        hop has numbered travel on a second stream while the next hop is sampled.  Ended with
+        sample_blocks_end; out[:n] is whole for work queued on the context's stream afterwards."""
+        assert indptr.dtype == torch.int64 and indptr.is_contiguous()
+        assert indices.dtype in (torch.int32, torch.int64) and indices.is_contiguous()
+        assert seeds.dtype == indices.dtype and seeds.is_contiguous()
+        assert cache_map is None or (cache_map.dtype == torch.int32 and cache_map.is_contiguous())
+        ref = feat_dev if feat_dev is not None else feat_host
+        assert ref is not None and ref.dim() == 2
+        assert feat_host is None or feat_host.is_pinned(), "feat_host must be pinned host memory"
+        assert out.dim() == 2 and out.shape[1] == ref.shape[1] and out.dtype == ref.dtype
+        fan = (C.c_int32 * len(fanouts))(*fanouts)
+        rc = lib().a3_sample_gather_begin(self._h, _dptr(indptr), _dptr(indices), indices.element_size(),
+                                          indptr.shape[0] - 1, _dptr(seeds), seeds.shape[0], fan,
+                                          len(fanouts), _dptr(cache_map), bias_q16, rng_seed,
+                                          _dptr(feat_dev), _row_stride(feat_dev), _dptr(feat_host),
+                                          _row_stride(feat_host), ref.shape[1] * ref.element_size(),
+                                          _dptr(out), _row_stride(out), out.shape[0])
         self._check(rc)
         self._begun = (indices.dtype, indices.device)
 

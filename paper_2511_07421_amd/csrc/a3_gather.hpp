@@ -38,9 +38,10 @@ template <typename VecT, typename IdxT>
 __device__ __forceinline__ void gather_host_rows(const char* __restrict__ feat_host,
                                                  const int32_t* __restrict__ cache_map,
                                                  const int32_t* __restrict__ resolved,
-                                                 const IdxT* __restrict__ ids, int64_t n_ids, int64_t id_limit,
-                                                 uint32_t vecs_per_row, int64_t host_stride, int64_t out_stride,
-                                                 int log2_g, uint32_t host_blocks, char* __restrict__ out) {
+                                                 const IdxT* __restrict__ ids, int64_t row0, int64_t n_ids,
+                                                 int64_t id_limit, uint32_t vecs_per_row, int64_t host_stride,
+                                                 int64_t out_stride, int log2_g, uint32_t host_blocks,
+                                                 char* __restrict__ out) {
   constexpr int kPerWave = kWave * kHostScan;
   // kGatherHostLds bytes of dynamic LDS, given only to launches that set workgroups aside (the
   // other launches should not take LDS from kernels that run beside them)
@@ -55,7 +56,7 @@ __device__ __forceinline__ void gather_host_rows(const char* __restrict__ feat_h
   const uint32_t in_group = lane & (G - 1);
   const uint32_t group = lane >> log2_g, n_groups = (uint32_t)kWave >> log2_g;
   const int64_t step = (int64_t)host_blocks * kGatherThreads * kHostScan;
-  const int64_t first = ((int64_t)blockIdx.x * (kGatherThreads / kWave) + wave) * kPerWave;
+  const int64_t first = row0 + ((int64_t)blockIdx.x * (kGatherThreads / kWave) + wave) * kPerWave;
   // the lookups run two rounds ahead of the copies (ids) and one round ahead (device map), so a
   // wavefront goes from one round's copies straight into the next's
   int64_t id_ahead[kHostScan];
@@ -124,42 +125,48 @@ __device__ __forceinline__ void gather_host_rows(const char* __restrict__ feat_h
   }
 }
 
+// Rows [*first_dev, min(*n_ids_dev, n_ids)) of the id list (first_dev null: from row 0; n_ids_dev
+// null: n_ids rows).
 template <typename VecT, typename IdxT, int U, int R, bool kWaveRow>
-__global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restrict__ feat_dev,
-                                                           const char* __restrict__ feat_host,
-                                                           const int32_t* __restrict__ cache_map,
-                                                           const int32_t* __restrict__ resolved,
-                                                           const IdxT* __restrict__ ids,
-                                                           int64_t n_ids,
-                                                           const int32_t* __restrict__ n_ids_dev,
-                                                           int64_t id_limit,
-                                                           uint32_t vecs_per_row,
-                                                           int64_t dev_stride, int64_t host_stride,
-                                                           int64_t out_stride, int log2_g,
-                                                           uint32_t host_blocks,
-                                                           char* __restrict__ out) {
+__device__ __forceinline__ void gather_rows(const char* __restrict__ feat_dev,
+                                            const char* __restrict__ feat_host,
+                                            const int32_t* __restrict__ cache_map,
+                                            const int32_t* __restrict__ resolved,
+                                            const IdxT* __restrict__ ids,
+                                            const int32_t* __restrict__ first_dev,
+                                            int64_t n_ids,
+                                            const int32_t* __restrict__ n_ids_dev,
+                                            int64_t id_limit,
+                                            uint32_t vecs_per_row,
+                                            int64_t dev_stride, int64_t host_stride,
+                                            int64_t out_stride, int log2_g,
+                                            uint32_t host_blocks,
+                                            char* __restrict__ out) {
   // the row count may live on the device (gather queued before the host knows it); n_ids then
   // is the launch bound and the output capacity
   if (n_ids_dev) {
     const int64_t n_dev = *n_ids_dev;
     n_ids = n_dev < n_ids ? n_dev : n_ids;
   }
+  int64_t row0 = first_dev ? (int64_t)*first_dev : 0;
+  if (row0 < 0) row0 = 0;
+  if (row0 >= n_ids) return;
   // host_blocks > 0 (only with a device map and a host store): the first host_blocks workgroups
   // take the rows in host memory, the others the rows in the device store
   if (blockIdx.x < host_blocks) {
-    gather_host_rows<VecT, IdxT>(feat_host, cache_map, resolved, ids, n_ids, id_limit, vecs_per_row, host_stride,
-                                 out_stride, log2_g, host_blocks, out);
+    gather_host_rows<VecT, IdxT>(feat_host, cache_map, resolved, ids, row0, n_ids, id_limit, vecs_per_row,
+                                 host_stride, out_stride, log2_g, host_blocks, out);
     return;
   }
   const bool device_rows_only = host_blocks > 0;
   const uint32_t G = 1u << log2_g;
   const uint32_t lane = threadIdx.x & (G - 1);
   // the grid is capped and strides over the groups of rows
-  const int64_t n_groups = (n_ids + R - 1) / R;
+  const int64_t n_groups = (n_ids - row0 + R - 1) / R;
   const int64_t group_step = ((int64_t)(gridDim.x - host_blocks) * kGatherThreads) >> log2_g;
   for (int64_t group = ((int64_t)(blockIdx.x - host_blocks) * kGatherThreads + threadIdx.x) >> log2_g;
        group < n_groups; group += group_step) {
-  const int64_t r0 = group * R;
+  const int64_t r0 = row0 + group * R;
   const VecT* src[R];
   bool live[R];
 #pragma unroll
@@ -212,5 +219,31 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(const char* __restric
   }
   }
 }
+
+#define A3_GATHER_PARAMS                                                                                  \
+  const char *__restrict__ feat_dev, const char *__restrict__ feat_host, const int32_t *__restrict__ cache_map, \
+      const int32_t *__restrict__ resolved, const IdxT *__restrict__ ids, const int32_t *__restrict__ first_dev, \
+      int64_t n_ids, const int32_t *__restrict__ n_ids_dev, int64_t id_limit, uint32_t vecs_per_row,        \
+      int64_t dev_stride, int64_t host_stride, int64_t out_stride, int log2_g, uint32_t host_blocks,        \
+      char *__restrict__ out
+#define A3_GATHER_ARGS                                                                                   \
+  feat_dev, feat_host, cache_map, resolved, ids, first_dev, n_ids, n_ids_dev, id_limit, vecs_per_row, dev_stride, \
+      host_stride, out_stride, log2_g, host_blocks, out
+
+// the retrieve of a call
+template <typename VecT, typename IdxT, int U, int R, bool kWaveRow>
+__global__ __launch_bounds__(kGatherThreads) void k_gather(A3_GATHER_PARAMS) {
+  gather_rows<VecT, IdxT, U, R, kWaveRow>(A3_GATHER_ARGS);
+}
+
+// The same rows-by-id copy under a name of its own: the parts of a mini-batch's retrieve that
+// a3_sample_gather_begin runs ahead, on a second stream beside the sampling of the later hops.
+// Traces and counters then keep them apart from the retrieve that runs alone.
+template <typename VecT, typename IdxT, int U, int R, bool kWaveRow>
+__global__ __launch_bounds__(kGatherThreads) void k_gather_ahead(A3_GATHER_PARAMS) {
+  gather_rows<VecT, IdxT, U, R, kWaveRow>(A3_GATHER_ARGS);
+}
+#undef A3_GATHER_PARAMS
+#undef A3_GATHER_ARGS
 
 }  // namespace a3

@@ -98,11 +98,11 @@ def _run(say, name, cells, check_rows, validate=False, host_sampler=False):
             ctx.validate_cache_map(split.cache_map, split.n_cached, w.num_nodes - split.n_cached)
         seeds = seed_batch(w.num_nodes, batch, 0, b, dtype=idt)
         t0 = time.time()
-        # the step exactly as bench.py queues it: sampling, the gather of its input nodes with the
-        # row count taken on the device, then the wait for the counts
-        ctx.sample_blocks_begin(g.indptr, g.indices, torch.from_numpy(seeds).to(DEV), w.fanouts,
-                                split.cache_map, int(gamma * Q), b)
-        ctx.gather_input_features(split.feat_dev, split.feat_host, split.cache_map, out)
+        # the step exactly as bench.py queues it: sampling and the retrieve of its input rows as one
+        # unit (row counts taken on the device; where rows sit in host memory, those of earlier
+        # hops on a second stream beside the sampling of later hops), then the wait for the counts
+        ctx.sample_gather_begin(g.indptr, g.indices, torch.from_numpy(seeds).to(DEV), w.fanouts,
+                                split.cache_map, int(gamma * Q), b, split.feat_dev, split.feat_host, out)
         got_d = ctx.sample_blocks_end()
         rows = out[: got_d.n_src[-1]]
         torch.cuda.synchronize()

@@ -480,6 +480,45 @@ def test_split_call_and_device_count_gather_match_oracle():
     ctx.close()
 
 
+@pytest.mark.parametrize("name,frac", [("mini_copurchase", 0.2), ("mini_citation", 1.0), ("mini_social", 0.6), ("tiny", 0.0)])
+def test_sampling_and_retrieve_as_one_unit_match_oracle(name, frac):
+    """a3_sample_gather_begin: the rows of a hop's nodes travel on a second stream while the next
+    hop is sampled; blocks and rows equal the oracle's for 1 to 4 hops, both stores, both id widths,
+    an output buffer that is too small, an empty batch, and with ordinary calls in between"""
+    w, g, d_ip, d_ix = _graph(name)
+    idt = g.indices.numpy().dtype
+    full = make_features(g.num_nodes, w.feat_dim, w.feat_dtype, feat_seed=5)
+    split = degree_ranked_cache(g, full, frac, pin_host=True)
+    d_cm = split.cache_map.to(DEV)
+    d_fd = None if split.feat_dev is None else split.feat_dev.to(DEV)
+    fd_np = None if split.feat_dev is None else split.feat_dev.numpy()
+    fh_np = None if split.feat_host is None else split.feat_host.numpy()
+    ctx = a3.Context(w.batch, [15, 10, 5, 2])
+    cases = [([15, 10, 5], 200_000, w.batch, 4.0), ([10], 200_000, w.batch, 1.0), ([3, 2, 2, 2], 200_000, w.batch // 2, 2.0),
+             ([15, 10], 700, w.batch, 4.0), ([15, 10, 5], 200_000, 0, 4.0), ([15, 10, 5], 200_000, w.batch, 8.0)]
+    for b, (fan, cap, n_seeds, gamma) in enumerate(cases):
+        print(f"[case] one unit graph={name} fanouts={fan} out rows={cap} seeds={n_seeds} gamma={gamma}", flush=True)
+        seeds = seed_batch(w.num_nodes, n_seeds, 4, b, dtype=idt)
+        out = torch.full((cap, w.feat_dim), 7.0, dtype=w.feat_dtype, device=DEV)
+        ctx.sample_gather_begin(d_ip, d_ix, torch.from_numpy(seeds).to(DEV), fan, d_cm, int(gamma * Q), b,
+                                d_fd, split.feat_host, out)
+        with pytest.raises(a3.A3Error):              # a second begin before end is refused
+            ctx.sample_gather_begin(d_ip, d_ix, torch.from_numpy(seeds).to(DEV), fan, d_cm, int(gamma * Q), b,
+                                    d_fd, split.feat_host, out)
+        got = ctx.sample_blocks_end().to_host()
+        torch.cuda.synchronize()
+        want = oracle.sample_blocks(g.indptr.numpy(), g.indices.numpy(), seeds, fan, split.cache_map.numpy(),
+                                    int(gamma * Q), b)
+        blocks_equal(got, want)
+        n = min(cap, want.n_src[-1])
+        want_rows = oracle.gather_features(fd_np, fh_np, split.cache_map.numpy(), want.input_nodes[:n])
+        assert out[:n].cpu().numpy().tobytes() == want_rows.tobytes()
+        assert bool((out[n:] == 7.0).all()), "rows beyond the count or the capacity stay untouched"
+        if b == 2:   # an ordinary call in between
+            _compare(ctx, w, g, d_ip, d_ix, seeds, fan, split.cache_map.numpy(), gamma, b, "between units")
+    ctx.close()
+
+
 @pytest.mark.parametrize("host_workgroups", [0, 16, 3])
 @pytest.mark.parametrize("dim,dtype", [(100, torch.float32), (602, torch.float32), (8, torch.float16)])
 def test_gather_partly_cached_many_rows_and_missing_stores(dim, dtype, host_workgroups):
