@@ -1082,6 +1082,13 @@ extern "C" int a3_sample_gather_begin(a3_ctx* ctx, const int64_t* indptr, const 
                  feat_host != nullptr && cache_map != nullptr};
   int rc = check_gather_args(ctx, feat_dev, feat_host, cache_map, row_bytes, &plan.st);
   if (rc != A3_OK) return rc;
+  {  // refuse a retrieve that could not be launched before anything is queued
+    const void* ptrs[3] = {feat_dev, feat_host, out};
+    const int64_t strides[3] = {plan.st.dev, plan.st.host, plan.st.out};
+    int64_t copy_bytes = row_bytes;
+    if (pick_copy_width(row_bytes, ptrs, strides, 3, 2, &copy_bytes) == 0)
+      return fail(ctx, A3_ERR_INVALID_ARG, "a3_sample_gather_begin: buffers and strides must be 2-byte aligned");
+  }
   if (plan.parts_ahead && !(ctx->flags & A3_HOST_ONLY) && !ctx->side) {
     A3_HIP(ctx, hipSetDevice(ctx->device));
     A3_HIP(ctx, hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));
@@ -1745,11 +1752,28 @@ extern "C" int a3_pipeline_submit(a3_pipeline* p, const int64_t* indptr, const v
     const int rc = check_gather_args(c, feat_dev, feat_host, cache_map, row_bytes, &st);
     if (rc != A3_OK) return pfail(p, rc, c->err);
   }
-  int rc = a3_sample_blocks_begin(c, indptr, indices, idx_bytes, num_nodes, seeds, num_seeds, fanouts,
-                                  num_hops, cache_map, bias_q16, rng_seed);
-  if (rc != A3_OK) return pfail(p, rc, c->err);
+  const bool retrieve = row_bytes > 0 && out_rows > 0 && num_seeds > 0;
+  // one mini-batch at a time: sampling and retrieve as one unit, so that rows in host memory cross
+  // the link while later hops are sampled (with several in flight the link is busy anyway)
+  const bool one_unit = retrieve && p->mode == A3_PIPE_SEQUENTIAL;
+  int rc = one_unit ? a3_sample_gather_begin(c, indptr, indices, idx_bytes, num_nodes, seeds, num_seeds, fanouts,
+                                             num_hops, cache_map, bias_q16, rng_seed, feat_dev, dev_stride,
+                                             feat_host, host_stride, row_bytes, out, out_stride, out_rows)
+                    : a3_sample_blocks_begin(c, indptr, indices, idx_bytes, num_nodes, seeds, num_seeds, fanouts,
+                                             num_hops, cache_map, bias_q16, rng_seed);
+  if (rc != A3_OK) {
+    if (c->pending) p->submitted++;  // the sampling part is queued: reported by a3_pipeline_wait
+    return pfail(p, rc, c->err);
+  }
   p->has_gather[w] = false;
-  if (row_bytes > 0 && out_rows > 0 && num_seeds > 0) {
+  if (one_unit) {
+    hipError_t e = hipEventRecord(p->gathered[w], c->stream);
+    if (e != hipSuccess) {
+      p->submitted++;
+      return pfail(p, A3_ERR_HIP, std::string("a3_pipeline_submit: hipEventRecord: ") + hipGetErrorString(e));
+    }
+    p->has_gather[w] = true;
+  } else if (retrieve) {
     hipStream_t own = c->stream;
     if (p->mode == A3_PIPE_MODE2) {
       // batch generation is serialised: one stream takes the retrieves in submission order,

@@ -96,6 +96,22 @@ def test_sample_and_gather_argument_errors(L):
     assert gather(fd=None, fh=p, cm=None) == a3.A3_ERR_INVALID_ARG
     assert gather() == a3.A3_ERR_HIP
     assert L.a3_sample_blocks(None, p, p, 4, 10, p, 4, fan, 2, None, 65536, 0, C.byref(blocks)) == a3.A3_ERR_INVALID_ARG
+
+    # sampling and retrieve as one unit: the checks of both, before anything is queued
+    def unit(indptr=p, ns=4, bias=65536, fd=p, fh=None, cm=None, rb=8, out=p, rows=100, ds=0, os_=0):
+        return L.a3_sample_gather_begin(h, indptr, p, 4, 10, p, ns, fan, 2, cm, bias, 0, fd, ds, fh, 0, rb, out, os_, rows)
+
+    assert L.a3_sample_gather_begin(None, p, p, 4, 10, p, 4, fan, 2, None, 65536, 0, p, 0, None, 0, 8, p, 0, 100) == a3.A3_ERR_INVALID_ARG
+    assert unit(indptr=None) == a3.A3_ERR_INVALID_ARG
+    assert unit(bias=1) == a3.A3_ERR_INVALID_ARG
+    assert unit(ns=9) == a3.A3_ERR_CAPACITY
+    assert unit(rb=7) == a3.A3_ERR_INVALID_ARG
+    assert unit(out=None) == a3.A3_ERR_INVALID_ARG
+    assert unit(rows=-1) == a3.A3_ERR_INVALID_ARG
+    assert unit(fd=None, fh=None) == a3.A3_ERR_INVALID_ARG
+    assert unit(fd=None, fh=p, cm=None) == a3.A3_ERR_INVALID_ARG
+    assert unit(ds=6) == a3.A3_ERR_INVALID_ARG           # a stride below the row
+    assert unit() == a3.A3_ERR_HIP
     assert L.a3_destroy(h) == a3.A3_OK
 
 
