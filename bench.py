@@ -301,8 +301,12 @@ def measure(args, name, headline, legs):
         m_edges = m_dst = 0
         n_mean = min(K, 10)
         for b in range(W, W + n_mean):
-            ctx.sample_blocks_begin(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b)
-            ctx.gather_input_features(split.feat_dev, split.feat_host, d_cm, out)
+            if not args.separate_retrieve:
+                ctx.sample_gather_begin(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b,
+                                        split.feat_dev, split.feat_host, out)
+            else:
+                ctx.sample_blocks_begin(g.indptr, g.indices, seeds[b], w.fanouts, d_cm, bias_q16, b)
+                ctx.gather_input_features(split.feat_dev, split.feat_host, d_cm, out)
             ctx.block_mean_of_hop(H - 1, out, agg)
             blk = ctx.sample_blocks_end()
             m_edges += blk.n_edges[-1]
