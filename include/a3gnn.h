@@ -52,6 +52,8 @@ extern "C" {
 #define A3_HOST_ONLY 4u      /* no device: calls validate their arguments, then fail with A3_ERR_HIP */
 #define A3_FORCE_RADIX 8u    /* testing: always use the exhaustive selection path */
 #define A3_PROFILE 16u       /* bracket the kernels of every call with HIP events (see a3_profile_read) */
+#define A3_PROFILE_RETRIEVE 256u /* bracket the retrieves only (kind 1 of a3_profile_read): each event
+                                costs the stream about 4 us */
 #define A3_TEST_MAP_RANGE 32u /* testing: the relabel map's value ranges start two calls above the bottom
                                 of int32, so every third call refills the map and values are negative */
 #define A3_TEST_SMALL_GRID 128u /* testing: every role of the sampling kernels gets at most two workgroups,
@@ -337,7 +339,9 @@ int a3_cache_fifo_update_static(a3_ctx* ctx, int32_t* cache_map, int64_t num_nod
  * (kind 2) brackets its kernels with HIP events on the context's stream.  a3_profile_read waits for the newest event
  * and returns the device durations in milliseconds of the calls made since the previous read of
  * that kind, oldest first: ms (host) receives min(*n, max) values; at most A3_PROFILE_DEPTH calls
- * per kind are remembered.  A3_ERR_INVALID_ARG without A3_PROFILE. */
+ * per kind are remembered.  With A3_PROFILE_RETRIEVE only kind 1 is bracketed (of a
+ * a3_sample_gather_begin: its launch behind the sampling).  A3_ERR_INVALID_ARG for a kind that the
+ * context does not bracket. */
 int a3_profile_read(a3_ctx* ctx, int kind, float* ms, int max, int* n);
 
 /* ---- Mini-batch pipelines on HIP streams (Sec. III-B, "Multi-Level Parallelism Scheduling") ----

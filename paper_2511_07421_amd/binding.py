@@ -14,6 +14,7 @@ A3_MAX_HOPS = 8
 A3_MAX_FANOUT = 1024
 A3_OK, A3_ERR_INVALID_ARG, A3_ERR_CAPACITY, A3_ERR_HIP, A3_ERR_INPUT = 0, -1, -2, -3, -4
 A3_VALIDATE, A3_NO_EIDS, A3_HOST_ONLY, A3_FORCE_RADIX, A3_PROFILE, A3_TEST_MAP_RANGE, A3_TEST_FEW_DRAWS, A3_TEST_SMALL_GRID = 1, 2, 4, 8, 16, 32, 64, 128
+A3_PROFILE_RETRIEVE = 256
 A3_PROFILE_DEPTH = 256
 A3_FIFO_STATIC_MAX_IDS = 1 << 22
 A3_PIPE_SEQUENTIAL, A3_PIPE_MODE1, A3_PIPE_MODE2 = 0, 1, 2

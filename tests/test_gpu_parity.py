@@ -386,6 +386,33 @@ def test_two_workgroups_per_role_walk_the_node_lists_in_many_rounds(flags):
     ctx.close()
 
 
+def test_event_brackets_by_kind():
+    """A3_PROFILE brackets sampling, retrieve and aggregation; A3_PROFILE_RETRIEVE the retrieve only;
+    a plain context none.  One duration per call since the last read, each positive."""
+    w, g, d_ip, d_ix = _graph("mini_copurchase")
+    full = make_features(g.num_nodes, w.feat_dim, w.feat_dtype, feat_seed=5)
+    split = degree_ranked_cache(g, full, 0.2, pin_host=True)
+    d_cm, d_fd = split.cache_map.to(DEV), split.feat_dev.to(DEV)
+    out = torch.empty((200_000, w.feat_dim), dtype=w.feat_dtype, device=DEV)
+    for flags, kinds in [(a3.A3_PROFILE, (0, 1)), (a3.A3_PROFILE_RETRIEVE, (1,)), (0, ())]:
+        ctx = a3.Context(w.batch, w.fanouts, flags=flags)
+        for b in range(3):
+            seeds = torch.from_numpy(seed_batch(w.num_nodes, w.batch, 0, b)).to(DEV)
+            ctx.sample_gather_begin(d_ip, d_ix, seeds, w.fanouts, d_cm, 4 * Q, b, d_fd, split.feat_host, out)
+            ctx.sample_blocks_end()
+        for kind in (0, 1, 2):
+            if kind in kinds:
+                ms = ctx.profile_read(kind)
+                assert len(ms) == 3 and all(0.0 < t < 100.0 for t in ms)
+                assert ctx.profile_read(kind) == []
+            elif kind == 2 and flags == a3.A3_PROFILE:
+                assert ctx.profile_read(kind) == []
+            else:
+                with pytest.raises(a3.A3Error):
+                    ctx.profile_read(kind)
+        ctx.close()
+
+
 def test_isolated_nodes_and_no_eids():
     indptr = torch.tensor([0, 0, 1, 2, 2], dtype=torch.int64)
     indices = torch.tensor([2, 1], dtype=torch.int64)
