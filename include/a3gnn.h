@@ -11,13 +11,13 @@
  *      neighbourhood sampled by weighted reservoir sampling (Alg. 2) with a
  *      larger weight, the bias rate gamma, on neighbours whose feature row is
  *      already in the device cache (locality-aware sampling);
- *   2. reindex (Alg. 1 line 7): global ids -> local ids with duplicates
+ *   2. reindex (Alg. 1, reindex step): global ids -> local ids with duplicates
  *      eliminated, one bipartite block in CSR form per hop;
- *   3. feature_retrieve (Alg. 1 line 10): the input nodes' feature rows are
+ *   3. feature_retrieve (Alg. 1, feature-retrieve step): the input nodes' feature rows are
  *      copied from the device cache or from the host store, as the device map
  *      (Sec. III, feature cache module) says.
  *
- * Determinism.  rand(0,1) of Alg. 2 line 2 is a Philox4x32-10 draw x keyed on
+ * Determinism.  rand(0,1) of Alg. 2, key step is a Philox4x32-10 draw x keyed on
  * (rng_seed, hop, node id, neighbour slot); u = (x+1)/2^32.  The key
  * k = u^(1/w) is compared in the log domain with integers only:
  * K = floor((-log2(u) in Q32) * 65536 / w_q16), smaller is better, ties go to
@@ -80,11 +80,11 @@ int a3_destroy(a3_ctx* ctx);
 /* hipStream_t for subsequent calls; pending work on the old stream is waited for. */
 int a3_set_stream(a3_ctx* ctx, void* hip_stream);
 /* Optional: allocates now what depends on the graph's size (the relabel map, 4 bytes per node, and
- * the bitmap of cached nodes, 1 bit per node; Alg. 1 line 7 and Sec. III-A), so that no later
+ * the bitmap of cached nodes, 1 bit per node; Alg. 1, reindex step, and Sec. III-A), so that no later
  * sampling call on a graph of at most num_nodes nodes allocates device memory; without it the
  * first such call does.  A3_ERR_INVALID_ARG while a begun sampling call is pending. */
 int a3_reserve(a3_ctx* ctx, int64_t num_nodes);
-/* Tuning of the feature retrieve (Alg. 1 line 10) where both stores are given: n workgroups of
+/* Tuning of the feature retrieve (Alg. 1, feature-retrieve step) where both stores are given: n workgroups of
  * each launch are set aside for the rows in host memory and the others copy the device rows.
  * n = 0, a context's default: none are, every workgroup copies rows of both stores as they come,
  * the fastest when the retrieve has the GPU to itself.  A small n (16 fill a PCIe 5.0 x16 link)
@@ -114,7 +114,7 @@ typedef struct {
   void* input_nodes;                 /* device [n_src[num_hops-1]], idx_bytes wide: global id of local id */
 } a3_blocks;
 
-/* Sampling + reindex (Sec. III-A, Alg. 2, Alg. 1 line 7).
+/* Sampling + reindex (Sec. III-A, Alg. 2, Alg. 1, reindex step).
  *   indptr      device int64 [num_nodes + 1], CSR row starts.
  *   indices     device int32 (idx_bytes = 4) or int64 (idx_bytes = 8) [indptr[num_nodes]];
  *               rows sorted, no repeated neighbour (not checked).
@@ -178,7 +178,7 @@ int a3_sample_blocks_end(a3_ctx* ctx, a3_blocks* out);
  * A3_ERR_INVALID_ARG before the first ended call or while a begun call is pending. */
 int a3_sample_stats(a3_ctx* ctx, int64_t stats[5]);
 
-/* Feature retrieve (Alg. 1 line 10): out[i,:] = feat_dev[c,:] if
+/* Feature retrieve (Alg. 1, feature-retrieve step): out[i,:] = feat_dev[c,:] if
  * c = cache_map[ids[i]] >= 0, else feat_host[-c-1,:].
  *   feat_dev    device [n_cached, row_bytes]; may be NULL if no id maps to it.
  *   feat_host   host memory that the device can read (pinned, mapped)
@@ -225,8 +225,8 @@ int a3_gather_input_features_strided(a3_ctx* ctx, const void* feat_dev, int64_t 
                                      const int32_t* cache_map, int64_t row_bytes, void* out,
                                      int64_t out_stride, int64_t out_rows);
 
-/* a3_sample_blocks_begin and a3_gather_input_features_strided as one queued unit (Alg. 1 lines 7
- * and 10; Sec. III-B: sampling and batch generation use different resources and can overlap).
+/* a3_sample_blocks_begin and a3_gather_input_features_strided as one queued unit (Alg. 1,
+ * reindex and feature-retrieve steps; Sec. III-B: sampling and batch generation use different resources and can overlap).
  * The input nodes of a mini-batch are numbered hop by hop.  Where rows may sit in host memory
  * (feat_host and cache_map given), the rows of the nodes a hop has numbered are retrieved on a
  * second stream of the context while the next hop is sampled, so that they cross the host link

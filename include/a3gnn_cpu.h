@@ -3,7 +3,7 @@
  *
  * The paper's design space lets sampling run on the CPU with n worker processes instead of on
  * the GPU (Tab. I: "Sampling Device", "Workers"; Sec. III).  This sampler is that choice: the
- * same locality-aware multi-hop sampling and reindex (Sec. III-A, Alg. 2, Alg. 1 line 7), the same
+ * same locality-aware multi-hop sampling and reindex (Sec. III-A, Alg. 2, Alg. 1, reindex step), the same
  * draws, keys and orderings as the GPU library (see a3gnn.h, "Determinism"), on host pointers,
  * with n worker threads.  For given inputs both devices produce identical arrays.
  * It is called explicitly; the GPU entry points never route through it.

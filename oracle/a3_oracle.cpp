@@ -41,7 +41,7 @@ extern "C" void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// rand(0,1) of Alg. 2 line 2, made reproducible: a counter-based draw that
+// rand(0,1) of Alg. 2, key step, made reproducible: a counter-based draw that
 // depends only on (rng_seed, hop, node, slot).
 extern "C" uint32_t oracle_draw(uint64_t rng_seed, uint32_t hop, uint64_t node, uint64_t slot) {
   const uint32_t ctr[4] = {(uint32_t)(slot >> 2), (uint32_t)node, (uint32_t)(node >> 32), hop};
@@ -74,7 +74,7 @@ extern "C" uint64_t oracle_fixlog2_q32(uint64_t U) {
   return ((uint64_t)e << 32) | frac;
 }
 
-// Alg. 2 line 2: k = u^(1/w).  Ordering by k descending equals ordering by
+// Alg. 2, key step: k = u^(1/w).  Ordering by k descending equals ordering by
 // -log2(u)/w ascending; with u = (x+1)/2^32, -log2(u) = 32 - log2(x+1).
 extern "C" uint64_t oracle_key(uint32_t x, uint32_t w_q16) {
   const uint64_t L = (32ull << 32) - oracle_fixlog2_q32((uint64_t)x + 1);
@@ -98,8 +98,8 @@ bool better(const Keyed& a, const Keyed& b) {
 
 }  // namespace
 
-// Alg. 2 reaches "the m neighbours with the largest keys" (lines 6-8 evict
-// the current minimum whenever a larger key arrives), so the plain definition
+// Alg. 2 reaches the m neighbours with the largest keys (its replacement step
+// evicts the current minimum whenever a larger key arrives), so the plain definition
 // is evaluated: key every slot, order them, keep the first m.
 extern "C" int64_t oracle_select(uint64_t rng_seed, uint32_t hop, uint64_t node, int64_t deg,
                                  int64_t fanout, const uint32_t* weights_q16, int64_t* chosen) {

@@ -54,7 +54,7 @@ void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t
 
 /* The draw of slot `slot` of node `node` at hop `hop`: word (slot & 3) of the
  * Philox block with counter (slot >> 2, lo32(node), hi32(node), hop) and key
- * (lo32(rng_seed), hi32(rng_seed)).  Stands for rand(0,1) of Alg. 2 line 2
+ * (lo32(rng_seed), hi32(rng_seed)).  Stands for rand(0,1) of Alg. 2, key step
  * through u = (x + 1) / 2^32, so u lies in (0, 1]. */
 uint32_t oracle_draw(uint64_t rng_seed, uint32_t hop, uint64_t node, uint64_t slot);
 
@@ -62,7 +62,7 @@ uint32_t oracle_draw(uint64_t rng_seed, uint32_t hop, uint64_t node, uint64_t sl
  * shift-and-square recurrence on a Q1.31 mantissa, integers only. */
 uint64_t oracle_fixlog2_q32(uint64_t U);
 
-/* Alg. 2 line 2 in the log domain.  k = u^(1/w) descending is the same order
+/* Alg. 2, key step in the log domain.  k = u^(1/w) descending is the same order
  * as -log2(u)/w ascending; the key is K = floor(((L << 16)) / w_q16) with
  * L = 32*2^32 - fixlog2(x + 1) = -log2(u) in Q32 and w_q16 the weight in
  * Q16.16.  Smaller K is better. */

@@ -105,7 +105,7 @@ __device__ __forceinline__ uint64_t div_by_weight(uint64_t n, uint32_t w, double
   return q;
 }
 
-// Alg. 2 line 2 in the log domain: -log2(u)/w in Q32 with u = (x+1)/2^32; inv_w = 1.0 / w_q16.
+// Alg. 2, key step in the log domain: -log2(u)/w in Q32 with u = (x+1)/2^32; inv_w = 1.0 / w_q16.
 __device__ __forceinline__ uint64_t sample_key(uint32_t x, uint32_t w_q16, double inv_w) {
   const uint64_t L = (32ull << 32) - fixlog2_q32((uint64_t)x + 1);
   return div_by_weight(L << 16, w_q16, inv_w);

@@ -238,7 +238,7 @@ inline uint64_t log2_q32(uint64_t U) {
   return ((uint64_t)e << 32) | frac;
 }
 
-// Alg. 2 line 2 in the log domain: -log2(u) / w in Q32, u = (x + 1) / 2^32
+// Alg. 2, key step in the log domain: -log2(u) / w in Q32, u = (x + 1) / 2^32
 inline uint64_t weighted_key(uint32_t x, uint32_t w_q16) {
   const uint64_t neg_log = (32ull << 32) - log2_q32((uint64_t)x + 1);
   return (neg_log << 16) / w_q16;

@@ -1,4 +1,4 @@
-"""Pins for the oracle's primitives: Philox, fixlog2, the key (Alg. 2 line 2)."""
+"""Pins for the oracle's primitives: Philox, fixlog2, the key (Alg. 2, key step)."""
 import os
 import random
 from decimal import Decimal, getcontext
@@ -97,7 +97,7 @@ def test_fixlog2_monotone():
 
 
 def test_key_is_minus_log2_u_over_w_in_q32():
-    """Alg. 2 line 2: k = u^(1/w); the oracle's K is -log2(k) in Q32, u = (x+1)/2^32."""
+    """Alg. 2, key step: k = u^(1/w); the oracle's K is -log2(k) in Q32, u = (x+1)/2^32."""
     rnd = random.Random(4)
     for _ in range(1500):
         x = rnd.getrandbits(32)
