@@ -46,7 +46,7 @@ class CacheSplit:
 def degree_ranked_cache(graph: Graph, full: Optional[torch.Tensor], frac: float,
                         pin_host: bool = False, row_align: int = 0) -> CacheSplit:
     """Static cache of the hottest rows, hotness = degree (the policy the paper cites from
-    PaGraph in Sec. II-B and uses, as 'most frequently accessed', in its ablation).
+    PaGraph in Sec. II-B and uses, as the nodes accessed most often, in its ablation).
     Rank nodes by (degree descending, id ascending); the first ceil(frac * N) ranks live in
     the device cache at slot = rank, the others in the host store at slot = rank - n_cached.
     row_align > 0 pads the rows of both stores (see padded_rows)."""
