@@ -632,8 +632,8 @@ def run_sweep(args):
 def run_policies(args):
     """Cache policies on the co-purchase-style graph: hit rate and step time of the static fill
     ranked by degree (the input generators' default), the static fill ranked by access count over
-    pre-sampled mini-batches (a3_cache_count_accesses + a3_cache_rank; Sec. IV-C: "most frequently
-    accessed nodes"), and a FIFO dynamic cache that starts empty (a3_cache_fifo_update_static;
+    pre-sampled mini-batches (a3_cache_count_accesses + a3_cache_rank; Sec. IV-C fills the cache
+    with the nodes accessed most often), and a FIFO dynamic cache that starts empty (a3_cache_fifo_update_static;
     Sec. II-B), each under uniform and locality-aware sampling.  Markdown table."""
     import numpy as np
     import torch

@@ -278,8 +278,8 @@ int a3_block_mean_of_hop_strided(a3_ctx* ctx, int32_t hop, const void* x, int64_
                                  int32_t x_dtype, int64_t dim, void* out, int64_t out_stride,
                                  int64_t out_rows);
 
-/* ---- Cache policies (Sec. III feature cache module; Sec. IV-C caches "the most frequently
- * accessed nodes"; Sec. II-B names static and FIFO caches).  In all three calls ids == NULL means
+/* ---- Cache policies (Sec. III feature cache module; Sec. IV-C caches the nodes
+ * accessed most often; Sec. II-B names static and FIFO caches).  In all three calls ids == NULL means
  * the input nodes of the context's most recent a3_sample_blocks(_begin), with their count taken on
  * the device (idx_bytes and n_ids are then ignored), so the call can be queued without a host wait.
  *
