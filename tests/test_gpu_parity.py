@@ -413,6 +413,35 @@ def test_event_brackets_by_kind():
         ctx.close()
 
 
+def test_one_unit_with_a_bad_seed_retrieves_nothing_and_recovers():
+    """A3_VALIDATE finds a repeated seed on the device: the unit's retrieve copies no row, the
+    error comes with sample_blocks_end, and the next unit on the context is right again."""
+    w, g, d_ip, d_ix = _graph("mini_copurchase")
+    full = make_features(g.num_nodes, w.feat_dim, w.feat_dtype, feat_seed=5)
+    split = degree_ranked_cache(g, full, 0.2, pin_host=True)
+    d_cm, d_fd = split.cache_map.to(DEV), split.feat_dev.to(DEV)
+    ctx = a3.Context(64, w.fanouts, flags=a3.A3_VALIDATE)
+    out = torch.full((100_000, w.feat_dim), 7.0, dtype=w.feat_dtype, device=DEV)
+    bad = torch.tensor([5, 9, 5, 11], dtype=torch.int32, device=DEV)
+    ctx.sample_gather_begin(d_ip, d_ix, bad, w.fanouts, d_cm, 4 * Q, 0, d_fd, split.feat_host, out)
+    with pytest.raises(a3.A3Error) as ei:
+        ctx.sample_blocks_end()
+    assert ei.value.code == a3.A3_ERR_INPUT
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())
+    seeds = seed_batch(w.num_nodes, 64, 3, 1)
+    ctx.sample_gather_begin(d_ip, d_ix, torch.from_numpy(seeds).to(DEV), w.fanouts, d_cm, 4 * Q, 1, d_fd,
+                            split.feat_host, out)
+    got = ctx.sample_blocks_end().to_host()
+    torch.cuda.synchronize()
+    want = oracle.sample_blocks(g.indptr.numpy(), g.indices.numpy(), seeds, w.fanouts, split.cache_map.numpy(), 4 * Q, 1)
+    blocks_equal(got, want)
+    want_rows = oracle.gather_features(split.feat_dev.numpy(), split.feat_host.numpy(), split.cache_map.numpy(),
+                                       want.input_nodes)
+    assert out[: want.n_src[-1]].cpu().numpy().tobytes() == want_rows.tobytes()
+    ctx.close()
+
+
 def test_isolated_nodes_and_no_eids():
     indptr = torch.tensor([0, 0, 1, 2, 2], dtype=torch.int64)
     indices = torch.tensor([2, 1], dtype=torch.int64)
