@@ -1,7 +1,7 @@
 """Seeded random configurations against the oracle: graphs of several sizes, degree ranges and
 id widths, 1-3 hops, fanouts 1-64, every cache fraction (degree-ranked and arbitrary cached sets),
 bias rates from 1 to 1000; tables of several widths and types through the retrieve with and
-without workgroups set aside for host rows.  Equality throughout; what the fixed cases of the other
+without workgroups set aside for host rows, and through sampling and retrieve as one unit.  Equality throughout; what the fixed cases of the other
 files do not happen to combine, these do."""
 import numpy as np
 import pytest
@@ -43,6 +43,53 @@ def test_random_sampling_configurations(seed):
             got = ctx.sample_blocks(d_ip, d_ix, torch.from_numpy(seeds).to(DEV), fan, cm.to(DEV),
                                     int(gamma * 65536), rs).to_host()
             blocks_equal(got, oracle.sample_blocks(ip, ix, seeds, fan, cm.numpy(), int(gamma * 65536), rs))
+            ctx.close()
+
+
+@pytest.mark.parametrize("seed", [31, 32, 33])
+def test_random_units_of_sampling_and_retrieve(seed):
+    """a3_sample_gather_begin on random graphs, tables of several widths and types, every cache
+    fraction (rows ahead on the second stream whenever a host store exists), 1-3 hops, output
+    buffers that are sometimes too small: blocks and rows equal the oracle's"""
+    rng = np.random.default_rng(seed)
+    for _ in range(4):
+        N = int(rng.choice([300, 2000, 12000]))
+        mean = min(float(rng.choice([3.0, 12.0, 60.0, 300.0])), N / 4)
+        dmax = int(min(N - 1, rng.choice([50, 500, 6000])))
+        idt = torch.int32 if rng.integers(0, 2) else torch.int64
+        g = make_graph(N, mean, 1, max(dmax, 2), 2.1, bool(rng.integers(0, 2)), int(rng.integers(0, 1 << 30)), idt)
+        ip, ix = g.indptr.numpy(), g.indices.numpy()
+        d_ip, d_ix = g.indptr.to(DEV), g.indices.to(DEV)
+        for rep in range(4):
+            dim = int(rng.choice([1, 2, 3, 8, 25, 64, 100, 128, 301, 602]))
+            dt = torch.float32 if rng.integers(0, 2) else torch.float16
+            full = torch.from_numpy(rng.standard_normal((N, dim)).astype(np.float32)).to(dt)
+            frac = float(rng.choice([0.0, 0.1, 0.5, 0.97, 1.0]))
+            split = degree_ranked_cache(g, full, frac, pin_host=True)
+            fan = [int(rng.choice([1, 2, 5, 10, 15, 25])) for _ in range(int(rng.integers(1, 4)))]
+            n_seeds = min(int(rng.choice([1, 7, 64, 300])), N)
+            gamma = float(rng.choice([1.0, 2.0, 4.0, 33.0]))
+            rs = int(rng.integers(0, 1 << 40))
+            cap = int(rng.choice([N, N, max(1, N // 7)]))
+            seeds = seed_batch(N, n_seeds, int(rng.integers(0, 100)), rep, dtype=ix.dtype)
+            print(f"[case] random unit seed={seed} N={N} {idt} dim={dim} {dt} frac={frac} fan={fan} seeds={n_seeds} "
+                  f"gamma={gamma} out rows={cap}", flush=True)
+            fd = split.feat_dev.to(DEV) if split.feat_dev is not None and split.feat_dev.shape[0] else None
+            fh = split.feat_host if split.feat_host is not None and split.feat_host.shape[0] else None
+            out = torch.full((cap, dim), 3.0, dtype=dt, device=DEV)
+            ctx = a3.Context(n_seeds, fan)
+            ctx.sample_gather_begin(d_ip, d_ix, torch.from_numpy(seeds).to(DEV), fan, split.cache_map.to(DEV),
+                                    int(gamma * 65536), rs, fd, fh, out)
+            got = ctx.sample_blocks_end().to_host()
+            torch.cuda.synchronize()
+            want = oracle.sample_blocks(ip, ix, seeds, fan, split.cache_map.numpy(), int(gamma * 65536), rs)
+            blocks_equal(got, want)
+            n = min(cap, want.n_src[-1])
+            want_rows = oracle.gather_features(None if fd is None else split.feat_dev.numpy(),
+                                               None if fh is None else split.feat_host.numpy(),
+                                               split.cache_map.numpy(), want.input_nodes[:n])
+            assert out[:n].cpu().numpy().tobytes() == want_rows.tobytes()
+            assert bool((out[n:] == 3.0).all())
             ctx.close()
 
 
