@@ -126,7 +126,7 @@ def measure(args, name, headline, legs):
     # roofline's launch duration); the sampling time comes from a repeat of the same mini-batches
     # on a context that brackets everything.  Each event costs the stream about 4 us: with all
     # five of them a mini-batch of 0.19 ms takes 0.205.
-    ctx = a3.Context(batch, w.fanouts, flags=a3.A3_PROFILE_RETRIEVE)
+    ctx = a3.Context(batch, w.fanouts, flags=a3.A3_PROFILE_RETRIEVE | a3.A3_STATIC_MAP)
     bias_q16 = int(round(gamma * 65536))
     cap_rows = cap_rows_of(w, batch)
     out = padded_rows(cap_rows, w.feat_dim, w.feat_dtype, dev, args.row_align)
@@ -196,7 +196,7 @@ def measure(args, name, headline, legs):
     ids_l = last_ids.to(torch.int64, copy=True)   # a copy: last_ids is a view of the context's own memory
     # the same mini-batches once more, every call bracketed: the sampling's device time
     ctx.close()
-    ctx = a3.Context(batch, w.fanouts, flags=a3.A3_PROFILE)
+    ctx = a3.Context(batch, w.fanouts, flags=a3.A3_PROFILE | a3.A3_STATIC_MAP)
     for b in range(max(W - 2, 0), W):
         step(b, False)
     torch.cuda.synchronize()
@@ -369,7 +369,7 @@ def measure(args, name, headline, legs):
         if can_consume:
             plans += [(a3.A3_PIPE_SEQUENTIAL, 1, True), (a3.A3_PIPE_MODE1, 3, True)]
         for mode, n_w, consume in plans:
-            pipe = a3.Pipeline(mode, n_w, batch, w.fanouts)
+            pipe = a3.Pipeline(mode, n_w, batch, w.fanouts, flags=a3.A3_STATIC_MAP)
             # a worker must not start its next mini-batch (which overwrites its blocks and its
             # row buffer) before the consumer has read the previous one: an event per worker
             worker_streams = [torch.cuda.ExternalStream(pipe.stream(k), device=dev) for k in range(n_w)]
@@ -561,11 +561,11 @@ def run_sweep(args):
     for frac in fracs:
         split = degree_ranked_cache(g, full, frac, pin_host=True, row_align=args.row_align)
         for batch in batches:
-            ctx = a3.Context(batch, w.fanouts, flags=a3.A3_PROFILE)
+            ctx = a3.Context(batch, w.fanouts, flags=a3.A3_PROFILE | a3.A3_STATIC_MAP)
             cap_rows = cap_rows_of(w, batch)
             out = padded_rows(cap_rows, w.feat_dim, w.feat_dtype, dev, args.row_align)
             out2 = padded_rows(cap_rows, w.feat_dim, w.feat_dtype, dev, args.row_align)
-            pipe = a3.Pipeline(a3.A3_PIPE_MODE2, 2, batch, w.fanouts)
+            pipe = a3.Pipeline(a3.A3_PIPE_MODE2, 2, batch, w.fanouts, flags=a3.A3_STATIC_MAP)
             seeds = [torch.from_numpy(seed_batch(w.num_nodes, batch, 0, b, dtype=idx_np)).to(dev)
                      for b in range(K + W)]
             base_total = base_piped = None

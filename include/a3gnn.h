@@ -61,6 +61,15 @@ extern "C" {
 #define A3_TEST_FEW_DRAWS 64u /* testing: the draw threshold keeps about fanout / 2 candidates per node at
                                 first, so most nodes take the path for too few candidates (one more scan
                                 with a lower threshold; the exhaustive selection after that) */
+#define A3_STATIC_MAP 512u   /* the caller's promise that a device map's contents do not change while
+                                sampling calls on this context are given the same map pointer, except
+                                through this context's own a3_cache_fifo_update*: what a weighted call
+                                derives from the map (a bitmap of the cached nodes, the weight classes
+                                present: Sec. III-A) is then made when the pointer or num_nodes changes
+                                instead of at every call (two kernels, 10 us at 2.45 M nodes).  A change
+                                the context cannot see (the caller rewrote the map, or freed it and
+                                built another at the same address) is announced with
+                                a3_device_map_changed */
 #define A3_PROFILE_DEPTH 256 /* calls remembered per kind */
 
 typedef struct a3_ctx a3_ctx;
@@ -84,6 +93,10 @@ int a3_set_stream(a3_ctx* ctx, void* hip_stream);
  * sampling call on a graph of at most num_nodes nodes allocates device memory; without it the
  * first such call does.  A3_ERR_INVALID_ARG while a begun sampling call is pending. */
 int a3_reserve(a3_ctx* ctx, int64_t num_nodes);
+/* A3_STATIC_MAP contexts: the device map was rewritten, or another one now lives at its address;
+ * the next weighted sampling call derives its bitmap of cached nodes again (Sec. III-A).  Harmless
+ * on other contexts. */
+int a3_device_map_changed(a3_ctx* ctx);
 /* Tuning of the feature retrieve (Alg. 1, feature-retrieve step) where both stores are given: n workgroups of
  * each launch are set aside for the rows in host memory and the others copy the device rows.
  * n = 0, a context's default: none are, every workgroup copies rows of both stores as they come,

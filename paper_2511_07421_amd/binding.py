@@ -15,6 +15,7 @@ A3_MAX_FANOUT = 1024
 A3_OK, A3_ERR_INVALID_ARG, A3_ERR_CAPACITY, A3_ERR_HIP, A3_ERR_INPUT = 0, -1, -2, -3, -4
 A3_VALIDATE, A3_NO_EIDS, A3_HOST_ONLY, A3_FORCE_RADIX, A3_PROFILE, A3_TEST_MAP_RANGE, A3_TEST_FEW_DRAWS, A3_TEST_SMALL_GRID = 1, 2, 4, 8, 16, 32, 64, 128
 A3_PROFILE_RETRIEVE = 256
+A3_STATIC_MAP = 512
 A3_PROFILE_DEPTH = 256
 A3_FIFO_STATIC_MAX_IDS = 1 << 22
 A3_PIPE_SEQUENTIAL, A3_PIPE_MODE1, A3_PIPE_MODE2 = 0, 1, 2
@@ -66,6 +67,8 @@ def lib():
         L.a3_set_gather_host_workgroups.restype = C.c_int
         L.a3_reserve.argtypes = [C.c_void_p, C.c_int64]
         L.a3_reserve.restype = C.c_int
+        L.a3_device_map_changed.argtypes = [C.c_void_p]
+        L.a3_device_map_changed.restype = C.c_int
         L.a3_pipeline_reserve.argtypes = [C.c_void_p, C.c_int64]
         L.a3_pipeline_reserve.restype = C.c_int
         L.a3_last_error.argtypes = [C.c_void_p]
@@ -290,6 +293,10 @@ class Context:
     def reserve(self, num_nodes: int):
         """allocate now what depends on the graph's size, so that no later sampling call does"""
         self._check(lib().a3_reserve(self._h, num_nodes))
+
+    def device_map_changed(self):
+        """A3_STATIC_MAP contexts: the map was rewritten, or another one lives at its address now"""
+        self._check(lib().a3_device_map_changed(self._h))
 
     def validate_graph(self, indptr: torch.Tensor, indices: torch.Tensor):
         """raises A3Error (A3_ERR_INPUT) unless (indptr, indices) is a CSR with sorted, repeat-free rows"""

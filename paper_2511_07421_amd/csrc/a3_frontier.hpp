@@ -47,8 +47,10 @@ __global__ __launch_bounds__(kTileThreads) void k_cached_bits(const int32_t* __r
   }
 }
 
+// `kept` receives the result too: a context whose device map does not change between calls
+// (A3_STATIC_MAP) skips this kernel and k_cached_bits, and k_frontier restores the word from there
 __global__ __launch_bounds__(kTileThreads) void k_class_mix(const int32_t* __restrict__ block_seen, int n_blocks,
-                                                           DevState* st) {
+                                                           DevState* st, int32_t* kept) {
   __shared__ uint32_t seen_lds[kTileThreads / kWave];
   uint32_t seen = 0;
   for (int b = threadIdx.x; b < n_blocks; b += kTileThreads) seen |= (uint32_t)block_seen[b];
@@ -59,6 +61,7 @@ __global__ __launch_bounds__(kTileThreads) void k_class_mix(const int32_t* __res
     uint32_t all = 0;
     for (int w = 0; w < kTileThreads / kWave; ++w) all |= seen_lds[w];
     st->class_mix = (int32_t)all;
+    *kept = (int32_t)all;
   }
 }
 
@@ -79,6 +82,7 @@ struct FrontierArgs {
   int32_t* tile_sums;
   int64_t num_nodes;
   NodeRec* bins[kNumBins];   // node records per degree bin
+  const int32_t* class_mix_kept;  // hop 0 of a weighted call that reuses the bitmap of cached nodes, else null
 };
 
 __device__ __forceinline__ int degree_bin(uint32_t deg) {
@@ -93,6 +97,7 @@ __global__ __launch_bounds__(kTileThreads) void k_frontier(const FrontierArgs<Id
   __shared__ uint32_t bin_n[kNumBins];
   __shared__ uint32_t bin_base[kNumBins];
   const bool from_seeds = a.from_seeds != 0;
+  if (a.class_mix_kept && blockIdx.x == 0 && threadIdx.x == 0) a.st->class_mix = *a.class_mix_kept;
   if (from_seeds && blockIdx.x == 0 && threadIdx.x == 0) a.st->n_dst[0] = (int32_t)a.num_seeds;
   const int64_t n = from_seeds ? a.num_seeds : (int64_t)a.st->n_dst[a.hop];
   if ((int64_t)blockIdx.x * kTile >= n) return;

@@ -54,7 +54,11 @@ struct a3_ctx {
   bool last_weighted = false;   // the launch plan of the last sampling call
   bool last_full_only = false;
   uint64_t* cached_bits = nullptr;  // one bit per node, rebuilt from the device map by every weighted call
-  int64_t cached_bits_words = 0;
+  int64_t cached_bits_words = 0;    // (with A3_STATIC_MAP: when the map's pointer or size changes)
+  int32_t* class_mix_kept = nullptr;  // the weight classes of the map the bitmap was made from (device)
+  const int32_t* bits_map = nullptr;  // that map, its size; `bits_stale`: it must be made again
+  int64_t bits_nodes = -1;
+  bool bits_stale = true;
   int32_t* fifo_rank = nullptr;   // FIFO update: per id, rank among its tile's misses (grown on demand)
   int64_t fifo_rank_cap = 0;
   int32_t* fifo_tiles = nullptr;  // FIFO update: tile sums, then tile offsets
@@ -308,6 +312,7 @@ int reserve_cached_bits(a3_ctx* ctx, int64_t num_nodes) {
   A3_HIP(ctx, hipMalloc(&q, (size_t)words * sizeof(uint64_t)));
   ctx->cached_bits = (uint64_t*)q;
   ctx->cached_bits_words = words;
+  ctx->bits_stale = true;
   return A3_OK;
 }
 
@@ -320,7 +325,7 @@ int build_cached_bits(a3_ctx* ctx, const int32_t* cache_map, int64_t num_nodes) 
   hipLaunchKernelGGL(a3::k_cached_bits, dim3(blocks), dim3(a3::kTileThreads), 0, ctx->stream, cache_map,
                      num_nodes, ctx->cached_bits, ctx->block_seen);
   hipLaunchKernelGGL(a3::k_class_mix, dim3(1), dim3(a3::kTileThreads), 0, ctx->stream, ctx->block_seen,
-                     (int)blocks, ctx->d_state);
+                     (int)blocks, ctx->d_state, ctx->class_mix_kept);
   A3_HIP(ctx, hipGetLastError());
   return A3_OK;
 }
@@ -360,9 +365,19 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
   if (rc != A3_OK) return rc;
 
   prof_mark(ctx, 0, 0);
+  // A3_STATIC_MAP: the bitmap of cached nodes and the map's weight classes are kept while the
+  // caller passes the same map (its contents do not change, by the flag's contract)
+  bool bits_kept = false;
   if (weighted) {
-    rc = build_cached_bits(ctx, cache_map, num_nodes);
-    if (rc != A3_OK) return rc;
+    bits_kept = (ctx->flags & A3_STATIC_MAP) && !ctx->bits_stale && ctx->bits_map == cache_map &&
+                ctx->bits_nodes == num_nodes;
+    if (!bits_kept) {
+      rc = build_cached_bits(ctx, cache_map, num_nodes);
+      if (rc != A3_OK) return rc;
+      ctx->bits_map = cache_map;
+      ctx->bits_nodes = num_nodes;
+      ctx->bits_stale = false;
+    }
   }
   if (validate) {
     hipLaunchKernelGGL(a3::k_init_seeds_checked<IdxT>, dim3(blocks_for(num_seeds, 256)), dim3(256),
@@ -383,6 +398,7 @@ int sample_enqueue(a3_ctx* ctx, const int64_t* indptr, const IdxT* indices, int6
     fa.from_seeds = (h == 0 && !validate) ? 1 : 0;
     fa.num_seeds = num_seeds;
     fa.cache_map = cache_map;
+    fa.class_mix_kept = (h == 0 && bits_kept) ? ctx->class_mix_kept : nullptr;
     fa.S_slot = ctx->S_slot;
     fa.S = S;
     fa.node_map = ctx->node_map;
@@ -939,6 +955,7 @@ extern "C" int a3_create(a3_ctx** out, int hip_device, void* hip_stream, int64_t
   for (int b = 0; b < a3::kNumBins; ++b) chk(dev_alloc(ctx, &ctx->bins[b], ctx->cap_dst[max_hops - 1]));
   chk(dev_alloc(ctx, &ctx->d_state, 1));
   chk(dev_alloc(ctx, &ctx->block_seen, kCachedBitsBlocks));
+  chk(dev_alloc(ctx, &ctx->class_mix_kept, 1));
   if (rc == A3_OK) {
     static_assert(sizeof(DevState) % sizeof(int32_t) == 0, "DevState is a block of int32");
     hipLaunchKernelGGL(a3::k_fill_i32, dim3(1), dim3(256), 0, ctx->stream, (int32_t*)ctx->d_state,
@@ -1106,6 +1123,12 @@ extern "C" int a3_sample_gather_begin(a3_ctx* ctx, const int64_t* indptr, const 
                               cache_map, bias_q16, rng_seed);
   ctx->ahead = nullptr;
   return rc;
+}
+
+extern "C" int a3_device_map_changed(a3_ctx* ctx) {
+  if (!ctx) return fail(nullptr, A3_ERR_INVALID_ARG, "a3_device_map_changed: ctx is null");
+  ctx->bits_stale = true;
+  return A3_OK;
 }
 
 extern "C" int a3_reserve(a3_ctx* ctx, int64_t num_nodes) {
@@ -1524,6 +1547,7 @@ int fifo_enqueue(a3_ctx* ctx, int32_t* cache_map, int64_t num_nodes, int32_t* sl
                  int64_t n_slots, void* feat_dev, int64_t row_bytes, const void* ids, int32_t idx_bytes,
                  int64_t n_ids, const int32_t* n_dev, const void* rows, int32_t* rank, int32_t* tile_sums,
                  int32_t* tile_offs) {
+  ctx->bits_stale = true;  // the update rewrites map entries: a kept bitmap of cached nodes is out of date
   const int64_t n_tiles = (n_ids + a3::kTile - 1) / a3::kTile;
   if (idx_bytes == 4)
     hipLaunchKernelGGL(a3::k_fifo_flag<int32_t>, dim3((unsigned)n_tiles), dim3(a3::kTileThreads), 0, ctx->stream,

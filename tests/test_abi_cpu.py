@@ -270,4 +270,6 @@ def test_validate_argument_errors(L):
     assert L.a3_reserve(h, -1) == a3.A3_ERR_INVALID_ARG
     assert L.a3_reserve(h, 10) == a3.A3_ERR_HIP                                   # valid, but no device
     assert L.a3_pipeline_reserve(None, 10) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_device_map_changed(None) == a3.A3_ERR_INVALID_ARG
+    assert L.a3_device_map_changed(h) == a3.A3_OK
     assert L.a3_destroy(h) == a3.A3_OK

@@ -442,6 +442,49 @@ def test_one_unit_with_a_bad_seed_retrieves_nothing_and_recovers():
     ctx.close()
 
 
+def test_static_map_contexts_keep_what_they_derived_from_the_map():
+    """A3_STATIC_MAP: the bitmap of cached nodes and the weight classes are made when the map's
+    pointer changes, not at every call; calls on one map, on another, without weights in between,
+    after a FIFO update through the context (which rewrites the map in place), all equal the oracle"""
+    w, g, d_ip, d_ix = _graph("mini_copurchase")
+    maps = [degree_ranked_cache(g, None, f).cache_map for f in (0.2, 0.6, 1.0)]
+    d_maps = [m.to(DEV) for m in maps]
+    ctx = a3.Context(128, [15, 10, 5], flags=a3.A3_STATIC_MAP)
+
+    def call(k, b, gamma=4.0, fan=(15, 10, 5)):
+        seeds = seed_batch(w.num_nodes, 128 - b, 6, b)
+        got = ctx.sample_blocks(d_ip, d_ix, torch.from_numpy(seeds).to(DEV), list(fan), d_maps[k], int(gamma * Q), b)
+        want = oracle.sample_blocks(g.indptr.numpy(), g.indices.numpy(), seeds, list(fan), d_maps[k].cpu().numpy(),
+                                    int(gamma * Q), b)
+        blocks_equal(got.to_host(), want)
+        return ctx.sample_stats()["weight_classes"]
+
+    assert [call(0, b) for b in range(3)] == [3, 3, 3]        # made once, kept twice
+    assert call(1, 3) == 3 and call(1, 4, fan=(3, 2)) == 3     # another map
+    assert call(2, 5) == 1                                      # everything cached: one class
+    assert call(0, 6, gamma=1.0) == 0                           # no weights in between
+    assert call(0, 7) == 3
+    # the map rewritten in place by this context's FIFO update: noticed without a new pointer
+    N, n_slots = w.num_nodes, 500
+    cm = (-torch.arange(N, dtype=torch.int32) - 1).to(DEV)
+    d_maps.append(cm)
+    owner = torch.full((n_slots,), -1, dtype=torch.int32, device=DEV)
+    state = torch.zeros(4, dtype=torch.int32, device=DEV)
+    cache = torch.zeros((n_slots, 4), dtype=torch.float32, device=DEV)
+    rows = torch.zeros((N, 4), dtype=torch.float32, device=DEV)
+    classes = []
+    for b in range(8, 11):
+        classes.append(call(3, b))
+        ctx.cache_fifo_update(cm, owner, state, cache, rows)
+        torch.cuda.synchronize()
+    assert classes == [2, 3, 3]                                 # empty cache first, then both classes
+    # the caller rewrites a map in place: announced
+    d_maps[0].copy_(d_maps[2])
+    ctx.device_map_changed()
+    assert call(0, 11) == 1
+    ctx.close()
+
+
 def test_isolated_nodes_and_no_eids():
     indptr = torch.tensor([0, 0, 1, 2, 2], dtype=torch.int64)
     indices = torch.tensor([2, 1], dtype=torch.int64)
